@@ -1,0 +1,193 @@
+/*
+ * randline.h -- C ABI of the MI355X (gfx950) random cache-line read benchmark.
+ *
+ * The library implements the benchmark of the paper "Enabling full-speed random
+ * access to the entire memory on the A100 GPU" (Sec. 1.3, Sec. 2.1-2.4) for
+ * CDNA4: every wavefront reads random, aligned, coalesced lines anywhere in a
+ * device-memory region; optionally all waves of one group of compute units
+ * (CUs) are restricted to that group's window of the region; a pinned variant
+ * runs the same access stream on a chosen set of CUs only.
+ *
+ * The paper measures time only.  To make the reads checkable, the region holds
+ * a known fill and every call returns a checksum:
+ *
+ *   mix64(z)    SplitMix64 output function (Steele, Lea, Flood 2014)
+ *   sm(s,k)     = mix64(s + (k+1)*0x9E3779B97F4A7C15): k-th output of SplitMix64 seeded s
+ *   fill        region as little-endian uint64[R/8]: u64[j] = sm(fill_seed, j)
+ *   draw        logical wave w, iteration it: h = sm(sm(read_seed, w), it)
+ *   line index  window_of_group[w mod G] * L_win + (h mod L_win),  L_win = (R/B)/n_windows
+ *   checksum    sum modulo 2^64 of every 32-bit word (zero extended) of every line read
+ *
+ * A "logical wave" is the unit that reads one line per iteration: 32 lanes (the
+ * paper's warp, Sec. 1.3; two of them share one 64-lane hardware wavefront) or
+ * all 64 lanes.  The checksum depends only on the arguments below, never on
+ * launch geometry or on where the hardware places workgroups.
+ *
+ * Conventions
+ *   - "device" pointers are HIP device addresses; "host" pointers are ordinary
+ *     process memory.  The library never frees or keeps caller memory.
+ *   - hip_stream is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls enqueue on that stream and return after the work has finished.
+ *   - Every call returns RR_OK (0) or a negative code; on failure `out`
+ *     arguments are left untouched.  rr_last_error() gives a message for the
+ *     calling thread's last failure.  All RR_EINVAL checks that do not need the
+ *     device are made before the first HIP call.
+ *   - The library keeps a few KB of device scratch per GPU (checksum cell,
+ *     ticket counters, timestamps, lookup tables), created on first use and
+ *     released by rr_shutdown().  Calls that overlap on one GPU are not supported.
+ */
+#ifndef RANDLINE_H
+#define RANDLINE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define RR_OK 0
+#define RR_EINVAL (-1) /* bad argument */
+#define RR_EHIP (-2)   /* a HIP runtime call failed */
+#define RR_EPLACE (-3) /* some group / target CU never received a resident wave */
+
+#define RR_CU_EXCLUDED 0xFFFFu /* group_of_cu entry: waves landing on this CU do no work */
+#define RR_MAX_GROUPS 1024u
+#define RR_MAX_CUS 1024u
+
+/* Hardware coordinates of one compute unit: XCC_ID and the SE / SH / CU fields of HW_ID. */
+typedef struct {
+    uint32_t xcc, se, sh, cu;
+} rr_cu_t;
+
+/*
+ * Window map (paper Sec. 2.1: one random half per SM; Sec. 2.4: one half per
+ * resource group).  The region's n_lines = region_bytes/line_bytes lines are cut
+ * into n_windows equal contiguous windows.  CU c (dense id, see
+ * rr_enumerate_cus) belongs to group group_of_cu[c]; logical wave w belongs to
+ * group w mod n_groups, is executed only by waves resident on a CU of that
+ * group, and reads only from window window_of_group[w mod n_groups].
+ * Both arrays are host memory, read during the call.
+ */
+typedef struct {
+    uint32_t n_groups;               /* G >= 1, <= RR_MAX_GROUPS; W must be a multiple of G   */
+    uint32_t n_windows;              /* >= 1; must divide n_lines                              */
+    uint32_t n_cus;                  /* length of group_of_cu; must equal the device CU count  */
+    const uint16_t *group_of_cu;     /* [n_cus] values < G, or RR_CU_EXCLUDED                  */
+    const uint16_t *window_of_group; /* [G] values < n_windows                                 */
+} rr_window_map_t;
+
+typedef struct {
+    uint64_t checksum;       /* see top of file                                             */
+    double kernel_ms_event;  /* HIP-event time around the read kernel launch(es)            */
+    double kernel_ms_device; /* in-kernel constant-clock time, first working wave's start to
+                                last working wave's end (excludes draining idle workgroups) */
+    uint32_t waves_run;      /* hardware wavefronts that executed at least one logical wave */
+    uint32_t launches;       /* kernel launches needed (1 unless placement forced a retry)  */
+} rr_result_t;
+
+/* How the line index reaches the lanes of a logical wave (all give identical results). */
+#define RR_BCAST_DEFAULT 0
+#define RR_BCAST_LDS 1      /* ds_bpermute through the LDS crossbar                   */
+#define RR_BCAST_DPP 2      /* DPP row broadcast, 16 iterations generated per batch   */
+#define RR_BCAST_READLANE 3 /* v_readlane to scalar registers (+ select per half)     */
+
+#define RR_MODE_AUTO 0
+#define RR_MODE_FLAT 1   /* one hardware wave per 64 lanes of logical waves, fixed by block index */
+#define RR_MODE_TICKET 2 /* resident waves claim logical waves of their CU's group from counters  */
+
+/*
+ * Optional launch controls.  NULL or a zeroed struct = defaults.  None of them
+ * changes the checksum.  Values the library does not implement give RR_EINVAL.
+ */
+typedef struct {
+    uint32_t block_threads;  /* 64, 128 or 256 (default 256)                                      */
+    uint32_t grid_blocks;    /* ticket mode: workgroups per launch (default: 2 x resident capacity;
+                                pinned runs: 64 x).  Flat mode ignores it.                        */
+    uint32_t unroll;         /* loads kept in flight per wave: 2, 4, 8 or 16 (default by line width) */
+    uint32_t mode;           /* RR_MODE_*                                                          */
+    uint32_t bcast;          /* RR_BCAST_*                                                         */
+    uint32_t nontemporal;    /* 1: loads carry the non-temporal hint                               */
+    uint64_t first_wave;     /* id of the first logical wave (default 0); multiple of n_groups     */
+    uint16_t *placement_out; /* host [W] or NULL: dense CU id that executed each logical wave      */
+    uint32_t *cu_waves_out;  /* host [n_cus] or NULL: working hardware waves counted per CU        */
+} rr_launch_opts_t;
+
+/*
+ * List the device's compute units.  A kernel records, for every CU on which a
+ * workgroup ran, the tuple (XCC_ID, HW_ID.SE_ID, HW_ID.SH_ID, HW_ID.CU_ID); the
+ * dense id of a CU is its rank in the sorted order of those tuples.  This is
+ * the CDNA4 counterpart of reading %smid (paper Sec. 1.1).  Writes up to `cap`
+ * entries to out (host, may be NULL if cap == 0) and the total count to *n_cus.
+ */
+int rr_enumerate_cus(rr_cu_t *out, uint32_t cap, uint32_t *n_cus, void *hip_stream);
+
+/*
+ * Fill `region` (device, 16-byte aligned, region_bytes a multiple of 16) with
+ * the SplitMix64 stream of fill_seed.  Not part of the paper's benchmark (the
+ * content of the region is irrelevant to its timing); needed for the checksum.
+ */
+int rr_fill(void *region, uint64_t region_bytes, uint64_t fill_seed, void *hip_stream);
+
+/*
+ * The benchmark (paper Sec. 2.1; with a window map also Sec. 2.4).
+ *   region          device pointer, aligned to line_bytes, holding region_bytes bytes
+ *   region_bytes    > 0, multiple of line_bytes; region_bytes/line_bytes <= 2^32
+ *   line_bytes      128, 256 or 512
+ *   lanes_per_line  32 or 64; line_bytes/lanes_per_line must be 4, 8 or 16 bytes
+ *   n_reads         total lines read = W * iters_per_wave (W = logical waves); 0 is allowed
+ *   iters_per_wave  I >= 1; n_reads must be a multiple of it
+ *   wm              NULL = no windows (G = 1, one window)
+ *   read_seed       seed of the draw stream
+ *   opts            NULL = defaults
+ *   out             host; filled on success
+ * Throughput in the paper's sense is n_reads * line_bytes / kernel time.
+ */
+int rr_rand_read(const void *region, uint64_t region_bytes, uint32_t line_bytes,
+                 uint32_t lanes_per_line, uint64_t n_reads, uint32_t iters_per_wave,
+                 const rr_window_map_t *wm, uint64_t read_seed, void *hip_stream,
+                 const rr_launch_opts_t *opts, rr_result_t *out);
+
+/*
+ * The paper's two-SM probe (Sec. 2.2): the same access stream (G = 1, no
+ * windows, 128-byte lines of 32 lanes x 4 bytes) executed only by waves resident
+ * on CUs cu_a and cu_b (dense ids, different, < CU count).  An oversubscribed
+ * grid is launched; workgroups that land elsewhere exit at once, the others
+ * claim logical waves until none are left.  The checksum does not depend on
+ * the pair.  rr_probe_cus is the same for an arbitrary non-empty set of CUs
+ * (one CU alone; a whole group, Sec. 2.3).
+ */
+int rr_probe_pair(const void *region, uint64_t region_bytes, uint32_t cu_a, uint32_t cu_b,
+                  uint64_t n_reads, uint32_t iters_per_wave, uint64_t read_seed, void *hip_stream,
+                  const rr_launch_opts_t *opts, rr_result_t *out);
+int rr_probe_cus(const void *region, uint64_t region_bytes, const uint32_t *cus, uint32_t n_target,
+                 uint64_t n_reads, uint32_t iters_per_wave, uint64_t read_seed, void *hip_stream,
+                 const rr_launch_opts_t *opts, rr_result_t *out);
+
+/*
+ * Groups of CUs from the pair heatmap (paper Sec. 2.2, Fig. 2 -> Fig. 3; the
+ * paper gives no algorithm).  T is a host n x n row-major symmetric matrix of
+ * pair throughputs (diagonal ignored); singles is NULL or host [n] single-CU
+ * throughputs.  Ratio r_ab = T[a][b]/(singles[a]+singles[b]), or T[a][b]/max T
+ * without singles; the ratios are sorted, the largest gap between neighbours
+ * splits "interfering" from "independent" pairs unless it is below
+ * min_gap * median ratio (then every CU is its own group); groups are the
+ * connected components of the interfering pairs, numbered by smallest member.
+ * Outputs (host): group_out[n], order_out[n] = CUs sorted by (group, id),
+ * *n_groups_out, *threshold_out (NaN when no structure was found).
+ */
+int rr_groups_from_heatmap(const double *T, uint32_t n, const double *singles, double min_gap,
+                           uint16_t *group_out, uint32_t *order_out, uint32_t *n_groups_out,
+                           double *threshold_out);
+
+/* Release the per-GPU scratch and cached CU tables.  Safe to call when nothing was created. */
+int rr_shutdown(void);
+
+/* Static description of a return code; never NULL. */
+const char *rr_strerror(int code);
+/* Message of the calling thread's most recent failure ("" if none). */
+const char *rr_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RANDLINE_H */

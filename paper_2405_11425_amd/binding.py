@@ -1,0 +1,249 @@
+"""ctypes binding of librandline.so -- same names as the C ABI (include/randline.h).
+
+Argument marshalling only: every step of the benchmark runs in the HIP library.
+PyTorch is used by callers for device memory and streams; this module accepts a
+torch tensor (its data_ptr/nbytes are taken) or a raw (pointer, bytes) pair.
+There is no CPU fallback: if the library is missing, importing fails loudly.
+"""
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional, Sequence, Tuple
+
+import numpy as np
+
+from . import build as _build
+
+RR_OK, RR_EINVAL, RR_EHIP, RR_EPLACE = 0, -1, -2, -3
+RR_CU_EXCLUDED = 0xFFFF
+BCAST_DEFAULT, BCAST_LDS, BCAST_DPP, BCAST_READLANE = 0, 1, 2, 3
+MODE_AUTO, MODE_FLAT, MODE_TICKET = 0, 1, 2
+
+
+class RandlineError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__(f"randline error {code}: {message}")
+        self.code = code
+
+
+class _CU(C.Structure):
+    _fields_ = [("xcc", C.c_uint32), ("se", C.c_uint32), ("sh", C.c_uint32), ("cu", C.c_uint32)]
+
+
+class _WindowMap(C.Structure):
+    _fields_ = [("n_groups", C.c_uint32), ("n_windows", C.c_uint32), ("n_cus", C.c_uint32),
+                ("group_of_cu", C.POINTER(C.c_uint16)), ("window_of_group", C.POINTER(C.c_uint16))]
+
+
+class _Result(C.Structure):
+    _fields_ = [("checksum", C.c_uint64), ("kernel_ms_event", C.c_double),
+                ("kernel_ms_device", C.c_double), ("waves_run", C.c_uint32), ("launches", C.c_uint32)]
+
+
+class _Opts(C.Structure):
+    _fields_ = [("block_threads", C.c_uint32), ("grid_blocks", C.c_uint32), ("unroll", C.c_uint32),
+                ("mode", C.c_uint32), ("bcast", C.c_uint32), ("nontemporal", C.c_uint32),
+                ("first_wave", C.c_uint64), ("placement_out", C.POINTER(C.c_uint16)),
+                ("cu_waves_out", C.POINTER(C.c_uint32))]
+
+
+EXPORTS = ["rr_enumerate_cus", "rr_fill", "rr_rand_read", "rr_probe_pair", "rr_probe_cus",
+           "rr_groups_from_heatmap", "rr_shutdown", "rr_strerror", "rr_last_error"]
+
+_lib = None
+
+
+def library_path() -> str:
+    return _build.LIB
+
+
+def lib():
+    """Load the built library (build it only if nothing is built yet)."""
+    global _lib
+    if _lib is None:
+        path = library_path()
+        if not os.path.exists(path):
+            _build.build()
+        L = C.CDLL(path)
+        u64, u32, vp = C.c_uint64, C.c_uint32, C.c_void_p
+        L.rr_enumerate_cus.restype = C.c_int
+        L.rr_enumerate_cus.argtypes = [C.POINTER(_CU), u32, C.POINTER(u32), vp]
+        L.rr_fill.restype = C.c_int
+        L.rr_fill.argtypes = [vp, u64, u64, vp]
+        L.rr_rand_read.restype = C.c_int
+        L.rr_rand_read.argtypes = [vp, u64, u32, u32, u64, u32, C.POINTER(_WindowMap), u64, vp,
+                                   C.POINTER(_Opts), C.POINTER(_Result)]
+        L.rr_probe_pair.restype = C.c_int
+        L.rr_probe_pair.argtypes = [vp, u64, u32, u32, u64, u32, u64, vp, C.POINTER(_Opts), C.POINTER(_Result)]
+        L.rr_probe_cus.restype = C.c_int
+        L.rr_probe_cus.argtypes = [vp, u64, C.POINTER(u32), u32, u64, u32, u64, vp, C.POINTER(_Opts),
+                                   C.POINTER(_Result)]
+        L.rr_groups_from_heatmap.restype = C.c_int
+        L.rr_groups_from_heatmap.argtypes = [C.POINTER(C.c_double), u32, C.POINTER(C.c_double), C.c_double,
+                                             C.POINTER(C.c_uint16), C.POINTER(u32), C.POINTER(u32),
+                                             C.POINTER(C.c_double)]
+        L.rr_shutdown.restype = C.c_int
+        L.rr_shutdown.argtypes = []
+        L.rr_strerror.restype = C.c_char_p
+        L.rr_strerror.argtypes = [C.c_int]
+        L.rr_last_error.restype = C.c_char_p
+        L.rr_last_error.argtypes = []
+        _lib = L
+    return _lib
+
+
+def _check(rc: int):
+    if rc != RR_OK:
+        msg = lib().rr_last_error().decode() or lib().rr_strerror(rc).decode()
+        raise RandlineError(rc, msg)
+
+
+def _region(region, region_bytes: Optional[int]) -> Tuple[int, int]:
+    """(device pointer, bytes) of a torch tensor, or of an explicit (ptr, bytes) pair."""
+    if hasattr(region, "data_ptr"):
+        nbytes = region.numel() * region.element_size()
+        return int(region.data_ptr()), int(nbytes if region_bytes is None else region_bytes)
+    if isinstance(region, tuple):
+        return int(region[0]), int(region[1])
+    if region_bytes is None:
+        raise ValueError("region_bytes is required with a raw pointer")
+    return int(region), int(region_bytes)
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        try:
+            import torch
+            if torch.cuda.is_available():
+                return int(torch.cuda.current_stream().cuda_stream) or None
+        except ImportError:
+            pass
+        return None
+    if hasattr(stream, "cuda_stream"):
+        return int(stream.cuda_stream) or None
+    return int(stream) or None
+
+
+@dataclass
+class WindowMap:
+    """Host-side window map: CU -> group -> window (see rr_window_map_t)."""
+    n_windows: int
+    group_of_cu: np.ndarray       # uint16 [n_cus]; RR_CU_EXCLUDED keeps a CU out
+    window_of_group: np.ndarray   # uint16 [G]
+
+    def __post_init__(self):
+        self.group_of_cu = np.ascontiguousarray(self.group_of_cu, dtype=np.uint16)
+        self.window_of_group = np.ascontiguousarray(self.window_of_group, dtype=np.uint16)
+
+    @property
+    def n_groups(self) -> int:
+        return int(self.window_of_group.size)
+
+    def _c(self) -> _WindowMap:
+        return _WindowMap(self.n_groups, self.n_windows, int(self.group_of_cu.size),
+                          self.group_of_cu.ctypes.data_as(C.POINTER(C.c_uint16)),
+                          self.window_of_group.ctypes.data_as(C.POINTER(C.c_uint16)))
+
+
+@dataclass
+class ReadResult:
+    checksum: int
+    kernel_ms_event: float
+    kernel_ms_device: float
+    waves_run: int
+    launches: int
+    placement: Optional[np.ndarray] = None   # dense CU id per logical wave, if requested
+    cu_waves: Optional[np.ndarray] = None    # working hardware waves per CU, if requested
+
+
+def _opts(W: int, n_cus_hint: int, block_threads=0, grid_blocks=0, unroll=0, mode=0, bcast=0,
+          nontemporal=0, first_wave=0, want_placement=False, want_cu_waves=False):
+    o = _Opts(block_threads, grid_blocks, unroll, mode, bcast, nontemporal, first_wave, None, None)
+    placement = cu_waves = None
+    if want_placement:
+        placement = np.full(max(W, 1), 0xFFFF, dtype=np.uint16)
+        o.placement_out = placement.ctypes.data_as(C.POINTER(C.c_uint16))
+    if want_cu_waves:
+        cu_waves = np.zeros(n_cus_hint, dtype=np.uint32)
+        o.cu_waves_out = cu_waves.ctypes.data_as(C.POINTER(C.c_uint32))
+    return o, placement, cu_waves
+
+
+def enumerate_cus(stream=None) -> np.ndarray:
+    """Array [n_cus, 4] of (xcc, se, sh, cu); row index = dense CU id."""
+    n = C.c_uint32(0)
+    buf = (_CU * 1024)()
+    _check(lib().rr_enumerate_cus(buf, 1024, C.byref(n), _stream(stream)))
+    return np.array([[buf[i].xcc, buf[i].se, buf[i].sh, buf[i].cu] for i in range(n.value)], dtype=np.uint32)
+
+
+def fill(region, fill_seed: int, region_bytes: Optional[int] = None, stream=None) -> None:
+    ptr, nbytes = _region(region, region_bytes)
+    _check(lib().rr_fill(ptr, nbytes, fill_seed, _stream(stream)))
+
+
+def rand_read(region, line_bytes: int, n_reads: int, iters_per_wave: int, read_seed: int,
+              window_map: Optional[WindowMap] = None, lanes_per_line: int = 32,
+              region_bytes: Optional[int] = None, stream=None, want_placement: bool = False,
+              want_cu_waves: bool = False, **launch) -> ReadResult:
+    ptr, nbytes = _region(region, region_bytes)
+    W = n_reads // iters_per_wave if iters_per_wave else 0
+    o, placement, cu_waves = _opts(W, 1024, want_placement=want_placement, want_cu_waves=want_cu_waves, **launch)
+    res = _Result()
+    wm = window_map._c() if window_map is not None else None
+    _check(lib().rr_rand_read(ptr, nbytes, line_bytes, lanes_per_line, n_reads, iters_per_wave,
+                              C.byref(wm) if wm is not None else None, read_seed, _stream(stream),
+                              C.byref(o), C.byref(res)))
+    return ReadResult(int(res.checksum), res.kernel_ms_event, res.kernel_ms_device, int(res.waves_run),
+                      int(res.launches), placement[:W] if placement is not None else None, cu_waves)
+
+
+def probe_cus(region, cus: Sequence[int], n_reads: int, iters_per_wave: int, read_seed: int,
+              region_bytes: Optional[int] = None, stream=None, want_placement: bool = False,
+              want_cu_waves: bool = False, **launch) -> ReadResult:
+    ptr, nbytes = _region(region, region_bytes)
+    W = n_reads // iters_per_wave if iters_per_wave else 0
+    o, placement, cu_waves = _opts(W, 1024, want_placement=want_placement, want_cu_waves=want_cu_waves, **launch)
+    res = _Result()
+    arr = (C.c_uint32 * max(len(cus), 1))(*[int(c) for c in cus])
+    _check(lib().rr_probe_cus(ptr, nbytes, arr, len(cus), n_reads, iters_per_wave, read_seed, _stream(stream),
+                              C.byref(o), C.byref(res)))
+    return ReadResult(int(res.checksum), res.kernel_ms_event, res.kernel_ms_device, int(res.waves_run),
+                      int(res.launches), placement[:W] if placement is not None else None, cu_waves)
+
+
+def probe_pair(region, cu_a: int, cu_b: int, n_reads: int, iters_per_wave: int, read_seed: int,
+               region_bytes: Optional[int] = None, stream=None, **launch) -> ReadResult:
+    ptr, nbytes = _region(region, region_bytes)
+    o, _, _ = _opts(0, 1024, **launch)
+    res = _Result()
+    _check(lib().rr_probe_pair(ptr, nbytes, cu_a, cu_b, n_reads, iters_per_wave, read_seed, _stream(stream),
+                               C.byref(o), C.byref(res)))
+    return ReadResult(int(res.checksum), res.kernel_ms_event, res.kernel_ms_device, int(res.waves_run),
+                      int(res.launches))
+
+
+def groups_from_heatmap(T: np.ndarray, singles: Optional[np.ndarray] = None, min_gap: float = 0.05):
+    """(group_of_cu[n], order[n], threshold) from an n x n pair-throughput matrix."""
+    T = np.ascontiguousarray(T, dtype=np.float64)
+    n = T.shape[0]
+    if T.shape != (n, n):
+        raise ValueError("T must be square")
+    s_ptr = None
+    if singles is not None:
+        singles = np.ascontiguousarray(singles, dtype=np.float64)
+        s_ptr = singles.ctypes.data_as(C.POINTER(C.c_double))
+    group = np.zeros(n, dtype=np.uint16)
+    order = np.zeros(n, dtype=np.uint32)
+    ng = C.c_uint32(0)
+    thr = C.c_double(0.0)
+    rc = lib().rr_groups_from_heatmap(T.ctypes.data_as(C.POINTER(C.c_double)), n, s_ptr, min_gap,
+                                      group.ctypes.data_as(C.POINTER(C.c_uint16)),
+                                      order.ctypes.data_as(C.POINTER(C.c_uint32)), C.byref(ng), C.byref(thr))
+    if rc != RR_OK:
+        raise RandlineError(rc, lib().rr_strerror(rc).decode())
+    return group, order, float(thr.value)
+
+
+def shutdown() -> None:
+    _check(lib().rr_shutdown())

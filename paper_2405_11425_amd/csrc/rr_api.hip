@@ -1,0 +1,527 @@
+// Host side of the C ABI declared in include/randline.h, plus the small
+// kernels (fill, CU enumeration, scratch reset).  The read kernel itself is in
+// rr_read_kernel.hpp and is instantiated in the rr_inst_*.hip files.
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <mutex>
+#include <string>
+#include <vector>
+
+#include "../../include/randline.h"
+#include "rr_read_kernel.hpp"
+
+namespace rr {
+
+// ------------------------------------------------------------------ small kernels
+
+// Region as uint64[]: element j = mix64(seed + (j+1)*gamma).  Each thread writes
+// 16 bytes per step (two consecutive elements), grid-stride.
+typedef u64 u64x2 __attribute__((ext_vector_type(2)));
+__global__ void __launch_bounds__(256) fill_kernel(u64x2 *out, u64 n_pairs, u64 seed) {
+    const u64 stride = (u64)gridDim.x * blockDim.x;
+    u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x;
+    u64 ctr = seed + (2 * i + 1) * kGamma;  // state of element 2i
+    const u64 ctr_step = 2 * stride * kGamma;
+    for (; i < n_pairs; i += stride) {
+        u64x2 v;
+        v.x = mix64(ctr);
+        v.y = mix64(ctr + kGamma);
+        __builtin_nontemporal_store(v, &out[i]);  // one 16-byte store per lane
+        ctr += ctr_step;
+    }
+}
+
+// Marks the key of the CU each workgroup runs on; a short sleep keeps the
+// workgroup resident so that the dispatcher has to use the other CUs too.
+__global__ void __launch_bounds__(64) enumerate_kernel(Scratch *s, u32 naps) {
+    if (threadIdx.x == 0) s->key_seen[cu_key()] = 1u;
+    for (u32 i = 0; i < naps; ++i) __builtin_amdgcn_s_sleep(100);
+}
+
+// what: bit 0 head (checksum, timestamps, wave count); bit 1 tickets; bit 2 per-CU counts; bit 3 key marks
+__global__ void __launch_bounds__(256) reset_kernel(Scratch *s, u32 what) {
+    const u32 t = threadIdx.x;
+    if ((what & 1u) && t == 0) {
+        s->checksum = 0;
+        s->t_min = ~0ull;
+        s->t_max = 0;
+        s->waves_run = 0;
+        s->pad = 0;
+    }
+    if (what & 2u)
+        for (u32 i = t; i < kMaxGroups; i += blockDim.x) s->tickets[i] = 0;
+    if (what & 4u)
+        for (u32 i = t; i < kMaxCus; i += blockDim.x) s->cu_waves[i] = 0;
+    if (what & 8u)
+        for (u32 i = t; i < kNumKeys; i += blockDim.x) s->key_seen[i] = 0;
+}
+
+}  // namespace rr
+
+using namespace rr;
+
+// ------------------------------------------------------------------ errors
+
+static thread_local std::string g_last_error;
+
+static int fail(int code, const char *fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    g_last_error = buf;
+    return code;
+}
+
+#define HIP_TRY(expr)                                                                          \
+    do {                                                                                       \
+        hipError_t e_ = (expr);                                                                \
+        if (e_ != hipSuccess)                                                                  \
+            return fail(RR_EHIP, "%s failed: %s (%s:%d)", #expr, hipGetErrorString(e_), __FILE__, \
+                        __LINE__);                                                             \
+    } while (0)
+
+extern "C" const char *rr_strerror(int code) {
+    switch (code) {
+        case RR_OK: return "success";
+        case RR_EINVAL: return "invalid argument";
+        case RR_EHIP: return "HIP runtime error";
+        case RR_EPLACE: return "a group or target compute unit received no resident wave";
+        default: return "unknown error code";
+    }
+}
+
+extern "C" const char *rr_last_error(void) { return g_last_error.c_str(); }
+
+// ------------------------------------------------------------------ per-device state
+
+namespace {
+
+struct HostHead {  // mirror of the head of Scratch + tickets, in pinned memory
+    u64 checksum, t_min, t_max;
+    u32 waves_run, pad;
+    u32 tickets[kMaxGroups];
+    u32 cu_waves[kMaxCus];
+};
+
+struct DeviceState {
+    bool ready = false;
+    Scratch *scratch = nullptr;
+    u16 *group_of_key = nullptr;  // [kNumKeys]
+    u16 *dense_of_key = nullptr;  // [kNumKeys]
+    u32 *window_base = nullptr;   // [kMaxGroups]
+    u16 *placement = nullptr;
+    size_t placement_cap = 0;
+    HostHead *head = nullptr;     // pinned
+    hipEvent_t ev0 = nullptr, ev1 = nullptr;
+    int wall_khz = 0;
+    std::vector<rr_cu_t> cus;             // dense id -> coordinates
+    std::vector<u16> dense_of_key_host;   // [kNumKeys], kExcluded if no such CU
+};
+
+constexpr int kMaxDevices = 16;
+DeviceState g_state[kMaxDevices];
+std::mutex g_mutex;
+
+u32 key_of(const rr_cu_t &c) { return (c.xcc << 8) | (c.se << 5) | (c.sh << 4) | c.cu; }
+
+int enumerate(DeviceState &st, hipStream_t stream) {
+    int dev = 0, n_expected = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    HIP_TRY(hipDeviceGetAttribute(&n_expected, hipDeviceAttributeMultiprocessorCount, dev));
+    std::vector<u32> seen(kNumKeys);
+    u32 found = 0;
+    for (int attempt = 0; attempt < 4 && (int)found < n_expected; ++attempt) {
+        hipLaunchKernelGGL(reset_kernel, dim3(1), dim3(256), 0, stream, st.scratch, 8u);
+        HIP_TRY(hipGetLastError());
+        const u32 blocks = (u32)n_expected * 64u << attempt;
+        hipLaunchKernelGGL(enumerate_kernel, dim3(blocks), dim3(64), 0, stream, st.scratch, 4u << attempt);
+        HIP_TRY(hipGetLastError());
+        HIP_TRY(hipMemcpyAsync(seen.data(), st.scratch->key_seen, kNumKeys * sizeof(u32),
+                               hipMemcpyDeviceToHost, stream));
+        HIP_TRY(hipStreamSynchronize(stream));
+        found = 0;
+        for (u32 k = 0; k < kNumKeys; ++k) found += seen[k] ? 1u : 0u;
+    }
+    if (found == 0 || found > kMaxCus)
+        return fail(RR_EPLACE, "CU enumeration found %u compute units (device reports %d)", found, n_expected);
+    if ((int)found != n_expected)
+        return fail(RR_EPLACE, "CU enumeration found %u of %d compute units", found, n_expected);
+    st.cus.clear();
+    st.dense_of_key_host.assign(kNumKeys, kExcluded);
+    for (u32 k = 0; k < kNumKeys; ++k) {  // ascending key == sorted (xcc, se, sh, cu)
+        if (!seen[k]) continue;
+        rr_cu_t c;
+        c.xcc = k >> 8;
+        c.se = (k >> 5) & 7u;
+        c.sh = (k >> 4) & 1u;
+        c.cu = k & 15u;
+        st.dense_of_key_host[k] = (u16)st.cus.size();
+        st.cus.push_back(c);
+    }
+    HIP_TRY(hipMemcpyAsync(st.dense_of_key, st.dense_of_key_host.data(), kNumKeys * sizeof(u16),
+                           hipMemcpyHostToDevice, stream));
+    HIP_TRY(hipStreamSynchronize(stream));
+    return RR_OK;
+}
+
+// Create (once per device) the scratch, tables, events and the CU list.
+int get_state(hipStream_t stream, DeviceState **out) {
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(RR_EHIP, "device index %d not supported", dev);
+    DeviceState &st = g_state[dev];
+    if (!st.ready) {
+        if (!st.scratch) HIP_TRY(hipMalloc((void **)&st.scratch, sizeof(Scratch)));
+        if (!st.group_of_key) HIP_TRY(hipMalloc((void **)&st.group_of_key, kNumKeys * sizeof(u16)));
+        if (!st.dense_of_key) HIP_TRY(hipMalloc((void **)&st.dense_of_key, kNumKeys * sizeof(u16)));
+        if (!st.window_base) HIP_TRY(hipMalloc((void **)&st.window_base, kMaxGroups * sizeof(u32)));
+        if (!st.head) HIP_TRY(hipHostMalloc((void **)&st.head, sizeof(HostHead), hipHostMallocDefault));
+        if (!st.ev0) HIP_TRY(hipEventCreate(&st.ev0));
+        if (!st.ev1) HIP_TRY(hipEventCreate(&st.ev1));
+        HIP_TRY(hipDeviceGetAttribute(&st.wall_khz, hipDeviceAttributeWallClockRate, dev));
+        if (st.wall_khz <= 0) st.wall_khz = 100000;  // s_memrealtime: 100 MHz
+        int rc = enumerate(st, stream);
+        if (rc != RR_OK) return rc;
+        st.ready = true;
+    }
+    *out = &st;
+    return RR_OK;
+}
+
+struct Family {
+    u32 lanes, wdw;
+    kernel_handle (*find)(u32, u32, u32);
+    u32 default_unroll;
+};
+const Family kFamilies[] = {
+    {32, 1, find_read_kernel_32_1, 8}, {32, 2, find_read_kernel_32_2, 8}, {32, 4, find_read_kernel_32_4, 4},
+    {64, 1, find_read_kernel_64_1, 8}, {64, 2, find_read_kernel_64_2, 8},
+};
+
+const Family *find_family(u32 lanes, u32 wdw) {
+    for (const Family &f : kFamilies)
+        if (f.lanes == lanes && f.wdw == wdw) return &f;
+    return nullptr;
+}
+
+// Validated description of one read call.
+struct Plan {
+    u64 n_lines = 0, W = 0, first_wave = 0;
+    u32 log2_line = 0, lanes = 0, wdw = 0, G = 1, n_windows = 1;
+    u32 block = 256, unroll = 0, bcast = RR_BCAST_DPP, nt = 0, mode = RR_MODE_AUTO, grid_blocks = 0;
+    bool pinned = false;
+    const Family *family = nullptr;
+    kernel_handle kernel = nullptr;
+};
+
+// Device-independent checks (everything that can be rejected without HIP).
+int make_plan(const void *region, uint64_t region_bytes, uint32_t line_bytes, uint32_t lanes,
+              uint64_t n_reads, uint32_t iters, const rr_window_map_t *wm,
+              const rr_launch_opts_t *opts, const void *out, Plan &pl) {
+    if (!out) return fail(RR_EINVAL, "out is NULL");
+    if (!region) return fail(RR_EINVAL, "region is NULL");
+    if (line_bytes != 128 && line_bytes != 256 && line_bytes != 512)
+        return fail(RR_EINVAL, "line_bytes must be 128, 256 or 512 (got %u)", line_bytes);
+    if (lanes != 32 && lanes != 64) return fail(RR_EINVAL, "lanes_per_line must be 32 or 64 (got %u)", lanes);
+    const u32 width = line_bytes / lanes;
+    if (width * lanes != line_bytes || (width != 4 && width != 8 && width != 16))
+        return fail(RR_EINVAL, "line_bytes/lanes_per_line must be 4, 8 or 16 bytes (got %u/%u)", line_bytes, lanes);
+    pl.lanes = lanes;
+    pl.wdw = width / 4;
+    pl.family = find_family(pl.lanes, pl.wdw);
+    if (!pl.family) return fail(RR_EINVAL, "%u lanes x %u bytes is not a supported line shape", lanes, width);
+    if (region_bytes == 0 || region_bytes % line_bytes != 0)
+        return fail(RR_EINVAL, "region_bytes must be a positive multiple of line_bytes");
+    if ((uintptr_t)region % line_bytes != 0) return fail(RR_EINVAL, "region is not aligned to line_bytes");
+    pl.n_lines = region_bytes / line_bytes;
+    if (pl.n_lines > (1ull << 32)) return fail(RR_EINVAL, "region has more than 2^32 lines");
+    pl.log2_line = line_bytes == 128 ? 7 : line_bytes == 256 ? 8 : 9;
+    if (iters == 0) return fail(RR_EINVAL, "iters_per_wave must be at least 1");
+    if (n_reads % iters != 0) return fail(RR_EINVAL, "n_reads must be a multiple of iters_per_wave");
+    pl.W = n_reads / iters;
+    if (wm) {
+        if (wm->n_groups == 0 || wm->n_groups > RR_MAX_GROUPS)
+            return fail(RR_EINVAL, "n_groups must be in [1, %u]", RR_MAX_GROUPS);
+        if (wm->n_windows == 0 || pl.n_lines % wm->n_windows != 0)
+            return fail(RR_EINVAL, "n_windows must be positive and divide the number of lines");
+        if (!wm->group_of_cu || !wm->window_of_group) return fail(RR_EINVAL, "window map arrays are NULL");
+        if (wm->n_cus == 0 || wm->n_cus > RR_MAX_CUS) return fail(RR_EINVAL, "window map n_cus out of range");
+        for (u32 c = 0; c < wm->n_cus; ++c)
+            if (wm->group_of_cu[c] != RR_CU_EXCLUDED && wm->group_of_cu[c] >= wm->n_groups)
+                return fail(RR_EINVAL, "group_of_cu[%u] = %u is not below n_groups", c, wm->group_of_cu[c]);
+        for (u32 g = 0; g < wm->n_groups; ++g)
+            if (wm->window_of_group[g] >= wm->n_windows)
+                return fail(RR_EINVAL, "window_of_group[%u] = %u is not below n_windows", g, wm->window_of_group[g]);
+        if (pl.W % wm->n_groups != 0) return fail(RR_EINVAL, "the number of logical waves must be a multiple of n_groups");
+        pl.G = wm->n_groups;
+        pl.n_windows = wm->n_windows;
+    }
+    if (pl.W / pl.G >= (1ull << 31)) return fail(RR_EINVAL, "too many logical waves per group");
+    pl.unroll = pl.family->default_unroll;
+    if (opts) {
+        if (opts->block_threads) {
+            if (opts->block_threads != 64 && opts->block_threads != 128 && opts->block_threads != 256)
+                return fail(RR_EINVAL, "block_threads must be 64, 128 or 256");
+            pl.block = opts->block_threads;
+        }
+        if (opts->unroll) pl.unroll = opts->unroll;
+        if (opts->bcast > RR_BCAST_READLANE) return fail(RR_EINVAL, "unknown bcast value");
+        if (opts->bcast) pl.bcast = opts->bcast;
+        if (opts->nontemporal > 1) return fail(RR_EINVAL, "nontemporal must be 0 or 1");
+        pl.nt = opts->nontemporal;
+        if (opts->mode > RR_MODE_TICKET) return fail(RR_EINVAL, "unknown mode value");
+        pl.mode = opts->mode;
+        pl.grid_blocks = opts->grid_blocks;
+        if (opts->first_wave % pl.G != 0) return fail(RR_EINVAL, "first_wave must be a multiple of n_groups");
+        pl.first_wave = opts->first_wave;
+    }
+    pl.kernel = pl.family->find(pl.unroll, pl.bcast, pl.nt);
+    if (!pl.kernel) return fail(RR_EINVAL, "unroll %u is not built for this line shape", pl.unroll);
+    bool needs_tickets = false;
+    if (wm) {
+        if (wm->n_groups > 1) needs_tickets = true;
+        for (u32 c = 0; c < wm->n_cus; ++c)
+            if (wm->group_of_cu[c] == RR_CU_EXCLUDED) needs_tickets = true;
+    }
+    if (pl.mode == RR_MODE_FLAT && needs_tickets)
+        return fail(RR_EINVAL, "flat mode cannot honour a window map with several groups or excluded CUs");
+    if (pl.mode == RR_MODE_AUTO) pl.mode = needs_tickets ? RR_MODE_TICKET : RR_MODE_FLAT;
+    return RR_OK;
+}
+
+Reducer make_reducer(u64 L) {
+    Reducer r;
+    r.L = L;
+    r.pow2 = (L & (L - 1)) == 0 ? 1u : 0u;
+    r.M = r.pow2 ? 0 : (~0ull) / L;  // floor((2^64-1)/L) == floor(2^64/L) when L is not a power of two
+    return r;
+}
+
+int run_plan(const Plan &pl, const void *region, uint32_t iters, const rr_window_map_t *wm,
+             uint64_t read_seed, hipStream_t stream, const rr_launch_opts_t *opts, rr_result_t *out) {
+    rr_result_t res;
+    memset(&res, 0, sizeof res);
+    if (pl.W == 0) {  // nothing to read
+        *out = res;
+        return RR_OK;
+    }
+    std::lock_guard<std::mutex> lock(g_mutex);
+    DeviceState *stp = nullptr;
+    int rc = get_state(stream, &stp);
+    if (rc != RR_OK) return rc;
+    DeviceState &st = *stp;
+    const u32 n_cus = (u32)st.cus.size();
+    if (wm && wm->n_cus != n_cus)
+        return fail(RR_EINVAL, "window map describes %u compute units, the device has %u", wm->n_cus, n_cus);
+
+    // tables: CU key -> group, group -> first line of its window
+    const u32 lpw = 64 / pl.lanes;
+    const u64 L_win = pl.n_lines / pl.n_windows;
+    const u64 quota = pl.W / pl.G;
+    std::vector<u16> group_of_key(kNumKeys, kExcluded);
+    std::vector<u32> cus_in_group(pl.G, 0);
+    for (u32 c = 0; c < n_cus; ++c) {
+        u16 g = wm ? wm->group_of_cu[c] : 0;
+        group_of_key[key_of(st.cus[c])] = g;
+        if (g != kExcluded) cus_in_group[g]++;
+    }
+    std::vector<u32> window_base(pl.G, 0);
+    for (u32 g = 0; g < pl.G; ++g) {
+        if (wm) window_base[g] = (u32)(wm->window_of_group[g] * L_win);
+        if (cus_in_group[g] == 0) return fail(RR_EPLACE, "group %u has no compute unit", g);
+    }
+    HIP_TRY(hipMemcpyAsync(st.group_of_key, group_of_key.data(), kNumKeys * sizeof(u16), hipMemcpyHostToDevice, stream));
+    HIP_TRY(hipMemcpyAsync(st.window_base, window_base.data(), pl.G * sizeof(u32), hipMemcpyHostToDevice, stream));
+    const bool want_placement = opts && opts->placement_out;
+    if (want_placement && st.placement_cap < pl.W) {
+        HIP_TRY(hipStreamSynchronize(stream));
+        if (st.placement) HIP_TRY(hipFree(st.placement));
+        st.placement = nullptr;
+        st.placement_cap = 0;
+        HIP_TRY(hipMalloc((void **)&st.placement, pl.W * sizeof(u16)));
+        st.placement_cap = pl.W;
+    }
+    if (want_placement) HIP_TRY(hipMemsetAsync(st.placement, 0xFF, pl.W * sizeof(u16), stream));
+
+    ReadParams p;
+    memset(&p, 0, sizeof p);
+    p.region = (const char *)region;
+    p.read_seed = read_seed;
+    p.first_wave = pl.first_wave;
+    p.quota = quota;
+    p.iters = iters;
+    p.n_groups = pl.G;
+    p.ticket_mode = pl.mode == RR_MODE_TICKET ? 1u : 0u;
+    p.log2_line = pl.log2_line;
+    p.red = make_reducer(L_win);
+    p.scratch = st.scratch;
+    p.group_of_key = st.group_of_key;
+    p.dense_of_key = st.dense_of_key;
+    p.window_base = st.window_base;
+    p.placement = want_placement ? st.placement : nullptr;
+
+    const u32 waves_per_block = pl.block / 64;
+    int blocks_per_cu = 0;
+    HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks_per_cu, pl.kernel, (int)pl.block, 0));
+    if (blocks_per_cu < 1) blocks_per_cu = 1;
+    u64 grid;
+    if (p.ticket_mode) {
+        grid = pl.grid_blocks ? pl.grid_blocks : (u64)blocks_per_cu * n_cus * (pl.pinned ? 64u : 2u);
+    } else {
+        const u64 hw_waves = (pl.W + lpw - 1) / lpw;
+        grid = (hw_waves + waves_per_block - 1) / waves_per_block;
+    }
+    if (grid == 0 || grid > 0x7FFFFFFFull) return fail(RR_EINVAL, "launch of %llu workgroups is out of range", grid);
+
+    hipLaunchKernelGGL(reset_kernel, dim3(1), dim3(256), 0, stream, st.scratch, 1u | 2u | 4u);
+    HIP_TRY(hipGetLastError());
+    const u32 tickets_needed = (u32)((quota + lpw - 1) / lpw);
+    const int max_launches = p.ticket_mode ? 32 : 1;
+    void *args[] = {(void *)&p};
+    for (int launch = 0;; ++launch) {
+        HIP_TRY(hipEventRecord(st.ev0, stream));
+        HIP_TRY(hipLaunchKernel(pl.kernel, dim3((u32)grid), dim3(pl.block), args, 0, stream));
+        HIP_TRY(hipEventRecord(st.ev1, stream));
+        HIP_TRY(hipMemcpyAsync(st.head, st.scratch, sizeof(HostHead), hipMemcpyDeviceToHost, stream));
+        HIP_TRY(hipStreamSynchronize(stream));
+        float ms = 0.f;
+        HIP_TRY(hipEventElapsedTime(&ms, st.ev0, st.ev1));
+        res.launches++;
+        res.kernel_ms_event += ms;
+        res.checksum += st.head->checksum;
+        res.waves_run += st.head->waves_run;
+        if (st.head->waves_run && st.head->t_max >= st.head->t_min)
+            res.kernel_ms_device += (double)(st.head->t_max - st.head->t_min) / (double)st.wall_khz;
+        bool done = true;
+        if (p.ticket_mode)
+            for (u32 g = 0; g < pl.G; ++g)
+                if (st.head->tickets[g] < tickets_needed) done = false;
+        if (done) break;
+        if (launch + 1 >= max_launches)
+            return fail(RR_EPLACE, "after %d launches some group still has unclaimed logical waves", max_launches);
+        hipLaunchKernelGGL(reset_kernel, dim3(1), dim3(256), 0, stream, st.scratch, 1u);
+        HIP_TRY(hipGetLastError());
+    }
+    if (want_placement) {
+        HIP_TRY(hipMemcpyAsync(opts->placement_out, st.placement, pl.W * sizeof(u16), hipMemcpyDeviceToHost, stream));
+        HIP_TRY(hipStreamSynchronize(stream));
+    }
+    if (opts && opts->cu_waves_out) memcpy(opts->cu_waves_out, st.head->cu_waves, n_cus * sizeof(u32));
+    *out = res;
+    return RR_OK;
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------ C ABI
+
+extern "C" int rr_enumerate_cus(rr_cu_t *out, uint32_t cap, uint32_t *n_cus, void *hip_stream) {
+    if (!n_cus) return fail(RR_EINVAL, "n_cus is NULL");
+    if (cap > 0 && !out) return fail(RR_EINVAL, "out is NULL but cap > 0");
+    std::lock_guard<std::mutex> lock(g_mutex);
+    DeviceState *st = nullptr;
+    int rc = get_state((hipStream_t)hip_stream, &st);
+    if (rc != RR_OK) return rc;
+    const u32 n = (u32)st->cus.size();
+    for (u32 i = 0; i < n && i < cap; ++i) out[i] = st->cus[i];
+    *n_cus = n;
+    return RR_OK;
+}
+
+extern "C" int rr_fill(void *region, uint64_t region_bytes, uint64_t fill_seed, void *hip_stream) {
+    if (!region) return fail(RR_EINVAL, "region is NULL");
+    if ((uintptr_t)region % 16 != 0) return fail(RR_EINVAL, "region is not 16-byte aligned");
+    if (region_bytes % 16 != 0) return fail(RR_EINVAL, "region_bytes must be a multiple of 16");
+    if (region_bytes == 0) return RR_OK;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    int dev = 0, n_cu = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    HIP_TRY(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
+    const u64 n_pairs = region_bytes / 16;
+    u64 blocks = (n_pairs + 255) / 256;
+    const u64 cap = (u64)n_cu * 16;  // grid-stride beyond this
+    if (blocks > cap) blocks = cap;
+    hipLaunchKernelGGL(fill_kernel, dim3((u32)blocks), dim3(256), 0, stream, (u64x2 *)region, n_pairs,
+                       (u64)fill_seed);
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipStreamSynchronize(stream));
+    return RR_OK;
+}
+
+extern "C" int rr_rand_read(const void *region, uint64_t region_bytes, uint32_t line_bytes,
+                            uint32_t lanes_per_line, uint64_t n_reads, uint32_t iters_per_wave,
+                            const rr_window_map_t *wm, uint64_t read_seed, void *hip_stream,
+                            const rr_launch_opts_t *opts, rr_result_t *out) {
+    Plan pl;
+    int rc = make_plan(region, region_bytes, line_bytes, lanes_per_line, n_reads, iters_per_wave, wm, opts, out, pl);
+    if (rc != RR_OK) return rc;
+    return run_plan(pl, region, iters_per_wave, wm, read_seed, (hipStream_t)hip_stream, opts, out);
+}
+
+extern "C" int rr_probe_cus(const void *region, uint64_t region_bytes, const uint32_t *cus, uint32_t n_target,
+                            uint64_t n_reads, uint32_t iters_per_wave, uint64_t read_seed, void *hip_stream,
+                            const rr_launch_opts_t *opts, rr_result_t *out) {
+    if (!cus || n_target == 0) return fail(RR_EINVAL, "the target set is empty");
+    if (n_target > RR_MAX_CUS) return fail(RR_EINVAL, "too many target compute units");
+    for (u32 a = 0; a < n_target; ++a)
+        for (u32 b = a + 1; b < n_target; ++b)
+            if (cus[a] == cus[b]) return fail(RR_EINVAL, "compute unit %u is named twice", cus[a]);
+    if (opts && opts->mode == RR_MODE_FLAT) return fail(RR_EINVAL, "a pinned run cannot use flat mode");
+    // validate everything else before touching the device (map filled in below)
+    Plan pl;
+    int rc = make_plan(region, region_bytes, 128, 32, n_reads, iters_per_wave, nullptr, opts, out, pl);
+    if (rc != RR_OK) return rc;
+    u32 n_cus = 0;
+    {
+        std::lock_guard<std::mutex> lock(g_mutex);
+        DeviceState *st = nullptr;
+        rc = get_state((hipStream_t)hip_stream, &st);
+        if (rc != RR_OK) return rc;
+        n_cus = (u32)st->cus.size();
+    }
+    std::vector<uint16_t> group_of_cu(n_cus, RR_CU_EXCLUDED);
+    for (u32 a = 0; a < n_target; ++a) {
+        if (cus[a] >= n_cus) return fail(RR_EINVAL, "compute unit id %u is not below %u", cus[a], n_cus);
+        group_of_cu[cus[a]] = 0;
+    }
+    const uint16_t window_of_group[1] = {0};
+    rr_window_map_t wm = {1, 1, n_cus, group_of_cu.data(), window_of_group};
+    pl.mode = RR_MODE_TICKET;
+    pl.pinned = true;
+    return run_plan(pl, region, iters_per_wave, &wm, read_seed, (hipStream_t)hip_stream, opts, out);
+}
+
+extern "C" int rr_probe_pair(const void *region, uint64_t region_bytes, uint32_t cu_a, uint32_t cu_b,
+                             uint64_t n_reads, uint32_t iters_per_wave, uint64_t read_seed, void *hip_stream,
+                             const rr_launch_opts_t *opts, rr_result_t *out) {
+    if (cu_a == cu_b) return fail(RR_EINVAL, "cu_a and cu_b must differ");
+    const uint32_t cus[2] = {cu_a, cu_b};
+    return rr_probe_cus(region, region_bytes, cus, 2, n_reads, iters_per_wave, read_seed, hip_stream, opts, out);
+}
+
+extern "C" int rr_shutdown(void) {
+    std::lock_guard<std::mutex> lock(g_mutex);
+    int current = 0;
+    bool have_current = hipGetDevice(&current) == hipSuccess;
+    for (int d = 0; d < kMaxDevices; ++d) {
+        DeviceState &st = g_state[d];
+        if (!st.scratch && !st.head && !st.ev0) continue;
+        if (hipSetDevice(d) != hipSuccess) continue;
+        (void)hipDeviceSynchronize();
+        if (st.scratch) (void)hipFree(st.scratch);
+        if (st.group_of_key) (void)hipFree(st.group_of_key);
+        if (st.dense_of_key) (void)hipFree(st.dense_of_key);
+        if (st.window_base) (void)hipFree(st.window_base);
+        if (st.placement) (void)hipFree(st.placement);
+        if (st.head) (void)hipHostFree(st.head);
+        if (st.ev0) (void)hipEventDestroy(st.ev0);
+        if (st.ev1) (void)hipEventDestroy(st.ev1);
+        st = DeviceState();
+    }
+    if (have_current) (void)hipSetDevice(current);
+    return RR_OK;
+}

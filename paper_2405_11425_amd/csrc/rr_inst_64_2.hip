@@ -1,0 +1,25 @@
+// Instantiations of the read kernel for 64 lanes per line, 2 dword(s) per lane.
+#include "rr_read_kernel.hpp"
+namespace rr {
+kernel_handle find_read_kernel_64_2(u32 unroll, u32 bcast, u32 nt) {
+    if (unroll == 4 && bcast == 1 && nt == 0) return (kernel_handle)&rand_read_kernel<64, 2, 4, 1, 0>;
+    if (unroll == 4 && bcast == 1 && nt == 1) return (kernel_handle)&rand_read_kernel<64, 2, 4, 1, 1>;
+    if (unroll == 4 && bcast == 2 && nt == 0) return (kernel_handle)&rand_read_kernel<64, 2, 4, 2, 0>;
+    if (unroll == 4 && bcast == 2 && nt == 1) return (kernel_handle)&rand_read_kernel<64, 2, 4, 2, 1>;
+    if (unroll == 4 && bcast == 3 && nt == 0) return (kernel_handle)&rand_read_kernel<64, 2, 4, 3, 0>;
+    if (unroll == 4 && bcast == 3 && nt == 1) return (kernel_handle)&rand_read_kernel<64, 2, 4, 3, 1>;
+    if (unroll == 8 && bcast == 1 && nt == 0) return (kernel_handle)&rand_read_kernel<64, 2, 8, 1, 0>;
+    if (unroll == 8 && bcast == 1 && nt == 1) return (kernel_handle)&rand_read_kernel<64, 2, 8, 1, 1>;
+    if (unroll == 8 && bcast == 2 && nt == 0) return (kernel_handle)&rand_read_kernel<64, 2, 8, 2, 0>;
+    if (unroll == 8 && bcast == 2 && nt == 1) return (kernel_handle)&rand_read_kernel<64, 2, 8, 2, 1>;
+    if (unroll == 8 && bcast == 3 && nt == 0) return (kernel_handle)&rand_read_kernel<64, 2, 8, 3, 0>;
+    if (unroll == 8 && bcast == 3 && nt == 1) return (kernel_handle)&rand_read_kernel<64, 2, 8, 3, 1>;
+    if (unroll == 16 && bcast == 1 && nt == 0) return (kernel_handle)&rand_read_kernel<64, 2, 16, 1, 0>;
+    if (unroll == 16 && bcast == 1 && nt == 1) return (kernel_handle)&rand_read_kernel<64, 2, 16, 1, 1>;
+    if (unroll == 16 && bcast == 2 && nt == 0) return (kernel_handle)&rand_read_kernel<64, 2, 16, 2, 0>;
+    if (unroll == 16 && bcast == 2 && nt == 1) return (kernel_handle)&rand_read_kernel<64, 2, 16, 2, 1>;
+    if (unroll == 16 && bcast == 3 && nt == 0) return (kernel_handle)&rand_read_kernel<64, 2, 16, 3, 0>;
+    if (unroll == 16 && bcast == 3 && nt == 1) return (kernel_handle)&rand_read_kernel<64, 2, 16, 3, 1>;
+    return nullptr;
+}
+}  // namespace rr

@@ -1,0 +1,213 @@
+// The random cache-line read kernel (paper Sec. 2.1: every warp reads random
+// coalesced lines in a memory region; Sec. 2.4: per-group windows; Sec. 2.2:
+// pinned to chosen compute units), written for 64-lane CDNA4 wavefronts.
+//
+// Layout of the work inside one hardware wave
+//   LANES = 32 : the wave carries two logical waves (lanes 0-31 and 32-63), each
+//                reading its own line per iteration, so one global_load touches
+//                two independent lines.
+//   LANES = 64 : the wave is one logical wave and the line address is uniform.
+// Line indices are generated lane-parallel: in a batch lane l evaluates the
+// draw for iteration it0 + (l mod ITB) of its logical wave, so one evaluation
+// of the 64-bit hash serves ITB iterations.  For iteration k the address held
+// by lane k of the half is broadcast to the half's lanes (LDS permute, DPP row
+// broadcast or v_readlane) and every lane loads its WDW dwords of that line.
+// U loads stay in flight per wave: a ring of U result registers is consumed one
+// slot at a time, each slot refilled by the next load, across batch boundaries.
+#pragma once
+#include <utility>
+#include "rr_common.hpp"
+
+namespace rr {
+
+enum { BC_LDS = 1, BC_DPP = 2, BC_READLANE = 3 };
+
+template <int WDW> struct Vec;
+template <> struct Vec<1> { typedef u32 type; };
+typedef u32 u32x2 __attribute__((ext_vector_type(2)));
+typedef u32 u32x4 __attribute__((ext_vector_type(4)));
+template <> struct Vec<2> { typedef u32x2 type; };
+template <> struct Vec<4> { typedef u32x4 type; };
+
+// 64-bit wrapping accumulator kept as two 32-bit halves: adding a zero-extended
+// word is an add with carry-out plus an add of the carry (no 64-bit register pair
+// has to be formed around every loaded word).
+struct Acc {
+    u32 lo, hi;
+    __device__ __forceinline__ void add(u32 w) {
+        u32 s = lo + w;
+        hi += (s < w) ? 1u : 0u;
+        lo = s;
+    }
+    __device__ __forceinline__ void add(u32x2 v) { add(v.x); add(v.y); }
+    __device__ __forceinline__ void add(u32x4 v) { add(v.x); add(v.y); add(v.z); add(v.w); }
+    __device__ __forceinline__ u64 value() const { return ((u64)hi << 32) | lo; }
+};
+
+// Loads go through a global-address-space pointer so that the compiler emits
+// global_load (not flat_load, which also ties up the LDS counter).
+template <int NT, typename T>
+__device__ __forceinline__ T load_line_part(u64 addr) {
+    typedef const T __attribute__((address_space(1))) *gptr;
+    gptr p = (gptr)addr;
+    if constexpr (NT != 0) return __builtin_nontemporal_load(p);
+    else return *p;
+}
+
+template <int K, int N, typename F>
+__device__ __forceinline__ void static_for(F &&f) {
+    if constexpr (K < N) {
+        f(std::integral_constant<int, K>());
+        static_for<K + 1, N>(f);
+    }
+}
+
+// Address of the line of iteration K (compile-time) for this lane's logical
+// wave, taken from the lane that generated it.
+template <int LANES, int BC, int K>
+__device__ __forceinline__ u64 bcast_addr(u32 alo, u32 ahi, u32 lane, u32 sel4) {
+    if constexpr (BC == BC_LDS) {
+        u32 lo = __builtin_amdgcn_ds_bpermute(sel4 + 4 * K, alo);
+        u32 hi = __builtin_amdgcn_ds_bpermute(sel4 + 4 * K, ahi);
+        return ((u64)hi << 32) | lo;
+    } else if constexpr (BC == BC_DPP) {
+        // row_newbcast:K -- lane K of every 16-lane row to the whole row
+        // (every lane has a valid source, so bound_ctrl only spares the compiler a zeroed "old" operand)
+        u32 lo = __builtin_amdgcn_update_dpp(0u, alo, 0x150 + K, 0xF, 0xF, true);
+        u32 hi = __builtin_amdgcn_update_dpp(0u, ahi, 0x150 + K, 0xF, 0xF, true);
+        return ((u64)hi << 32) | lo;
+    } else {
+        u32 lo = __builtin_amdgcn_readlane(alo, K);
+        u32 hi = __builtin_amdgcn_readlane(ahi, K);
+        if constexpr (LANES == 32) {
+            u32 lo1 = __builtin_amdgcn_readlane(alo, 32 + K);
+            u32 hi1 = __builtin_amdgcn_readlane(ahi, 32 + K);
+            bool upper = lane >= 32;
+            lo = upper ? lo1 : lo;
+            hi = upper ? hi1 : hi;
+        }
+        return ((u64)hi << 32) | lo;
+    }
+}
+
+// All `iters` reads of one logical wave per LANES lanes.  wave_seed = sm(read_seed, w)
+// and win_base are per lane (equal within a logical wave).  Returns this lane's
+// share of the logical wave's word sum.
+template <int LANES, int WDW, int U, int BC, int NT>
+__device__ __forceinline__ u64 read_logical_wave(const char *region, u64 wave_seed, u32 win_base,
+                                                 u32 iters, u32 log2_line, const Reducer red,
+                                                 u32 lane) {
+    typedef typename Vec<WDW>::type V;
+    constexpr int ITB = (BC == BC_DPP) ? 16 : LANES;  // iterations generated per batch
+    static_assert(ITB % U == 0, "ring must divide the batch");
+    const u32 itl = lane & (ITB - 1);              // iteration of the batch this lane generates
+    const u32 sub_bytes = (lane & (LANES - 1)) * (WDW * 4);  // this lane's slice of a line
+    const u32 sel4 = (lane & ~(u32)(LANES - 1)) * 4;         // LDS-permute byte index of lane 0 of the half
+    u64 ctr = wave_seed + (u64)(itl + 1) * kGamma;           // SplitMix64 state of iteration itl
+    const u64 step = (u64)ITB * kGamma;
+
+    auto gen = [&]() -> u64 {
+        u32 idx = reduce_to_line(mix64(ctr), red);
+        ctr += step;
+        return (u64)region + (((u64)win_base + idx) << log2_line);
+    };
+
+    V ring[U];
+#pragma unroll
+    for (int j = 0; j < U; ++j) ring[j] = V(0);
+    Acc acc{0u, 0u};
+    u64 cur = gen();
+    const u32 n_batches = iters / ITB;
+    for (u32 b = 0; b < n_batches; ++b) {
+        u64 nxt = gen();
+        const u32 clo = (u32)cur, chi = (u32)(cur >> 32);
+        __builtin_amdgcn_sched_barrier(0);
+        static_for<0, ITB>([&](auto kc) {
+            constexpr int K = decltype(kc)::value;
+            acc.add(ring[K % U]);  // oldest load of the ring: waits until only U-1 are outstanding
+            u64 line = bcast_addr<LANES, BC, K>(clo, chi, lane, sel4);
+            ring[K % U] = load_line_part<NT, V>(line | sub_bytes);
+            __builtin_amdgcn_sched_barrier(0);  // keep issue order: consume slot, refill slot
+        });
+        cur = nxt;
+    }
+#pragma unroll
+    for (int j = 0; j < U; ++j) acc.add(ring[j]);
+    // ragged tail: fewer than ITB iterations left, addresses already in `cur`
+    const u32 rem = iters - n_batches * ITB;
+    for (u32 k = 0; k < rem; ++k) {
+        u32 lo = __builtin_amdgcn_ds_bpermute(sel4 + 4 * k, (u32)cur);
+        u32 hi = __builtin_amdgcn_ds_bpermute(sel4 + 4 * k, (u32)(cur >> 32));
+        u64 line = ((u64)hi << 32) | lo;
+        acc.add(load_line_part<NT, V>(line | sub_bytes));
+    }
+    return acc.value();
+}
+
+template <int LANES, int WDW, int U, int BC, int NT>
+__global__ void __launch_bounds__(256) rand_read_kernel(const ReadParams p) {
+    constexpr u32 LPW = 64 / LANES;  // logical waves per hardware wave
+    const u32 lane = threadIdx.x & 63;
+    const u32 half = (LANES == 32) ? (lane >> 5) : 0;
+    Scratch *s = p.scratch;
+
+    u32 group = 0, dense = 0;
+    if (p.ticket_mode || p.placement) {
+        u32 key = cu_key();
+        group = p.group_of_key[key];
+        dense = p.dense_of_key[key];
+        if (group == kExcluded) return;  // a CU that takes no part (pinned runs)
+    }
+    const u32 win_base = p.window_base[group];
+    u64 acc = 0;
+    u64 t0 = 0;
+    bool worked = false;
+    for (;;) {
+        u64 j0;  // index, within the group, of the logical wave of lanes 0..LANES-1
+        if (p.ticket_mode) {
+            u32 t = 0;
+            if (lane == 0) t = atomicAdd(&s->tickets[group], 1u);
+            t = __builtin_amdgcn_readfirstlane(t);
+            j0 = (u64)t * LPW;
+        } else {
+            j0 = ((u64)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6)) * LPW;
+        }
+        if (j0 >= p.quota) break;
+        if (!worked) {
+            worked = true;
+            t0 = clock_ticks();
+        }
+        u64 j = j0 + half;
+        const bool valid = j < p.quota;  // odd quota: the upper half shadows the lower one
+        if (!valid) j = j0;
+        const u64 w = p.first_wave + group + (u64)p.n_groups * j;
+        const u64 wave_seed = mix64(p.read_seed + (w + 1) * kGamma);
+        u64 part = read_logical_wave<LANES, WDW, U, BC, NT>(p.region, wave_seed, win_base, p.iters,
+                                                            p.log2_line, p.red, lane);
+        acc += valid ? part : 0;
+        if (p.placement && valid && (lane & (LANES - 1)) == 0) p.placement[w - p.first_wave] = (u16)dense;
+        if (!p.ticket_mode) break;
+    }
+    if (!worked) return;
+    const u64 total = wave_sum(acc);
+    const u64 t1 = clock_ticks();
+    if (lane == 0) {
+        atomicAdd(&s->checksum, total);
+        atomicMin(&s->t_min, t0);
+        atomicMax(&s->t_max, t1);
+        atomicAdd(&s->waves_run, 1u);
+        if (p.ticket_mode || p.placement) atomicAdd(&s->cu_waves[dense], 1u);
+    }
+}
+
+// Each (LANES, WDW) family lives in its own translation unit and exposes a
+// finder that returns the kernel's host-side handle for (unroll, bcast,
+// nontemporal), or null if that combination is not built.
+typedef const void *kernel_handle;
+kernel_handle find_read_kernel_32_1(u32 unroll, u32 bcast, u32 nt);
+kernel_handle find_read_kernel_32_2(u32 unroll, u32 bcast, u32 nt);
+kernel_handle find_read_kernel_32_4(u32 unroll, u32 bcast, u32 nt);
+kernel_handle find_read_kernel_64_1(u32 unroll, u32 bcast, u32 nt);
+kernel_handle find_read_kernel_64_2(u32 unroll, u32 bcast, u32 nt);
+
+}  // namespace rr
