@@ -1,0 +1,328 @@
+"""GPU parity: the HIP library (through its C ABI binding) against the CPU oracle.
+
+Checksums, indices and placements are integer work: everything is compared bit-exactly.
+Run on the GPU machine with `pytest -m gpu`.
+"""
+import os
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+import paper_2405_11425_amd as rl                      # noqa: E402
+from paper_2405_11425_amd import workloads as wl       # noqa: E402
+from oracle import randline as orc                     # noqa: E402
+
+GiB = 1 << 30
+M64 = (1 << 64) - 1
+ORACLE_THREADS = 16
+
+
+@pytest.fixture(scope="module")
+def region():
+    """One device allocation, as large as fits (256 GiB on an idle MI355X), filled with seed 1."""
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    assert os.path.exists(rl.library_path()), "librandline.so is not built"
+    free, _ = torch.cuda.mem_get_info()
+    gib = min(256, int((free - 6 * GiB) // GiB))
+    assert gib >= 2, "not enough free device memory"
+    buf = torch.empty(gib * GiB, dtype=torch.uint8, device="cuda")
+    rl.fill(buf, wl.FILL_SEED)
+    return buf
+
+
+@pytest.fixture(scope="module")
+def cu_table():
+    return rl.enumerate_cus()
+
+
+def oracle(cfg_bytes, B, W, I, read_seed=wl.READ_SEED, **kw):
+    return orc.checksum(cfg_bytes, B, W, I, wl.FILL_SEED, read_seed, n_threads=ORACLE_THREADS, **kw)
+
+
+# ------------------------------------------------------------------ CU enumeration
+def test_enumerate_cus(cu_table):
+    n = torch.cuda.get_device_properties(0).multi_processor_count
+    assert cu_table.shape == (n, 4)
+    keys = [tuple(r) for r in cu_table.tolist()]
+    assert keys == sorted(set(keys))                      # distinct and in dense-id order
+    xcc, counts = np.unique(cu_table[:, 0], return_counts=True)
+    assert len(set(counts.tolist())) == 1                 # same CU count on every XCD
+    assert np.array_equal(rl.enumerate_cus(), cu_table)   # stable across calls
+
+
+# ------------------------------------------------------------------ fill
+def test_fill_matches_oracle_words(region):
+    n_words = region.numel() // 4
+    offsets = [0, 1, 1023, (1 << 20) - 512, n_words // 2 - 7, n_words - 4096]
+    if n_words > (1 << 32):
+        offsets += [(1 << 32) - 100, (1 << 32) + 12345, n_words - (1 << 31) - 3]  # beyond 32-bit word indices
+    rng = np.random.default_rng(3)
+    offsets += [int(x) for x in rng.integers(0, n_words - 4096, size=24)]
+    for off in offsets:
+        off -= off % 4                                     # keep the byte offset 16-aligned for the view
+        got = region[off * 4:(off + 4096) * 4].cpu().numpy().view(np.uint32)
+        assert np.array_equal(got, orc.fill_words(wl.FILL_SEED, off, 4096)), f"word offset {off}"
+
+
+def test_fill_ragged_sizes_and_other_seed():
+    """Sizes that are not a multiple of the grid's stride, incl. the 16-byte minimum; empty fill."""
+    for nbytes in (16, 48, 4096 + 16, (1 << 20) + 16 * 37, 3 * (1 << 22) + 16):
+        buf = torch.zeros(nbytes + 64, dtype=torch.uint8, device="cuda")
+        rl.fill(buf, 0xDEADBEEF12345, region_bytes=nbytes)
+        host = buf.cpu().numpy()
+        assert np.array_equal(host[:nbytes].view(np.uint32), orc.fill_words(0xDEADBEEF12345, 0, nbytes // 4))
+        assert not host[nbytes:].any()                     # nothing written past the end
+    buf = torch.zeros(64, dtype=torch.uint8, device="cuda")
+    rl.fill(buf, 5, region_bytes=0)
+    assert not buf.cpu().numpy().any()
+
+
+# ------------------------------------------------------------------ rand_read, small cases
+SMALL = [
+    # region bytes, line, lanes, W, I
+    (4096, 128, 32, 4, 8),
+    (4096, 256, 32, 4, 8),
+    (4096, 512, 32, 4, 8),
+    (12288, 128, 32, 4, 8),            # 96 lines: exact remainder path
+    (128, 128, 32, 2, 3),              # one-line region
+    (512, 512, 32, 1, 1),              # one line, one wave, one read
+    (1 << 20, 128, 32, 1, 1),          # single logical wave: upper half of the wavefront shadows
+    (1 << 20, 128, 32, 7, 100),        # odd W, I not a multiple of the batch
+    (1 << 20, 128, 32, 513, 33),       # several workgroups + ragged tail
+    (3 << 20, 256, 32, 77, 95),        # non-power-of-two lines, 8-byte lanes
+    (5 << 19, 512, 32, 31, 129),       # 16-byte lanes
+    (1 << 20, 256, 64, 9, 70),         # 64-lane lines
+    (3 << 20, 512, 64, 33, 257),
+    (1 << 28, 128, 32, 256, 4096),     # the small reference configuration
+    (1 << 28, 128, 32, 1024, 1024),
+]
+
+
+@pytest.mark.parametrize("R,B,lanes,W,I", SMALL)
+def test_rand_read_small(region, R, B, lanes, W, I):
+    want = oracle(R, B, W, I)
+    got = rl.rand_read(region, B, W * I, I, wl.READ_SEED, lanes_per_line=lanes, region_bytes=R)
+    assert got.checksum == want
+    assert got.launches == 1 and got.waves_run == (W * lanes + 63) // 64
+
+
+def test_reference_configuration_value(region, worked):
+    """The first configuration against the stored worked value (not only the live oracle)."""
+    got = rl.rand_read(region, 128, 1 << 20, 4096, 7, region_bytes=1 << 28)
+    assert got.checksum == worked["pr1_W256_I4096"][0]
+
+
+def test_empty_read(region):
+    got = rl.rand_read(region, 128, 0, 4096, 7, region_bytes=1 << 20)
+    assert got.checksum == 0 and got.waves_run == 0
+
+
+@pytest.mark.parametrize("B,lanes,unrolls", [(128, 32, (4, 8, 16)), (256, 32, (4, 8, 16)), (512, 32, (2, 4, 8)),
+                                             (256, 64, (4, 8, 16)), (512, 64, (4, 8, 16))])
+def test_launch_geometry_does_not_change_checksum(region, B, lanes, unrolls):
+    """Broadcast path, ring depth, cache hint, block size, flat vs ticketed, grid size."""
+    R, W, I = 3 << 24, 301, 197
+    want = oracle(R, B, W, I)
+    for bcast in (rl.BCAST_LDS, rl.BCAST_DPP, rl.BCAST_READLANE):
+        for unroll in unrolls:
+            for nt in (0, 1):
+                got = rl.rand_read(region, B, W * I, I, wl.READ_SEED, lanes_per_line=lanes, region_bytes=R,
+                                   bcast=bcast, unroll=unroll, nontemporal=nt)
+                assert got.checksum == want, (bcast, unroll, nt)
+    for block in (64, 128, 256):
+        for mode, grid in ((rl.MODE_FLAT, 0), (rl.MODE_TICKET, 0), (rl.MODE_TICKET, 3), (rl.MODE_TICKET, 1000)):
+            got = rl.rand_read(region, B, W * I, I, wl.READ_SEED, lanes_per_line=lanes, region_bytes=R,
+                               block_threads=block, mode=mode, grid_blocks=grid)
+            assert got.checksum == want, (block, mode, grid)
+
+
+def test_additivity_over_wave_ranges(region):
+    R, B, I = 1 << 26, 128, 64
+    whole = rl.rand_read(region, B, 1000 * I, I, 9, region_bytes=R).checksum
+    assert whole == oracle(R, B, 1000, I, read_seed=9)
+    parts = 0
+    for first, n in ((0, 1), (1, 333), (334, 666)):
+        got = rl.rand_read(region, B, n * I, I, 9, region_bytes=R, first_wave=first).checksum
+        assert got == oracle(R, B, n, I, read_seed=9, first_wave=first)
+        parts += got
+    assert parts & M64 == whole
+
+
+def test_line_shapes_with_equal_bytes_agree(region):
+    """256-byte lines as 32 x 8 B and as 64 x 4 B read the same words (same W)."""
+    R, W, I = 1 << 27, 128, 500
+    a = rl.rand_read(region, 256, W * I, I, 7, lanes_per_line=32, region_bytes=R).checksum
+    b = rl.rand_read(region, 256, W * I, I, 7, lanes_per_line=64, region_bytes=R).checksum
+    assert a == b == oracle(R, 256, W, I)
+
+
+def test_repeatable(region):
+    R, W, I = 1 << 30, 2048, 512
+    seen = {rl.rand_read(region, 128, W * I, I, 5, region_bytes=R).checksum for _ in range(5)}
+    assert seen == {oracle(R, 128, W, I, read_seed=5)}
+
+
+# ------------------------------------------------------------------ windows
+def check_placement(res, W, G, group_of_cu):
+    assert res.placement is not None and res.placement.shape == (W,)
+    assert (res.placement != 0xFFFF).all()                         # every logical wave was executed
+    for w in range(W):
+        assert group_of_cu[res.placement[w]] == w % G, f"logical wave {w} ran on CU {res.placement[w]}"
+
+
+@pytest.mark.parametrize("n_windows", [1, 2, 4, 8])
+def test_windows_by_xcd(region, cu_table, n_windows):
+    R, B, I = 1 << 30, 128, 256
+    g_of_cu, w_of_g = wl.window_map_by_xcd(cu_table, n_windows)
+    G = len(w_of_g)
+    W = G * 12
+    want = oracle(R, B, W, I, n_windows=n_windows, window_of_group=w_of_g)
+    res = rl.rand_read(region, B, W * I, I, wl.READ_SEED, rl.WindowMap(n_windows, g_of_cu, w_of_g),
+                       region_bytes=R, want_placement=True, want_cu_waves=True)
+    assert res.checksum == want
+    check_placement(res, W, G, g_of_cu)
+    assert int(res.cu_waves.sum()) == res.waves_run
+
+
+@pytest.mark.parametrize("n_windows", [2, 8])
+def test_windows_random_per_cu(region, cu_table, n_windows):
+    """Every CU its own group: each CU must turn up for its own logical waves."""
+    R, B, I = 3 << 28, 128, 64
+    n = len(cu_table)
+    g_of_cu, w_of_g = wl.window_map_random_per_cu(n, n_windows, seed=11)
+    W = n * 4
+    want = oracle(R, B, W, I, n_windows=n_windows, window_of_group=w_of_g)
+    res = rl.rand_read(region, B, W * I, I, wl.READ_SEED, rl.WindowMap(n_windows, g_of_cu, w_of_g),
+                       region_bytes=R, want_placement=True)
+    assert res.checksum == want
+    check_placement(res, W, n, g_of_cu)
+
+
+def test_windows_other_shapes_and_odd_quota(region, cu_table):
+    """512-byte and 64-lane lines under a map; odd number of logical waves per group."""
+    R, I = 3 << 27, 77
+    g_of_cu, w_of_g = wl.window_map_by_xcd(cu_table, 4)
+    G = len(w_of_g)
+    for B, lanes in ((512, 32), (256, 64), (256, 32)):
+        W = G * 5
+        want = oracle(R, B, W, I, n_windows=4, window_of_group=w_of_g)
+        res = rl.rand_read(region, B, W * I, I, wl.READ_SEED, rl.WindowMap(4, g_of_cu, w_of_g),
+                           lanes_per_line=lanes, region_bytes=R, want_placement=True)
+        assert res.checksum == want
+        check_placement(res, W, G, g_of_cu)
+
+
+def test_degenerate_maps_equal_no_map(region, cu_table):
+    R, B, W, I = 1 << 28, 128, 256, 128
+    plain = rl.rand_read(region, B, W * I, I, wl.READ_SEED, region_bytes=R).checksum
+    n = len(cu_table)
+    one = rl.WindowMap(1, np.zeros(n, np.uint16), np.zeros(1, np.uint16))
+    assert rl.rand_read(region, B, W * I, I, wl.READ_SEED, one, region_bytes=R).checksum == plain
+    g_of_cu, _ = wl.window_map_by_xcd(cu_table, 1)
+    many = rl.WindowMap(1, g_of_cu, np.zeros(int(g_of_cu.max()) + 1, np.uint16))
+    assert rl.rand_read(region, B, W * I, I, wl.READ_SEED, many, region_bytes=R).checksum == plain
+
+
+def test_group_without_cu_is_reported(region, cu_table):
+    n = len(cu_table)
+    wm = rl.WindowMap(2, np.zeros(n, np.uint16), np.array([0, 1], np.uint16))   # group 1 owns no CU
+    with pytest.raises(rl.RandlineError) as e:
+        rl.rand_read(region, 128, 2 * 8, 8, 7, wm, region_bytes=1 << 20)
+    assert e.value.code == rl.RR_EPLACE
+
+
+# ------------------------------------------------------------------ pinned probe
+def test_probe_pairs(region, cu_table):
+    R, I, W = 1 << 30, 256, 64
+    want = oracle(R, 128, W, I)
+    n = len(cu_table)
+    for a, b in ((0, 1), (0, n - 1), (n // 2, 5), (n - 2, n - 1)):
+        res = rl.probe_cus(region, [a, b], W * I, I, wl.READ_SEED, region_bytes=R,
+                           want_placement=True, want_cu_waves=True)
+        assert res.checksum == want                               # the same for every pair
+        assert set(np.unique(res.placement).tolist()) <= {a, b}
+        others = np.delete(res.cu_waves[:n], [a, b])
+        assert not others.any() and res.cu_waves[[a, b]].sum() == res.waves_run > 0
+        assert rl.probe_pair(region, a, b, W * I, I, wl.READ_SEED, region_bytes=R).checksum == want
+
+
+def test_probe_single_cu_and_group(region, cu_table):
+    R, I, W = 1 << 30, 128, 32
+    want = oracle(R, 128, W, I)
+    res = rl.probe_cus(region, [17], W * I, I, wl.READ_SEED, region_bytes=R, want_placement=True)
+    assert res.checksum == want and set(res.placement.tolist()) == {17}
+    xcd0 = np.flatnonzero(cu_table[:, 0] == cu_table[0, 0]).tolist()
+    res = rl.probe_cus(region, xcd0, W * I, I, wl.READ_SEED, region_bytes=R, want_placement=True)
+    assert res.checksum == want and set(res.placement.tolist()) <= set(xcd0)
+
+
+def test_probe_rejects_bad_targets(region, cu_table):
+    n = len(cu_table)
+    for cus in ([3, 3], [0, n], []):
+        with pytest.raises(rl.RandlineError) as e:
+            rl.probe_cus(region, cus, 64, 8, 7, region_bytes=1 << 20)
+        assert e.value.code == rl.RR_EINVAL
+
+
+# ------------------------------------------------------------------ full sizes, as bench.py launches them
+def test_region_sweep_full_size(region, cu_table):
+    """Every point of the region-size sweep (all wave slots occupied, 4096 reads per logical
+    wave, default launch options -- what bench.py times) against the oracle."""
+    for cfg in wl.region_sweep(region.numel(), len(cu_table)):
+        got = rl.rand_read(region, cfg.line_bytes, cfg.n_reads, cfg.iters_per_wave, cfg.read_seed,
+                           lanes_per_line=cfg.lanes_per_line, region_bytes=cfg.region_bytes)
+        want = oracle(cfg.region_bytes, cfg.line_bytes, cfg.logical_waves, cfg.iters_per_wave)
+        assert got.checksum == want, cfg.name
+        assert got.waves_run == cfg.logical_waves // 2
+
+
+def test_line_width_sweep_full_size(region):
+    """2^30 reads per line shape at the largest region: the whole run must equal the sum of its
+    16 wave sub-ranges (GPU), and sampled sub-ranges must equal the oracle."""
+    R = region.numel()
+    if R >= 256 * GiB:
+        R = 256 * GiB
+    for cfg in wl.line_width_sweep(R):
+        kw = dict(lanes_per_line=cfg.lanes_per_line, region_bytes=R)
+        whole = rl.rand_read(region, cfg.line_bytes, cfg.n_reads, cfg.iters_per_wave, cfg.read_seed, **kw).checksum
+        sub = cfg.logical_waves // 16
+        total = 0
+        for k in range(16):
+            part = rl.rand_read(region, cfg.line_bytes, sub * cfg.iters_per_wave, cfg.iters_per_wave, cfg.read_seed,
+                                first_wave=k * sub, **kw).checksum
+            total += part
+            if k in (0, 7, 15):
+                assert part == oracle(R, cfg.line_bytes, sub, cfg.iters_per_wave, first_wave=k * sub), (cfg.name, k)
+        assert total & M64 == whole, cfg.name
+
+
+def test_windowed_full_size(region, cu_table):
+    """Largest region, windows of 1/2, 1/4, 1/8, XCD-aware and random-per-CU, full occupancy."""
+    R = region.numel()
+    if R >= 256 * GiB:
+        R = 256 * GiB
+    n = len(cu_table)
+    W, I = wl.resident_logical_waves(n), wl.ITERS_PER_WAVE
+    for n_windows in (2, 4, 8):
+        for scheme in ("xcd", "random"):
+            g_of_cu, w_of_g = (wl.window_map_by_xcd(cu_table, n_windows) if scheme == "xcd"
+                               else wl.window_map_random_per_cu(n, n_windows, seed=n_windows))
+            want = oracle(R, 128, W, I, n_windows=n_windows, window_of_group=w_of_g)
+            got = rl.rand_read(region, 128, W * I, I, wl.READ_SEED, rl.WindowMap(n_windows, g_of_cu, w_of_g),
+                               region_bytes=R)
+            assert got.checksum == want, (n_windows, scheme)
+
+
+def test_probe_full_size(region, cu_table):
+    """The pair-probe configuration (16 GiB, 2^22 reads) on a few sampled pairs."""
+    cfg = wl.probe_config(min(16 * GiB, region.numel()))
+    want = oracle(cfg.region_bytes, 128, cfg.logical_waves, cfg.iters_per_wave)
+    sample = wl.probe_cu_sample(cu_table)
+    for a, b in ((sample[0], sample[1]), (sample[0], sample[-1]), (sample[10], sample[40])):
+        got = rl.probe_pair(region, int(a), int(b), cfg.n_reads, cfg.iters_per_wave, cfg.read_seed,
+                            region_bytes=cfg.region_bytes)
+        assert got.checksum == want

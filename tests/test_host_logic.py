@@ -1,0 +1,182 @@
+"""CPU-only checks of the product's host side: the C ABI library loads and exports what the
+header declares, rejects bad arguments before touching a device, clusters heatmaps exactly like
+the grouping oracle, and the workload/window-map generators produce valid inputs."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2405_11425_amd as rl
+from paper_2405_11425_amd import workloads as wl
+from oracle.grouping import groups_from_heatmap as oracle_groups
+from test_grouping_oracle import planted, same_partition
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "randline.h")).read()
+    declared = set(re.findall(r"\b(rr_[a-z_]+)\s*\(", header))
+    assert declared >= {"rr_fill", "rr_rand_read", "rr_probe_pair", "rr_enumerate_cus"}
+    lib = C.CDLL(rl.library_path())
+    for name in sorted(declared):
+        assert hasattr(lib, name), f"{name} is declared in randline.h but not exported"
+    assert declared == set(rl.binding.EXPORTS)
+
+
+def test_strerror_and_codes():
+    L = rl.lib()
+    assert L.rr_strerror(0) == b"success"
+    for code in (rl.RR_EINVAL, rl.RR_EHIP, rl.RR_EPLACE, -99):
+        assert L.rr_strerror(code)
+
+
+FAKE = (1 << 21, 1 << 20)  # an aligned, non-null "device pointer" that is never dereferenced on these paths
+
+
+@pytest.mark.parametrize("args,kw,needle", [
+    (((0, 4096), 128, 8, 8, 7), {}, "NULL"),
+    ((FAKE, 100, 8, 8, 7), {}, "line_bytes"),
+    ((FAKE, 128, 8, 8, 7), {"lanes_per_line": 64}, "4, 8 or 16"),
+    ((FAKE, 128, 8, 8, 7), {"lanes_per_line": 16}, "lanes_per_line"),
+    (((1 << 21, 1000), 128, 8, 8, 7), {}, "multiple of line_bytes"),
+    (((1 << 21, 0), 128, 8, 8, 7), {}, "multiple of line_bytes"),
+    ((((1 << 21) + 64, 4096), 128, 8, 8, 7), {}, "aligned"),
+    (((1 << 21, (1 << 39) + (1 << 38)), 128, 8, 8, 7), {}, "2^32"),
+    ((FAKE, 128, 9, 8, 7), {}, "multiple of iters_per_wave"),
+    ((FAKE, 128, 8, 0, 7), {}, "at least 1"),
+    ((FAKE, 128, 8, 8, 7), {"block_threads": 96}, "block_threads"),
+    ((FAKE, 128, 8, 8, 7), {"unroll": 3}, "unroll"),
+    ((FAKE, 512, 8, 8, 7), {"unroll": 16}, "unroll"),
+    ((FAKE, 128, 8, 8, 7), {"bcast": 9}, "bcast"),
+    ((FAKE, 128, 8, 8, 7), {"mode": 5}, "mode"),
+    ((FAKE, 128, 8, 8, 7), {"nontemporal": 2}, "nontemporal"),
+])
+def test_rand_read_rejects_bad_arguments_without_a_device(args, kw, needle):
+    with pytest.raises(rl.RandlineError) as e:
+        rl.rand_read(*args, **kw)
+    assert e.value.code == rl.RR_EINVAL and needle in str(e.value)
+
+
+@pytest.mark.parametrize("wm,n_reads,kw,needle", [
+    (rl.WindowMap(3, np.zeros(4, np.uint16), np.zeros(1, np.uint16)), 8, {}, "divide"),
+    (rl.WindowMap(2, np.array([0, 2], np.uint16), np.array([0, 1], np.uint16)), 16, {}, "group_of_cu"),
+    (rl.WindowMap(2, np.array([0, 1], np.uint16), np.array([0, 2], np.uint16)), 16, {}, "window_of_group"),
+    (rl.WindowMap(2, np.array([0, 1], np.uint16), np.array([0, 1], np.uint16)), 24, {}, "multiple of n_groups"),
+    (rl.WindowMap(2, np.array([0, 1], np.uint16), np.array([0, 1], np.uint16)), 16, {"first_wave": 1}, "first_wave"),
+    (rl.WindowMap(2, np.array([0, 1], np.uint16), np.array([0, 1], np.uint16)), 16, {"mode": rl.MODE_FLAT}, "flat"),
+    (rl.WindowMap(1, np.array([0, 0xFFFF], np.uint16), np.array([0], np.uint16)), 16, {"mode": rl.MODE_FLAT}, "flat"),
+])
+def test_window_map_validation(wm, n_reads, kw, needle):
+    with pytest.raises(rl.RandlineError) as e:
+        rl.rand_read(FAKE, 128, n_reads, 8, 7, wm, **kw)
+    assert e.value.code == rl.RR_EINVAL and needle in str(e.value)
+
+
+def test_fill_and_probe_validation():
+    with pytest.raises(rl.RandlineError):
+        rl.fill((0, 4096), 1)
+    with pytest.raises(rl.RandlineError):
+        rl.fill(((1 << 21) + 8, 4096), 1)
+    with pytest.raises(rl.RandlineError):
+        rl.fill((1 << 21, 4100), 1)
+    with pytest.raises(rl.RandlineError) as e:
+        rl.probe_pair(FAKE, 3, 3, 8, 8, 7)
+    assert "differ" in str(e.value)
+    with pytest.raises(rl.RandlineError) as e:
+        rl.probe_cus(FAKE, [1, 2, 1], 8, 8, 7)
+    assert "twice" in str(e.value)
+    with pytest.raises(rl.RandlineError):
+        rl.probe_cus(FAKE, [], 8, 8, 7)
+
+
+def test_out_left_untouched_on_failure():
+    res = rl.binding._Result(123, 1.0, 2.0, 4, 5)
+    rc = rl.lib().rr_rand_read(1 << 21, 1000, 128, 32, 8, 8, None, 7, None, None, C.byref(res))
+    assert rc == rl.RR_EINVAL and (res.checksum, res.waves_run, res.launches) == (123, 4, 5)
+    assert rl.lib().rr_rand_read(1 << 21, 4096, 128, 32, 8, 8, None, 7, None, None, None) == rl.RR_EINVAL
+
+
+# ------------------------------------------------------------------ heatmap clustering: library vs oracle
+@pytest.mark.parametrize("sizes,seed", [([8] * 8, 1), ([8, 6, 8, 8, 6, 8, 8, 8, 8, 8, 8, 8, 8, 8], 2),
+                                        ([2] * 32, 3), ([1, 1, 30], 4), ([64], 5), ([3, 5, 7, 11], 6)])
+@pytest.mark.parametrize("use_singles", [False, True])
+def test_groups_from_heatmap_matches_oracle(sizes, seed, use_singles):
+    slow = 1.0 if len(sizes) == 1 else 0.6
+    T, truth = planted(sizes, seed, slow=slow)
+    rng = np.random.default_rng(seed)
+    singles = 100.0 * (1 + 0.01 * rng.standard_normal(len(truth))) if use_singles else None
+    g_lib, order_lib, thr_lib = rl.groups_from_heatmap(T, singles)
+    g_orc, order_orc, thr_orc = oracle_groups(T, singles)
+    assert g_lib.tolist() == g_orc.tolist()
+    assert order_lib.tolist() == order_orc.tolist()
+    assert (np.isnan(thr_lib) and np.isnan(thr_orc)) or thr_lib == thr_orc
+    if len(sizes) > 1:
+        assert same_partition(g_lib, truth)
+
+
+def test_groups_from_heatmap_noisy_random_matrices_match_oracle():
+    rng = np.random.default_rng(0)
+    for n in (2, 3, 5, 17, 40):
+        A = rng.uniform(50, 200, size=(n, n))
+        T = (A + A.T) / 2
+        for gap in (0.0, 0.05, 0.5):
+            g_lib, o_lib, t_lib = rl.groups_from_heatmap(T, None, gap)
+            g_orc, o_orc, t_orc = oracle_groups(T, None, gap)
+            assert g_lib.tolist() == g_orc.tolist() and o_lib.tolist() == o_orc.tolist()
+            assert (np.isnan(t_lib) and np.isnan(t_orc)) or t_lib == t_orc
+
+
+def test_groups_from_heatmap_single_unit():
+    g, o, t = rl.groups_from_heatmap(np.zeros((1, 1)))
+    assert g.tolist() == [0] and o.tolist() == [0] and np.isnan(t)
+
+
+# ------------------------------------------------------------------ workload generators
+def test_window_maps_are_valid():
+    table = wl.synthetic_cu_table()
+    for nw in (1, 2, 4, 8):
+        g, w = wl.window_map_by_xcd(table, nw)
+        assert g.shape == (256,) and w.shape == (8,) and g.max() == 7 and w.max() == min(nw, 8) - 1
+        assert all((g[table[:, 0] == x] == x).all() for x in range(8))
+        g, w = wl.window_map_random_per_cu(256, nw, seed=4)
+        assert g.tolist() == list(range(256)) and w.max() < nw
+        assert np.array_equal(w, wl.window_map_random_per_cu(256, nw, seed=4)[1])   # seeded
+    g, w = wl.window_map_from_groups([0, 0, 1, 1, 2, 0xFFFF], 2)
+    assert w.tolist() == [0, 1, 0]
+
+
+def test_probe_sample_and_configs():
+    table = wl.synthetic_cu_table()
+    s = wl.probe_cu_sample(table)
+    assert len(s) == 64 and len(set(s.tolist())) == 64
+    assert all(np.sum(table[s, 0] == x) == 8 for x in range(8))
+    assert all(s[i + 1] == s[i] + 1 for i in range(0, 64, 2))       # adjacent-id pairs
+    sweep = wl.region_sweep()
+    assert [c.region_bytes >> 30 for c in sweep] == [1, 2, 4, 8, 16, 32, 64, 128, 192, 256]
+    assert all(c.n_reads == 1 << 26 and c.line_bytes == 128 for c in sweep)
+    assert wl.pr1_reference().n_reads == 1 << 20
+    assert all(c.n_reads == 1 << 30 for c in wl.line_width_sweep(128 << 30))
+    assert wl.probe_config().n_reads == 1 << 22
+
+
+# ------------------------------------------------------------------ the exact-remainder recipe of the kernel
+def test_reciprocal_remainder_recipe_is_exact():
+    """The read kernel reduces a 64-bit draw h modulo a non-power-of-two L <= 2^32 as
+    q = mulhi64(h, M), M = floor((2^64-1)/L), r = h - q*L, one conditional subtraction.
+    Shown here with Python integers: q is floor(h/L) or one less, so one step suffices."""
+    rng = np.random.default_rng(1)
+    Ls = [3, 5, 96, 3 << 30, (1 << 32) - 1, (1 << 31) + 1, 3 << 29, 1000003, 7 << 28]
+    Ls += [int(x) for x in rng.integers(3, 1 << 32, size=200) if int(x) & (int(x) - 1)]
+    hs = [0, 1, (1 << 64) - 1, (1 << 63), (1 << 63) - 1] + [int(x) for x in rng.integers(0, 1 << 64, size=300, dtype=np.uint64)]
+    for L in Ls:
+        M = ((1 << 64) - 1) // L
+        for h in hs + [L - 1, L, L + 1, ((1 << 64) - 1) // L * L, ((1 << 64) - 1) // L * L - 1]:
+            q = (h * M) >> 64
+            r = h - q * L
+            assert 0 <= r < 2 * L
+            if r >= L:
+                r -= L
+            assert r == h % L
