@@ -1,0 +1,186 @@
+#!/usr/bin/env python3
+"""Benchmark driver: random-line read GB/s vs region size (1..256 GiB) on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+
+One "step" is one pass of the hot path over the region-size sweep: for each region size
+(1, 2, 4, ..., 128, 192, 256 GiB prefixes of one filled allocation) one rr_rand_read call in
+which every wave slot of the device is occupied and every 32-lane logical wave reads 4096
+uniformly random, aligned 128-byte lines (paper Sec. 2.1).  The fill is done once before the
+timed region (the region is resident in HBM when timing starts).  Prints ONE JSON line.
+
+`value` is whole-job throughput: bytes read in the K timed steps / wall time between two device
+synchronisations, i.e. it includes launch, the 8-byte result read-back and host overhead.
+`roofline` is for the read kernel alone: algorithmic bytes per launch / average launch duration
+measured by the library with HIP events on the launch stream, against the 8 TB/s HBM3E peak.
+`cpu_baseline` times the CPU oracle (recompute mode) on one sweep point on the host's cores and
+checks that its checksum equals the GPU's for the same arguments.
+"""
+import argparse
+import json
+import os
+import statistics
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def read_traffic_file(path):
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary, or None."""
+    try:
+        with open(path) as f:
+            for line in f:
+                if line.startswith("hbm_read_bytes_per_launch:"):
+                    return float(line.split(":", 1)[1].split()[0])
+    except OSError:
+        pass
+    return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--max-region-gib", type=int, default=256)
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this benchmark is a single-GPU measurement; --gpus must be 1 "
+              "(no multi-GPU path is built: see DESIGN.md, 'How the path would shard').", file=sys.stderr)
+        return 2
+
+    import torch
+    import paper_2405_11425_amd as rl
+    from paper_2405_11425_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback.", file=sys.stderr)
+        return 3
+    if not os.path.exists(rl.library_path()):
+        print("bench.py: librandline.so is not built (run __graft_entry__.build()).", file=sys.stderr)
+        return 3
+
+    GiB = wl.GiB
+    free, total = torch.cuda.mem_get_info()
+    max_gib = min(args.max_region_gib, int((free - 4 * GiB) // GiB))
+    cu_table = rl.enumerate_cus()
+    n_cus = len(cu_table)
+    region = torch.empty(max_gib * GiB, dtype=torch.uint8, device="cuda")
+    t0 = time.perf_counter()
+    rl.fill(region, wl.FILL_SEED)
+    torch.cuda.synchronize()
+    fill_s = time.perf_counter() - t0
+    configs = wl.region_sweep(max_gib * GiB, n_cus)
+
+    def step(seed, record=None):
+        for cfg in configs:
+            r = rl.rand_read(region, cfg.line_bytes, cfg.n_reads, cfg.iters_per_wave, seed,
+                             lanes_per_line=cfg.lanes_per_line, region_bytes=cfg.region_bytes)
+            if record is not None:
+                record.setdefault(cfg.name, []).append(r)
+
+    for i in range(args.warmup):
+        step(1000 + i)
+    records = {}
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(wl.READ_SEED + k, records)
+    torch.cuda.synchronize()
+    wall_s = time.perf_counter() - t0
+
+    bytes_per_step = sum(c.bytes_read for c in configs)
+    value = bytes_per_step * args.steps / wall_s / 1e9
+    curve = []
+    all_ms = []
+    for cfg in configs:
+        ms = [r.kernel_ms_event for r in records[cfg.name]]
+        all_ms += ms
+        med = statistics.median(ms)
+        curve.append({"region_gib": cfg.region_bytes // GiB, "gbps": round(cfg.bytes_read / med / 1e6, 1),
+                      "gbps_min": round(cfg.bytes_read / max(ms) / 1e6, 1),
+                      "gbps_max": round(cfg.bytes_read / min(ms) / 1e6, 1),
+                      "pct_of_hbm_peak": round(cfg.bytes_read / med / 1e6 / HBM_PEAK_GBPS * 100, 1),
+                      "kernel_ms": round(med, 4)})
+    bytes_per_launch = configs[0].bytes_read
+    avg_ms = sum(all_ms) / len(all_ms)
+    achieved = bytes_per_launch / avg_ms / 1e6
+    roofline = {"bound": "hbm", "kernel": "rand_read_kernel<32 lanes, 1 dword, ring 8, DPP broadcast>",
+                "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                "traffic": read_traffic_file(os.path.join(ROOT, "profiles", "rand_read_region_sweep_pmc.txt")),
+                "bytes_per_launch": bytes_per_launch, "avg_launch_ms": round(avg_ms, 4),
+                "launches_timed": len(all_ms)}
+
+    out = {
+        "metric": "random-line read GB/s vs region size (1-256 GiB); % of 8 TB/s HBM peak",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(wall_s / args.steps * 1e3, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "u32", "data": "synthetic",
+        "config": {"workload": "region-size sweep (configs[1]): per region size one launch with all "
+                               f"{n_cus * wl.WAVES_PER_CU} wave slots occupied, each 32-lane logical wave reading "
+                               "4096 uniformly random 128-B lines; regions are prefixes of one filled allocation",
+                   "regions_gib": [c.region_bytes // GiB for c in configs], "line_bytes": 128,
+                   "lanes_per_line": 32, "logical_waves": configs[0].logical_waves,
+                   "iters_per_wave": configs[0].iters_per_wave, "reads_per_launch": configs[0].n_reads,
+                   "allocation_gib": max_gib, "fill_seed": wl.FILL_SEED, "first_read_seed": wl.READ_SEED,
+                   "n_cus": n_cus},
+        "pct_of_hbm_peak": round(value / HBM_PEAK_GBPS * 100, 1),
+        "curve": curve,
+        "gbps_at_largest_region": curve[-1]["gbps"],
+        "fill_gbps": round(max_gib * GiB / fill_s / 1e9, 1),
+        "roofline": roofline,
+    }
+
+    if not args.no_cpu_baseline:
+        # CPU-baseline leg: the oracle as it stands, on the largest sweep point, first timed seed.
+        from oracle import randline as orc
+        cores = len(os.sched_getaffinity(0))
+        picks = [configs[0], configs[len(configs) // 2], configs[-1]]   # smallest, middle, largest region
+        t_all, reads_all, used, match = 0.0, 0, 0, True
+        for cfg in picks:
+            t0 = time.perf_counter()
+            c_all, used = orc.checksum_ex(cfg.region_bytes, cfg.line_bytes, cfg.logical_waves, cfg.iters_per_wave,
+                                          cfg.fill_seed, wl.READ_SEED, n_threads=cores)
+            t_all += time.perf_counter() - t0
+            reads_all += cfg.n_reads
+            match = match and c_all == records[cfg.name][0].checksum
+        cfg = configs[-1]
+        sample_waves = cfg.logical_waves // 4           # single thread: a quarter of one point's waves
+        t0 = time.perf_counter()
+        orc.checksum(cfg.region_bytes, cfg.line_bytes, sample_waves, cfg.iters_per_wave, cfg.fill_seed,
+                     wl.READ_SEED, n_threads=1)
+        t_one = time.perf_counter() - t0
+        # materialised mode: real random reads from a 2 GiB host buffer (host-DRAM analogue)
+        mat_bytes = 2 * GiB
+        host = orc.fill_buffer(mat_bytes, cfg.fill_seed)
+        mat_waves = 16384
+        t0 = time.perf_counter()
+        orc.checksum_materialised(host, cfg.line_bytes, mat_waves, 1024, wl.READ_SEED, n_threads=cores)
+        t_mat = time.perf_counter() - t0
+        del host
+        out["cpu_baseline"] = {
+            "value": round(reads_all * cfg.line_bytes / t_all / 1e9, 3), "unit": "GB/s", "cores": used,
+            "kind": "oracle",
+            "sample": f"recompute mode, sweep points {[c.name for c in picks]}: all {cfg.logical_waves} logical "
+                      f"waves x {cfg.iters_per_wave} reads of 128 B each (same arguments as the GPU launches of the "
+                      f"first timed step), {used} threads, {t_all:.2f} s wall",
+            "reads_per_s": round(reads_all / t_all),
+            "single_thread_gbps": round(sample_waves * cfg.iters_per_wave * cfg.line_bytes / t_one / 1e9, 3),
+            "single_thread_sample": f"{sample_waves} logical waves of {cfg.name}, {t_one:.2f} s",
+            "materialised_gbps": round(mat_waves * 1024 * cfg.line_bytes / t_mat / 1e9, 3),
+            "materialised_sample": f"{mat_waves} logical waves x 1024 reads from a {mat_bytes // GiB} GiB host buffer, "
+                                   f"{cores} threads, {t_mat:.2f} s",
+            "checksum_matches_gpu": bool(match),
+        }
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -91,6 +91,10 @@ typedef struct {
 #define RR_BCAST_DPP 2      /* DPP row broadcast, 16 iterations generated per batch   */
 #define RR_BCAST_READLANE 3 /* v_readlane to scalar registers (+ select per half)     */
 
+#define RR_NT_DEFAULT 0 /* = RR_NT_ON: fastest measured on MI355X at every region size */
+#define RR_NT_ON 1      /* loads carry the non-temporal hint (lines are not expected to be reused) */
+#define RR_NT_OFF 2     /* plain loads */
+
 #define RR_MODE_AUTO 0
 #define RR_MODE_FLAT 1   /* one hardware wave per 64 lanes of logical waves, fixed by block index */
 #define RR_MODE_TICKET 2 /* resident waves claim logical waves of their CU's group from counters  */
@@ -101,12 +105,15 @@ typedef struct {
  */
 typedef struct {
     uint32_t block_threads;  /* 64, 128 or 256 (default 256)                                      */
-    uint32_t grid_blocks;    /* ticket mode: workgroups per launch (default: 2 x resident capacity;
-                                pinned runs: 64 x).  Flat mode ignores it.                        */
+    uint32_t grid_blocks;    /* ticket mode: workgroups per launch (default: the resident capacity;
+                                pinned runs: 64 x that).  Flat mode ignores it.                   */
     uint32_t unroll;         /* loads kept in flight per wave: 2, 4, 8 or 16 (default by line width) */
     uint32_t mode;           /* RR_MODE_*                                                          */
     uint32_t bcast;          /* RR_BCAST_*                                                         */
-    uint32_t nontemporal;    /* 1: loads carry the non-temporal hint                               */
+    uint32_t nontemporal;    /* RR_NT_*                                                            */
+    uint32_t chunk_iters;    /* iterations of a logical wave executed per ticket / hardware wave: a
+                                multiple of 64; 0 = default (flat: all of them; ticketed: 512)     */
+    uint32_t reserved;       /* must be 0                                                          */
     uint64_t first_wave;     /* id of the first logical wave (default 0); multiple of n_groups     */
     uint16_t *placement_out; /* host [W] or NULL: dense CU id that executed each logical wave      */
     uint32_t *cu_waves_out;  /* host [n_cus] or NULL: working hardware waves counted per CU        */
@@ -162,6 +169,24 @@ int rr_probe_pair(const void *region, uint64_t region_bytes, uint32_t cu_a, uint
 int rr_probe_cus(const void *region, uint64_t region_bytes, const uint32_t *cus, uint32_t n_target,
                  uint64_t n_reads, uint32_t iters_per_wave, uint64_t read_seed, void *hip_stream,
                  const rr_launch_opts_t *opts, rr_result_t *out);
+
+/*
+ * Streaming read of the whole region: every 32-bit word is read once, in address
+ * order per wave (the sequential access the paper expects to beat random lines,
+ * Sec. 2.1).  region: device, 16-byte aligned; region_bytes: multiple of 16.
+ * out->checksum = wrapping sum of all words; throughput = region_bytes / time.
+ * This is the measured ceiling against which the random-line rate is judged.
+ */
+int rr_seq_read(const void *region, uint64_t region_bytes, void *hip_stream, rr_result_t *out);
+
+/*
+ * Plain device-to-device copy kernel of exactly known traffic (bytes read =
+ * bytes written = bytes); used to calibrate profiler byte counters and as a
+ * read+write streaming figure.  dst, src: device, 16-byte aligned, not
+ * overlapping; bytes: multiple of 16.  *kernel_ms (host, may be NULL) receives
+ * the HIP-event time of the kernel.
+ */
+int rr_copy(void *dst, const void *src, uint64_t bytes, void *hip_stream, double *kernel_ms);
 
 /*
  * Groups of CUs from the pair heatmap (paper Sec. 2.2, Fig. 2 -> Fig. 3; the

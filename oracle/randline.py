@@ -40,6 +40,8 @@ def lib():
                                                 u64, i32, C.POINTER(u64), C.POINTER(i32)]
         L.rlo_fill_words.restype = i32
         L.rlo_fill_words.argtypes = [u64, u64, u64, C.POINTER(u32)]
+        L.rlo_sum_words.restype = i32
+        L.rlo_sum_words.argtypes = [u64, u64, u64, i32, C.POINTER(u64)]
         _lib = L
     return _lib
 
@@ -129,4 +131,13 @@ def checksum_materialised(buf: np.ndarray, line_bytes: int, W: int, I: int, read
                                          C.byref(out), C.byref(used))
     if rc != 0:
         raise ValueError("rlo_checksum_materialised: invalid argument")
+    return int(out.value)
+
+
+def sum_words(fill_seed: int, first_word: int, n_words: int, n_threads: int = 1) -> int:
+    """Wrapping 64-bit sum of a range of fill words (the sequential-read checksum)."""
+    out = C.c_uint64(0)
+    rc = lib().rlo_sum_words(fill_seed, first_word, n_words, n_threads, C.byref(out))
+    if rc != 0:
+        raise ValueError("rlo_sum_words: invalid argument")
     return int(out.value)

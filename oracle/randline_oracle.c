@@ -219,3 +219,22 @@ int rlo_fill_words(uint64_t fill_seed, uint64_t first_word, uint64_t n, uint32_t
     for (uint64_t k = 0; k < n; ++k) out[k] = rlo_fill_word(fill_seed, first_word + k);
     return RLO_OK;
 }
+
+/*
+ * Streaming read: wrapping 64-bit sum of the 32-bit words [first_word,
+ * first_word+n_words) of a region filled with fill_seed (zero extended).  The
+ * definition of the sequential-read checksum; threads only split the range.
+ */
+int rlo_sum_words(uint64_t fill_seed, uint64_t first_word, uint64_t n_words, int n_threads,
+                  uint64_t *sum) {
+    if (sum == NULL) return RLO_EINVAL;
+    uint64_t total = 0;
+#ifdef _OPENMP
+    if (n_threads < 1) n_threads = 1;
+#pragma omp parallel for num_threads(n_threads) reduction(+ : total) schedule(static)
+#endif
+    for (int64_t k = 0; k < (int64_t)n_words; ++k)
+        total += (uint64_t)rlo_fill_word(fill_seed, first_word + (uint64_t)k);
+    *sum = total;
+    return RLO_OK;
+}

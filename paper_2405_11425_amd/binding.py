@@ -18,6 +18,7 @@ RR_OK, RR_EINVAL, RR_EHIP, RR_EPLACE = 0, -1, -2, -3
 RR_CU_EXCLUDED = 0xFFFF
 BCAST_DEFAULT, BCAST_LDS, BCAST_DPP, BCAST_READLANE = 0, 1, 2, 3
 MODE_AUTO, MODE_FLAT, MODE_TICKET = 0, 1, 2
+NT_DEFAULT, NT_ON, NT_OFF = 0, 1, 2
 
 
 class RandlineError(RuntimeError):
@@ -43,11 +44,11 @@ class _Result(C.Structure):
 class _Opts(C.Structure):
     _fields_ = [("block_threads", C.c_uint32), ("grid_blocks", C.c_uint32), ("unroll", C.c_uint32),
                 ("mode", C.c_uint32), ("bcast", C.c_uint32), ("nontemporal", C.c_uint32),
-                ("first_wave", C.c_uint64), ("placement_out", C.POINTER(C.c_uint16)),
+                ("chunk_iters", C.c_uint32), ("reserved", C.c_uint32), ("first_wave", C.c_uint64), ("placement_out", C.POINTER(C.c_uint16)),
                 ("cu_waves_out", C.POINTER(C.c_uint32))]
 
 
-EXPORTS = ["rr_enumerate_cus", "rr_fill", "rr_rand_read", "rr_probe_pair", "rr_probe_cus",
+EXPORTS = ["rr_enumerate_cus", "rr_fill", "rr_rand_read", "rr_probe_pair", "rr_probe_cus", "rr_seq_read", "rr_copy",
            "rr_groups_from_heatmap", "rr_shutdown", "rr_strerror", "rr_last_error"]
 
 _lib = None
@@ -64,6 +65,12 @@ def lib():
         path = library_path()
         if not os.path.exists(path):
             _build.build()
+        # PyTorch ships its own HIP runtime under the same soname.  Import it first so that this
+        # library binds to that copy: two HIP runtimes in one process cannot both own the device.
+        try:
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         L = C.CDLL(path)
         u64, u32, vp = C.c_uint64, C.c_uint32, C.c_void_p
         L.rr_enumerate_cus.restype = C.c_int
@@ -78,6 +85,10 @@ def lib():
         L.rr_probe_cus.restype = C.c_int
         L.rr_probe_cus.argtypes = [vp, u64, C.POINTER(u32), u32, u64, u32, u64, vp, C.POINTER(_Opts),
                                    C.POINTER(_Result)]
+        L.rr_seq_read.restype = C.c_int
+        L.rr_seq_read.argtypes = [vp, u64, vp, C.POINTER(_Result)]
+        L.rr_copy.restype = C.c_int
+        L.rr_copy.argtypes = [vp, vp, u64, vp, C.POINTER(C.c_double)]
         L.rr_groups_from_heatmap.restype = C.c_int
         L.rr_groups_from_heatmap.argtypes = [C.POINTER(C.c_double), u32, C.POINTER(C.c_double), C.c_double,
                                              C.POINTER(C.c_uint16), C.POINTER(u32), C.POINTER(u32),
@@ -157,8 +168,8 @@ class ReadResult:
 
 
 def _opts(W: int, n_cus_hint: int, block_threads=0, grid_blocks=0, unroll=0, mode=0, bcast=0,
-          nontemporal=0, first_wave=0, want_placement=False, want_cu_waves=False):
-    o = _Opts(block_threads, grid_blocks, unroll, mode, bcast, nontemporal, first_wave, None, None)
+          nontemporal=0, chunk_iters=0, first_wave=0, want_placement=False, want_cu_waves=False):
+    o = _Opts(block_threads, grid_blocks, unroll, mode, bcast, nontemporal, chunk_iters, 0, first_wave, None, None)
     placement = cu_waves = None
     if want_placement:
         placement = np.full(max(W, 1), 0xFFFF, dtype=np.uint16)
@@ -221,6 +232,23 @@ def probe_pair(region, cu_a: int, cu_b: int, n_reads: int, iters_per_wave: int, 
                                C.byref(o), C.byref(res)))
     return ReadResult(int(res.checksum), res.kernel_ms_event, res.kernel_ms_device, int(res.waves_run),
                       int(res.launches))
+
+
+def seq_read(region, region_bytes: Optional[int] = None, stream=None) -> ReadResult:
+    ptr, nbytes = _region(region, region_bytes)
+    res = _Result()
+    _check(lib().rr_seq_read(ptr, nbytes, _stream(stream), C.byref(res)))
+    return ReadResult(int(res.checksum), res.kernel_ms_event, res.kernel_ms_device, int(res.waves_run),
+                      int(res.launches))
+
+
+def copy(dst, src, nbytes: Optional[int] = None, stream=None) -> float:
+    """Device-to-device copy with the library's plain copy kernel; returns the kernel time in ms."""
+    dptr, dbytes = _region(dst, nbytes)
+    sptr, sbytes = _region(src, nbytes)
+    ms = C.c_double(0.0)
+    _check(lib().rr_copy(dptr, sptr, min(dbytes, sbytes), _stream(stream), C.byref(ms)))
+    return float(ms.value)
 
 
 def groups_from_heatmap(T: np.ndarray, singles: Optional[np.ndarray] = None, min_gap: float = 0.05):

@@ -40,22 +40,118 @@ __global__ void __launch_bounds__(64) enumerate_kernel(Scratch *s, u32 naps) {
     for (u32 i = 0; i < naps; ++i) __builtin_amdgcn_s_sleep(100);
 }
 
-// what: bit 0 head (checksum, timestamps, wave count); bit 1 tickets; bit 2 per-CU counts; bit 3 key marks
+// Streaming counterpart of the random read: every 32-bit word of the region is
+// read once, 16 bytes per lane and load, consecutive lanes on consecutive
+// addresses, grid-stride, eight loads in flight per lane (the sequential reads
+// the paper expects to be faster than random lines, Sec. 2.1).  Same checksum
+// convention: wrapping 64-bit sum of zero-extended words, one atomic per wave.
+__global__ void __launch_bounds__(256) seq_read_kernel(const u32x4 *src, u64 n_vec, Scratch *s) {
+    typedef const u32x4 __attribute__((address_space(1))) *gptr;
+    gptr g = (gptr)(u64)src;
+    const u64 stride = (u64)gridDim.x * blockDim.x;
+    u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x;
+    const u64 t0 = clock_ticks();
+    Acc acc{0u, 0u};
+    for (; i + 7 * stride < n_vec; i += 8 * stride) {
+        u32x4 v[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) v[k] = __builtin_nontemporal_load(g + i + k * stride);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) acc.add(v[k]);
+    }
+    for (; i < n_vec; i += stride) acc.add(__builtin_nontemporal_load(g + i));
+    const u64 total = wave_sum(acc.value());
+    const u64 t1 = clock_ticks();
+    if ((threadIdx.x & 63) == 0) {
+        Cell *c = &s->cells[(blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6)) & (kNumCells - 1)];
+        atomicAdd(&c->sum, total);
+        atomicMin(&c->t_min, t0);
+        atomicMax(&c->t_max, t1);
+        atomicAdd(&c->waves, 1u);
+    }
+}
+
+// Plain copy, 16 bytes per lane and step, grid-stride: a kernel of exactly known
+// HBM traffic (bytes read = bytes written = n_vec * 16).
+__global__ void __launch_bounds__(256) copy_kernel(u32x4 *dst, const u32x4 *src, u64 n_vec) {
+    const u64 stride = (u64)gridDim.x * blockDim.x;
+    for (u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x; i < n_vec; i += stride)
+        __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
+}
+
+// what: bit 0 head and result cells; bit 1 ticket counters; bit 2 per-CU wave counts; bit 3 key marks
 __global__ void __launch_bounds__(256) reset_kernel(Scratch *s, u32 what) {
     const u32 t = threadIdx.x;
-    if ((what & 1u) && t == 0) {
-        s->checksum = 0;
-        s->t_min = ~0ull;
-        s->t_max = 0;
-        s->waves_run = 0;
-        s->pad = 0;
+    if (what & 1u) {
+        if (t == 0) {
+            s->checksum = 0;
+            s->t_min = ~0ull;
+            s->t_max = 0;
+            s->waves_run = 0;
+            s->unfinished = 0;
+        }
+        for (u32 i = t; i < kNumCells; i += blockDim.x) {
+            s->cells[i].sum = 0;
+            s->cells[i].t_min = ~0ull;
+            s->cells[i].t_max = 0;
+            s->cells[i].waves = 0;
+        }
     }
     if (what & 2u)
-        for (u32 i = t; i < kMaxGroups; i += blockDim.x) s->tickets[i] = 0;
+        for (u32 i = t; i < kMaxCus; i += blockDim.x) s->tickets[i * kTicketStride] = 0;
     if (what & 4u)
         for (u32 i = t; i < kMaxCus; i += blockDim.x) s->cu_waves[i] = 0;
     if (what & 8u)
         for (u32 i = t; i < kNumKeys; i += blockDim.x) s->key_seen[i] = 0;
+}
+
+// After a read launch (one block of 256 threads): fold the result cells into
+// the head, leave the cells cleared for the next launch, and count the compute
+// units whose share of tickets has not been fully claimed yet.
+__global__ void __launch_bounds__(256) finish_kernel(Scratch *s, const Tables *tb, u32 n_cus, u32 cpw,
+                                                     u32 ticket_mode) {
+    __shared__ u64 sh_sum[256], sh_min[256], sh_max[256];
+    __shared__ u32 sh_waves[256], sh_open[256];
+    const u32 t = threadIdx.x;
+    u64 sum = 0, tmin = ~0ull, tmax = 0;
+    u32 waves = 0, open = 0;
+    for (u32 i = t; i < kNumCells; i += 256) {
+        Cell *c = &s->cells[i];
+        sum += c->sum;
+        tmin = c->t_min < tmin ? c->t_min : tmin;
+        tmax = c->t_max > tmax ? c->t_max : tmax;
+        waves += c->waves;
+        c->sum = 0;
+        c->t_min = ~0ull;
+        c->t_max = 0;
+        c->waves = 0;
+    }
+    if (ticket_mode)
+        for (u32 c = t; c < n_cus; c += 256)
+            if (s->tickets[c * kTicketStride] < tb->cu_unit_count[c] * cpw) open++;
+    sh_sum[t] = sum;
+    sh_min[t] = tmin;
+    sh_max[t] = tmax;
+    sh_waves[t] = waves;
+    sh_open[t] = open;
+    __syncthreads();
+    for (u32 step = 128; step > 0; step >>= 1) {
+        if (t < step) {
+            sh_sum[t] += sh_sum[t + step];
+            sh_min[t] = sh_min[t + step] < sh_min[t] ? sh_min[t + step] : sh_min[t];
+            sh_max[t] = sh_max[t + step] > sh_max[t] ? sh_max[t + step] : sh_max[t];
+            sh_waves[t] += sh_waves[t + step];
+            sh_open[t] += sh_open[t + step];
+        }
+        __syncthreads();
+    }
+    if (t == 0) {
+        s->checksum = sh_sum[0];
+        s->t_min = sh_min[0];
+        s->t_max = sh_max[0];
+        s->waves_run = sh_waves[0];
+        s->unfinished = sh_open[0];
+    }
 }
 
 }  // namespace rr
@@ -100,19 +196,17 @@ extern "C" const char *rr_last_error(void) { return g_last_error.c_str(); }
 
 namespace {
 
-struct HostHead {  // mirror of the head of Scratch + tickets, in pinned memory
+struct HostHead {  // mirror of the head of Scratch, in pinned memory
     u64 checksum, t_min, t_max;
-    u32 waves_run, pad;
-    u32 tickets[kMaxGroups];
+    u32 waves_run, unfinished;
     u32 cu_waves[kMaxCus];
 };
 
 struct DeviceState {
     bool ready = false;
     Scratch *scratch = nullptr;
-    u16 *group_of_key = nullptr;  // [kNumKeys]
-    u16 *dense_of_key = nullptr;  // [kNumKeys]
-    u32 *window_base = nullptr;   // [kMaxGroups]
+    Tables *tables = nullptr;       // device
+    Tables *tables_host = nullptr;  // pinned staging copy
     u16 *placement = nullptr;
     size_t placement_cap = 0;
     HostHead *head = nullptr;     // pinned
@@ -162,9 +256,6 @@ int enumerate(DeviceState &st, hipStream_t stream) {
         st.dense_of_key_host[k] = (u16)st.cus.size();
         st.cus.push_back(c);
     }
-    HIP_TRY(hipMemcpyAsync(st.dense_of_key, st.dense_of_key_host.data(), kNumKeys * sizeof(u16),
-                           hipMemcpyHostToDevice, stream));
-    HIP_TRY(hipStreamSynchronize(stream));
     return RR_OK;
 }
 
@@ -176,9 +267,8 @@ int get_state(hipStream_t stream, DeviceState **out) {
     DeviceState &st = g_state[dev];
     if (!st.ready) {
         if (!st.scratch) HIP_TRY(hipMalloc((void **)&st.scratch, sizeof(Scratch)));
-        if (!st.group_of_key) HIP_TRY(hipMalloc((void **)&st.group_of_key, kNumKeys * sizeof(u16)));
-        if (!st.dense_of_key) HIP_TRY(hipMalloc((void **)&st.dense_of_key, kNumKeys * sizeof(u16)));
-        if (!st.window_base) HIP_TRY(hipMalloc((void **)&st.window_base, kMaxGroups * sizeof(u32)));
+        if (!st.tables) HIP_TRY(hipMalloc((void **)&st.tables, sizeof(Tables)));
+        if (!st.tables_host) HIP_TRY(hipHostMalloc((void **)&st.tables_host, sizeof(Tables), hipHostMallocDefault));
         if (!st.head) HIP_TRY(hipHostMalloc((void **)&st.head, sizeof(HostHead), hipHostMallocDefault));
         if (!st.ev0) HIP_TRY(hipEventCreate(&st.ev0));
         if (!st.ev1) HIP_TRY(hipEventCreate(&st.ev1));
@@ -212,7 +302,8 @@ const Family *find_family(u32 lanes, u32 wdw) {
 struct Plan {
     u64 n_lines = 0, W = 0, first_wave = 0;
     u32 log2_line = 0, lanes = 0, wdw = 0, G = 1, n_windows = 1;
-    u32 block = 256, unroll = 0, bcast = RR_BCAST_DPP, nt = 0, mode = RR_MODE_AUTO, grid_blocks = 0;
+    u32 block = 256, unroll = 0, bcast = RR_BCAST_DPP, nt = 1, mode = RR_MODE_AUTO, grid_blocks = 0;
+    u32 chunk_iters = 0;
     bool pinned = false;
     const Family *family = nullptr;
     kernel_handle kernel = nullptr;
@@ -271,11 +362,14 @@ int make_plan(const void *region, uint64_t region_bytes, uint32_t line_bytes, ui
         if (opts->unroll) pl.unroll = opts->unroll;
         if (opts->bcast > RR_BCAST_READLANE) return fail(RR_EINVAL, "unknown bcast value");
         if (opts->bcast) pl.bcast = opts->bcast;
-        if (opts->nontemporal > 1) return fail(RR_EINVAL, "nontemporal must be 0 or 1");
-        pl.nt = opts->nontemporal;
+        if (opts->nontemporal > RR_NT_OFF) return fail(RR_EINVAL, "nontemporal must be 0, 1 or 2");
+        if (opts->nontemporal) pl.nt = opts->nontemporal == RR_NT_ON ? 1u : 0u;
         if (opts->mode > RR_MODE_TICKET) return fail(RR_EINVAL, "unknown mode value");
         pl.mode = opts->mode;
         pl.grid_blocks = opts->grid_blocks;
+        if (opts->chunk_iters % 64 != 0) return fail(RR_EINVAL, "chunk_iters must be a multiple of 64");
+        if (opts->reserved != 0) return fail(RR_EINVAL, "reserved must be 0");
+        pl.chunk_iters = opts->chunk_iters;
         if (opts->first_wave % pl.G != 0) return fail(RR_EINVAL, "first_wave must be a multiple of n_groups");
         pl.first_wave = opts->first_wave;
     }
@@ -318,24 +412,42 @@ int run_plan(const Plan &pl, const void *region, uint32_t iters, const rr_window
     if (wm && wm->n_cus != n_cus)
         return fail(RR_EINVAL, "window map describes %u compute units, the device has %u", wm->n_cus, n_cus);
 
-    // tables: CU key -> group, group -> first line of its window
+    // tables: CU key -> group and dense id, group -> window, and each CU's share of its group's units
     const u32 lpw = 64 / pl.lanes;
     const u64 L_win = pl.n_lines / pl.n_windows;
     const u64 quota = pl.W / pl.G;
-    std::vector<u16> group_of_key(kNumKeys, kExcluded);
+    const u64 units = (quota + lpw - 1) / lpw;  // per group
+    Tables &tb = *st.tables_host;
+    memset(&tb, 0, sizeof tb);
+    for (u32 k = 0; k < kNumKeys; ++k) {
+        tb.group_of_key[k] = kExcluded;
+        tb.dense_of_key[k] = st.dense_of_key_host[k];
+    }
     std::vector<u32> cus_in_group(pl.G, 0);
     for (u32 c = 0; c < n_cus; ++c) {
-        u16 g = wm ? wm->group_of_cu[c] : 0;
-        group_of_key[key_of(st.cus[c])] = g;
+        const u16 g = wm ? wm->group_of_cu[c] : 0;
+        tb.group_of_key[key_of(st.cus[c])] = g;
         if (g != kExcluded) cus_in_group[g]++;
     }
-    std::vector<u32> window_base(pl.G, 0);
     for (u32 g = 0; g < pl.G; ++g) {
-        if (wm) window_base[g] = (u32)(wm->window_of_group[g] * L_win);
         if (cus_in_group[g] == 0) return fail(RR_EPLACE, "group %u has no compute unit", g);
+        tb.window_base[g] = wm ? (u32)(wm->window_of_group[g] * L_win) : 0u;
+        tb.group_begin[g + 1] = tb.group_begin[g] + cus_in_group[g];
     }
-    HIP_TRY(hipMemcpyAsync(st.group_of_key, group_of_key.data(), kNumKeys * sizeof(u16), hipMemcpyHostToDevice, stream));
-    HIP_TRY(hipMemcpyAsync(st.window_base, window_base.data(), pl.G * sizeof(u32), hipMemcpyHostToDevice, stream));
+    {
+        std::vector<u32> fill_pos(pl.G, 0);
+        for (u32 c = 0; c < n_cus; ++c) {  // ascending dense id within each group
+            const u16 g = wm ? wm->group_of_cu[c] : 0;
+            if (g == kExcluded) continue;
+            const u32 k = fill_pos[g]++, n = cus_in_group[g];
+            tb.group_cus[tb.group_begin[g] + k] = (u16)c;
+            tb.cu_pos[c] = (u16)k;
+            const u64 b0 = units * k / n, b1 = units * (k + 1) / n;  // even split of the group's units
+            tb.cu_unit_begin[c] = (u32)b0;
+            tb.cu_unit_count[c] = (u32)(b1 - b0);
+        }
+    }
+    HIP_TRY(hipMemcpyAsync(st.tables, st.tables_host, sizeof(Tables), hipMemcpyHostToDevice, stream));
     const bool want_placement = opts && opts->placement_out;
     if (want_placement && st.placement_cap < pl.W) {
         HIP_TRY(hipStreamSynchronize(stream));
@@ -354,38 +466,46 @@ int run_plan(const Plan &pl, const void *region, uint32_t iters, const rr_window
     p.first_wave = pl.first_wave;
     p.quota = quota;
     p.iters = iters;
+    // flat launches default to one hardware wave per whole logical wave (pair); ticketed ones to
+    // chunks of 512 iterations so that resident waves finish together
+    u32 chunk = pl.chunk_iters ? pl.chunk_iters : (pl.mode == RR_MODE_TICKET ? 512u : iters);
+    if (chunk > iters) chunk = iters;
+    p.chunk_iters = chunk;
+    p.chunks_per_wave = (iters + chunk - 1) / chunk;
     p.n_groups = pl.G;
     p.ticket_mode = pl.mode == RR_MODE_TICKET ? 1u : 0u;
     p.log2_line = pl.log2_line;
     p.red = make_reducer(L_win);
     p.scratch = st.scratch;
-    p.group_of_key = st.group_of_key;
-    p.dense_of_key = st.dense_of_key;
-    p.window_base = st.window_base;
+    p.tables = st.tables;
     p.placement = want_placement ? st.placement : nullptr;
 
     const u32 waves_per_block = pl.block / 64;
-    int blocks_per_cu = 0;
-    HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks_per_cu, pl.kernel, (int)pl.block, 0));
-    if (blocks_per_cu < 1) blocks_per_cu = 1;
+    // a CU holds at most 32 waves (8 per SIMD); workgroups beyond what really fits queue up,
+    // find every share claimed and leave at once
+    const u32 blocks_per_cu = 32 / waves_per_block;
     u64 grid;
     if (p.ticket_mode) {
-        grid = pl.grid_blocks ? pl.grid_blocks : (u64)blocks_per_cu * n_cus * (pl.pinned ? 64u : 2u);
+        grid = pl.grid_blocks ? pl.grid_blocks : (u64)blocks_per_cu * n_cus * (pl.pinned ? 64u : 1u);
     } else {
-        const u64 hw_waves = (pl.W + lpw - 1) / lpw;
+        const u64 hw_waves = (pl.W + lpw - 1) / lpw * p.chunks_per_wave;
         grid = (hw_waves + waves_per_block - 1) / waves_per_block;
     }
     if (grid == 0 || grid > 0x7FFFFFFFull) return fail(RR_EINVAL, "launch of %llu workgroups is out of range", grid);
 
+    if (units * p.chunks_per_wave >= (1ull << 31))
+        return fail(RR_EINVAL, "too many tickets per group (%llu)", units * p.chunks_per_wave);
     hipLaunchKernelGGL(reset_kernel, dim3(1), dim3(256), 0, stream, st.scratch, 1u | 2u | 4u);
     HIP_TRY(hipGetLastError());
-    const u32 tickets_needed = (u32)((quota + lpw - 1) / lpw);
     const int max_launches = p.ticket_mode ? 32 : 1;
     void *args[] = {(void *)&p};
     for (int launch = 0;; ++launch) {
         HIP_TRY(hipEventRecord(st.ev0, stream));
         HIP_TRY(hipLaunchKernel(pl.kernel, dim3((u32)grid), dim3(pl.block), args, 0, stream));
         HIP_TRY(hipEventRecord(st.ev1, stream));
+        hipLaunchKernelGGL(finish_kernel, dim3(1), dim3(256), 0, stream, st.scratch, st.tables, n_cus,
+                           p.chunks_per_wave, p.ticket_mode);
+        HIP_TRY(hipGetLastError());
         HIP_TRY(hipMemcpyAsync(st.head, st.scratch, sizeof(HostHead), hipMemcpyDeviceToHost, stream));
         HIP_TRY(hipStreamSynchronize(stream));
         float ms = 0.f;
@@ -396,15 +516,10 @@ int run_plan(const Plan &pl, const void *region, uint32_t iters, const rr_window
         res.waves_run += st.head->waves_run;
         if (st.head->waves_run && st.head->t_max >= st.head->t_min)
             res.kernel_ms_device += (double)(st.head->t_max - st.head->t_min) / (double)st.wall_khz;
-        bool done = true;
-        if (p.ticket_mode)
-            for (u32 g = 0; g < pl.G; ++g)
-                if (st.head->tickets[g] < tickets_needed) done = false;
-        if (done) break;
+        if (!p.ticket_mode || st.head->unfinished == 0) break;
         if (launch + 1 >= max_launches)
-            return fail(RR_EPLACE, "after %d launches some group still has unclaimed logical waves", max_launches);
-        hipLaunchKernelGGL(reset_kernel, dim3(1), dim3(256), 0, stream, st.scratch, 1u);
-        HIP_TRY(hipGetLastError());
+            return fail(RR_EPLACE, "after %d launches %u compute units' shares still have unclaimed tickets",
+                        max_launches, st.head->unfinished);
     }
     if (want_placement) {
         HIP_TRY(hipMemcpyAsync(opts->placement_out, st.placement, pl.W * sizeof(u16), hipMemcpyDeviceToHost, stream));
@@ -503,6 +618,79 @@ extern "C" int rr_probe_pair(const void *region, uint64_t region_bytes, uint32_t
     return rr_probe_cus(region, region_bytes, cus, 2, n_reads, iters_per_wave, read_seed, hip_stream, opts, out);
 }
 
+extern "C" int rr_seq_read(const void *region, uint64_t region_bytes, void *hip_stream, rr_result_t *out) {
+    if (!out) return fail(RR_EINVAL, "out is NULL");
+    if (!region) return fail(RR_EINVAL, "region is NULL");
+    if ((uintptr_t)region % 16 != 0) return fail(RR_EINVAL, "region is not 16-byte aligned");
+    if (region_bytes % 16 != 0) return fail(RR_EINVAL, "region_bytes must be a multiple of 16");
+    rr_result_t res;
+    memset(&res, 0, sizeof res);
+    if (region_bytes == 0) {
+        *out = res;
+        return RR_OK;
+    }
+    hipStream_t stream = (hipStream_t)hip_stream;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    DeviceState *st = nullptr;
+    int rc = get_state(stream, &st);
+    if (rc != RR_OK) return rc;
+    const u64 n_vec = region_bytes / 16;
+    int blocks_per_cu = 0;
+    HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks_per_cu, (const void *)seq_read_kernel, 256, 0));
+    if (blocks_per_cu < 1) blocks_per_cu = 1;
+    u64 blocks = (n_vec + 255) / 256;
+    const u64 cap = (u64)blocks_per_cu * st->cus.size();
+    if (blocks > cap) blocks = cap;
+    hipLaunchKernelGGL(reset_kernel, dim3(1), dim3(256), 0, stream, st->scratch, 1u);
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipEventRecord(st->ev0, stream));
+    hipLaunchKernelGGL(seq_read_kernel, dim3((u32)blocks), dim3(256), 0, stream, (const u32x4 *)region, n_vec,
+                       st->scratch);
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipEventRecord(st->ev1, stream));
+    hipLaunchKernelGGL(finish_kernel, dim3(1), dim3(256), 0, stream, st->scratch, st->tables, 0u, 1u, 0u);
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipMemcpyAsync(st->head, st->scratch, 32, hipMemcpyDeviceToHost, stream));
+    HIP_TRY(hipStreamSynchronize(stream));
+    float ms = 0.f;
+    HIP_TRY(hipEventElapsedTime(&ms, st->ev0, st->ev1));
+    res.checksum = st->head->checksum;
+    res.kernel_ms_event = ms;
+    res.kernel_ms_device = (double)(st->head->t_max - st->head->t_min) / (double)st->wall_khz;
+    res.waves_run = st->head->waves_run;
+    res.launches = 1;
+    *out = res;
+    return RR_OK;
+}
+
+extern "C" int rr_copy(void *dst, const void *src, uint64_t bytes, void *hip_stream, double *kernel_ms) {
+    if (!dst || !src) return fail(RR_EINVAL, "dst or src is NULL");
+    if ((uintptr_t)dst % 16 != 0 || (uintptr_t)src % 16 != 0 || bytes % 16 != 0)
+        return fail(RR_EINVAL, "dst, src and bytes must be multiples of 16");
+    const uintptr_t d = (uintptr_t)dst, c = (uintptr_t)src;
+    if (d < c + bytes && c < d + bytes && bytes > 0) return fail(RR_EINVAL, "dst and src overlap");
+    if (kernel_ms) *kernel_ms = 0.0;
+    if (bytes == 0) return RR_OK;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    DeviceState *st = nullptr;
+    int rc = get_state(stream, &st);
+    if (rc != RR_OK) return rc;
+    const u64 n_vec = bytes / 16;
+    u64 blocks = (n_vec + 255) / 256;
+    const u64 cap = (u64)st->cus.size() * 8;
+    if (blocks > cap) blocks = cap;
+    HIP_TRY(hipEventRecord(st->ev0, stream));
+    hipLaunchKernelGGL(copy_kernel, dim3((u32)blocks), dim3(256), 0, stream, (u32x4 *)dst, (const u32x4 *)src, n_vec);
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipEventRecord(st->ev1, stream));
+    HIP_TRY(hipStreamSynchronize(stream));
+    float ms = 0.f;
+    HIP_TRY(hipEventElapsedTime(&ms, st->ev0, st->ev1));
+    if (kernel_ms) *kernel_ms = ms;
+    return RR_OK;
+}
+
 extern "C" int rr_shutdown(void) {
     std::lock_guard<std::mutex> lock(g_mutex);
     int current = 0;
@@ -513,9 +701,8 @@ extern "C" int rr_shutdown(void) {
         if (hipSetDevice(d) != hipSuccess) continue;
         (void)hipDeviceSynchronize();
         if (st.scratch) (void)hipFree(st.scratch);
-        if (st.group_of_key) (void)hipFree(st.group_of_key);
-        if (st.dense_of_key) (void)hipFree(st.dense_of_key);
-        if (st.window_base) (void)hipFree(st.window_base);
+        if (st.tables) (void)hipFree(st.tables);
+        if (st.tables_host) (void)hipHostFree(st.tables_host);
         if (st.placement) (void)hipFree(st.placement);
         if (st.head) (void)hipHostFree(st.head);
         if (st.ev0) (void)hipEventDestroy(st.ev0);

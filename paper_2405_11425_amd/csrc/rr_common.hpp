@@ -17,16 +17,45 @@ constexpr u32 kKeyBits = 12;  // xcc[11:8] se[7:5] sh[4] cu[3:0]
 constexpr u32 kNumKeys = 1u << kKeyBits;
 constexpr u16 kExcluded = 0xFFFFu;
 
-// Device scratch, one per GPU.  The head is copied back after every launch.
+constexpr u32 kNumCells = 4096;     // result cells, one 128-byte line each
+constexpr u32 kTicketStride = 32;   // u32 slots between two CUs' ticket counters (one 128-byte line each)
+
+// Same-address device atomics retire at roughly one per 12 ns on this GPU, so
+// nothing that every wave touches may live at one address: results go to one
+// of kNumCells cells chosen by the wave's launch index, ticket counters are per
+// compute unit and each sits in a cache line of its own.
+struct Cell {
+    u64 sum;     // wrapping sum of the words read by the waves that hashed here
+    u64 t_min;   // earliest start of a working wave (constant-rate clock ticks)
+    u64 t_max;   // latest end of a working wave
+    u32 waves;   // working hardware waves
+    u32 pad[25];
+};
+static_assert(sizeof(Cell) == 128, "one cell per 128-byte line");
+
+// Device scratch, one per GPU.  The head (up to cu_waves) is copied back after every launch.
 struct Scratch {
-    u64 checksum;              // wrapping sum, one atomic add per working wave
-    u64 t_min;                 // earliest start of a working wave (constant-rate clock ticks)
-    u64 t_max;                 // latest end of a working wave
-    u32 waves_run;             // working hardware waves
-    u32 pad;
-    u32 tickets[kMaxGroups];   // next unclaimed ticket of each group
+    u64 checksum;              // filled by finish_kernel from the cells
+    u64 t_min;
+    u64 t_max;
+    u32 waves_run;
+    u32 unfinished;            // ticket mode: compute units whose share is not yet fully claimed
     u32 cu_waves[kMaxCus];     // working hardware waves per dense CU id
+    u32 tickets[kMaxCus * kTicketStride];  // next unclaimed ticket of each CU's share
     u32 key_seen[kNumKeys];    // CU enumeration: 1 if a workgroup ran on the CU with this key
+    Cell cells[kNumCells];
+};
+
+// Per-call lookup tables, built on the host and uploaded in one copy.
+struct Tables {
+    u16 group_of_key[kNumKeys];   // group of the CU with that hardware key, or kExcluded
+    u16 dense_of_key[kNumKeys];   // dense CU id of that key
+    u32 window_base[kMaxGroups];  // first line of each group's window
+    u32 group_begin[kMaxGroups + 1];  // group g's CUs are group_cus[group_begin[g] .. group_begin[g+1])
+    u16 group_cus[kMaxCus];       // dense CU ids sorted by group
+    u16 cu_pos[kMaxCus];          // position of a CU inside its group's list
+    u32 cu_unit_begin[kMaxCus];   // the CU's share of its group's work units: first unit ...
+    u32 cu_unit_count[kMaxCus];   // ... and how many
 };
 
 // Exact h mod L for L <= 2^32: mask when L is a power of two, else a
@@ -44,14 +73,14 @@ struct ReadParams {
     u64 first_wave;           // id of the first logical wave of this call
     u64 quota;                // logical waves per group (flat mode: all of them)
     u32 iters;                // iterations (lines read) per logical wave
+    u32 chunk_iters;          // iterations per ticket (a multiple of 64, or all of them)
+    u32 chunks_per_wave;      // ceil(iters / chunk_iters)
     u32 n_groups;             // G
     u32 ticket_mode;          // 0 flat, 1 ticketed
     u32 log2_line;            // 7, 8 or 9
     Reducer red;              // L = lines per window
     Scratch *scratch;
-    const u16 *group_of_key;  // [kNumKeys] group of the CU with that key, or kExcluded
-    const u16 *dense_of_key;  // [kNumKeys] dense CU id
-    const u32 *window_base;   // [G] first line of the group's window
+    const Tables *tables;
     u16 *placement;           // [W] or null: dense CU id that executed each logical wave
 };
 

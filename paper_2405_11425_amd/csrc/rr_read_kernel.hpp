@@ -90,12 +90,12 @@ __device__ __forceinline__ u64 bcast_addr(u32 alo, u32 ahi, u32 lane, u32 sel4) 
     }
 }
 
-// All `iters` reads of one logical wave per LANES lanes.  wave_seed = sm(read_seed, w)
-// and win_base are per lane (equal within a logical wave).  Returns this lane's
-// share of the logical wave's word sum.
+// Iterations [it0, it0 + iters) of one logical wave per LANES lanes.  wave_seed =
+// sm(read_seed, w) and win_base are per lane (equal within a logical wave).
+// Returns this lane's share of the word sum.
 template <int LANES, int WDW, int U, int BC, int NT>
 __device__ __forceinline__ u64 read_logical_wave(const char *region, u64 wave_seed, u32 win_base,
-                                                 u32 iters, u32 log2_line, const Reducer red,
+                                                 u32 it0, u32 iters, u32 log2_line, const Reducer red,
                                                  u32 lane) {
     typedef typename Vec<WDW>::type V;
     constexpr int ITB = (BC == BC_DPP) ? 16 : LANES;  // iterations generated per batch
@@ -103,7 +103,7 @@ __device__ __forceinline__ u64 read_logical_wave(const char *region, u64 wave_se
     const u32 itl = lane & (ITB - 1);              // iteration of the batch this lane generates
     const u32 sub_bytes = (lane & (LANES - 1)) * (WDW * 4);  // this lane's slice of a line
     const u32 sel4 = (lane & ~(u32)(LANES - 1)) * 4;         // LDS-permute byte index of lane 0 of the half
-    u64 ctr = wave_seed + (u64)(itl + 1) * kGamma;           // SplitMix64 state of iteration itl
+    u64 ctr = wave_seed + ((u64)it0 + itl + 1) * kGamma;     // SplitMix64 state of iteration it0 + itl
     const u64 step = (u64)ITB * kGamma;
 
     auto gen = [&]() -> u64 {
@@ -144,58 +144,127 @@ __device__ __forceinline__ u64 read_logical_wave(const char *region, u64 wave_se
     return acc.value();
 }
 
+// Work distribution.  A "unit" is what one hardware wave carries: a pair of
+// logical waves (LANES = 32) or one (LANES = 64) of one group; a ticket is one
+// chunk of a unit's iterations: ticket = unit * chunks_per_wave + chunk.
+//   flat mode   : the ticket is the wave's launch index; no counters.
+//   ticket mode : the wave reads which CU it is on; the CU's group decides which
+//                 logical waves it may execute and which window they read.
+//                 Each CU owns a contiguous share of its group's units and a
+//                 ticket counter of its own, so claims from different CUs never
+//                 meet on one address.  A wave first drains its own CU's share,
+//                 then scans the other CUs of the group (64 at a time, one lane
+//                 per CU, ballot) and drains whatever shares are still open, so
+//                 every ticket is executed even if some CU received no wave.
 template <int LANES, int WDW, int U, int BC, int NT>
 __global__ void __launch_bounds__(256) rand_read_kernel(const ReadParams p) {
     constexpr u32 LPW = 64 / LANES;  // logical waves per hardware wave
+    constexpr u32 kNone = 0xFFFFFFFFu;
     const u32 lane = threadIdx.x & 63;
     const u32 half = (LANES == 32) ? (lane >> 5) : 0;
     Scratch *s = p.scratch;
+    const Tables *tb = p.tables;
+    const u32 launch_index = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
 
     u32 group = 0, dense = 0;
     if (p.ticket_mode || p.placement) {
         u32 key = cu_key();
-        group = p.group_of_key[key];
-        dense = p.dense_of_key[key];
+        group = tb->group_of_key[key];
+        dense = tb->dense_of_key[key];
         if (group == kExcluded) return;  // a CU that takes no part (pinned runs)
     }
-    const u32 win_base = p.window_base[group];
+    const u32 win_base = tb->window_base[group];
+    const u32 cpw = p.chunks_per_wave;
+
+    auto claim = [&](u32 cu) -> u32 {
+        u32 t = 0;
+        if (lane == 0) t = atomicAdd(&s->tickets[cu * kTicketStride], 1u);
+        return __builtin_amdgcn_readfirstlane(t);
+    };
+    // scan state for stealing: candidates of the current 64-CU window, one per lane
+    const u32 g_begin = tb->group_begin[group];
+    const u32 g_count = tb->group_begin[group + 1] - g_begin;
+    const u32 my_pos = tb->cu_pos[dense];
+    u32 scan_base = 0, cand = 0;
+    unsigned long long open_mask = 0;
+    auto next_victim = [&]() -> u32 {
+        for (;;) {
+            if (open_mask) {
+                const u32 l = (u32)__builtin_ctzll(open_mask);
+                open_mask &= open_mask - 1;
+                return __builtin_amdgcn_readlane(cand, l);
+            }
+            if (scan_base + 1 >= g_count) return kNone;  // the ring minus this CU has g_count-1 entries
+            const u32 pos = scan_base + lane;
+            bool open = false;
+            if (pos + 1 < g_count) {
+                u32 ring = my_pos + 1 + pos;
+                if (ring >= g_count) ring -= g_count;
+                cand = tb->group_cus[g_begin + ring];
+                const u32 taken = __hip_atomic_load(&s->tickets[cand * kTicketStride], __ATOMIC_RELAXED,
+                                                    __HIP_MEMORY_SCOPE_AGENT);
+                open = taken < tb->cu_unit_count[cand] * cpw;
+            }
+            open_mask = __ballot(open);
+            scan_base += 64;
+        }
+    };
+
+    u32 cur = dense;          // CU whose share is being drained
+    u32 unit_begin = 0, limit;
+    u32 ticket;
+    if (p.ticket_mode) {
+        unit_begin = tb->cu_unit_begin[cur];
+        limit = tb->cu_unit_count[cur] * cpw;
+        ticket = claim(cur);
+    } else {
+        limit = (u32)((p.quota + LPW - 1) / LPW) * cpw;
+        ticket = launch_index;
+    }
     u64 acc = 0;
     u64 t0 = 0;
     bool worked = false;
     for (;;) {
-        u64 j0;  // index, within the group, of the logical wave of lanes 0..LANES-1
-        if (p.ticket_mode) {
-            u32 t = 0;
-            if (lane == 0) t = atomicAdd(&s->tickets[group], 1u);
-            t = __builtin_amdgcn_readfirstlane(t);
-            j0 = (u64)t * LPW;
-        } else {
-            j0 = ((u64)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6)) * LPW;
+        if (ticket >= limit) {
+            if (!p.ticket_mode) break;
+            cur = next_victim();
+            if (cur == kNone) break;
+            unit_begin = tb->cu_unit_begin[cur];
+            limit = tb->cu_unit_count[cur] * cpw;
+            ticket = claim(cur);
+            continue;
         }
-        if (j0 >= p.quota) break;
+        const u32 this_ticket = ticket;
+        if (p.ticket_mode) ticket = claim(cur);  // next ticket: its latency hides behind this chunk's loads
+        else ticket = kNone;
+        const u32 unit = this_ticket / cpw;
+        const u32 chunk = this_ticket - unit * cpw;
         if (!worked) {
             worked = true;
             t0 = clock_ticks();
         }
+        const u64 j0 = (u64)(unit_begin + unit) * LPW;  // index, within the group, of the lower logical wave
         u64 j = j0 + half;
         const bool valid = j < p.quota;  // odd quota: the upper half shadows the lower one
         if (!valid) j = j0;
         const u64 w = p.first_wave + group + (u64)p.n_groups * j;
         const u64 wave_seed = mix64(p.read_seed + (w + 1) * kGamma);
-        u64 part = read_logical_wave<LANES, WDW, U, BC, NT>(p.region, wave_seed, win_base, p.iters,
+        const u32 it0 = chunk * p.chunk_iters;
+        const u32 n_it = min(p.chunk_iters, p.iters - it0);
+        u64 part = read_logical_wave<LANES, WDW, U, BC, NT>(p.region, wave_seed, win_base, it0, n_it,
                                                             p.log2_line, p.red, lane);
         acc += valid ? part : 0;
         if (p.placement && valid && (lane & (LANES - 1)) == 0) p.placement[w - p.first_wave] = (u16)dense;
-        if (!p.ticket_mode) break;
     }
     if (!worked) return;
     const u64 total = wave_sum(acc);
     const u64 t1 = clock_ticks();
     if (lane == 0) {
-        atomicAdd(&s->checksum, total);
-        atomicMin(&s->t_min, t0);
-        atomicMax(&s->t_max, t1);
-        atomicAdd(&s->waves_run, 1u);
+        Cell *c = &s->cells[launch_index & (kNumCells - 1)];
+        atomicAdd(&c->sum, total);
+        atomicMin(&c->t_min, t0);
+        atomicMax(&c->t_max, t1);
+        atomicAdd(&c->waves, 1u);
         if (p.ticket_mode || p.placement) atomicAdd(&s->cu_waves[dense], 1u);
     }
 }

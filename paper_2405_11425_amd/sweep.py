@@ -1,0 +1,230 @@
+"""Experiment driver: runs the paper's experiments on one MI355X and appends one JSON row per
+measured point to a JSONL file (points already present are skipped, so a run can be resumed).
+
+    python -m paper_2405_11425_amd.sweep region  [--out results.jsonl] [--reps 5]
+    python -m paper_2405_11425_amd.sweep lines | windows | probe | stream | calib | all
+
+  region   throughput vs region size, uniform random 128-byte lines        (paper Sec. 2.1, Fig. 1)
+  lines    32 x {4,8,16} B and 64 x 4 B lines at 128 GiB and the largest region (Sec. 2.1, text)
+  windows  per-CU random windows vs XCD-aware windows, 1/2, 1/4, 1/8           (Sec. 2.1 / 2.4, Fig. 1 / 5)
+  probe    all pairs over 64 sampled CUs + each alone, heatmap and inferred groups (Sec. 2.2, Fig. 2 / 3)
+  stream   sequential read and copy ceilings                                 (Sec. 2.1, remark on sequential reads)
+  calib    one copy, one fill, one sequential read of known size (for profiler counter calibration)
+
+Throughput is n_reads * line_bytes / kernel time (HIP events), decimal GB/s, and as a
+percentage of the 8 TB/s HBM3E peak.  Only the HIP library is used; checksums are printed so that
+they can be compared with a reference elsewhere.
+"""
+import argparse
+import json
+import os
+import statistics
+import sys
+import time
+
+import numpy as np
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def _rows(path):
+    seen = set()
+    if path and os.path.exists(path):
+        with open(path) as f:
+            for line in f:
+                try:
+                    seen.add(json.loads(line)["key"])
+                except (ValueError, KeyError):
+                    pass
+    return seen
+
+
+class Runner:
+    def __init__(self, args):
+        import torch
+        from . import binding as rl
+        from . import workloads as wl
+        self.torch, self.rl, self.wl, self.args = torch, rl, wl, args
+        if not torch.cuda.is_available():
+            raise SystemExit("sweep: no GPU visible (the HIP path has no CPU fallback)")
+        free, _ = torch.cuda.mem_get_info()
+        self.max_gib = min(args.max_region_gib, int((free - 4 * wl.GiB) // wl.GiB))
+        self.cus = rl.enumerate_cus()
+        self.region = torch.empty(self.max_gib * wl.GiB, dtype=torch.uint8, device="cuda")
+        t0 = time.perf_counter()
+        rl.fill(self.region, wl.FILL_SEED)
+        self.fill_s = time.perf_counter() - t0
+        self.seen = _rows(args.out)
+        self.launch = {k: v for k, v in dict(unroll=args.unroll, bcast=args.bcast, nontemporal=args.nt,
+                                             block_threads=args.block).items() if v}
+        self.meta = {"device": torch.cuda.get_device_name(0), "n_cus": len(self.cus),
+                     "allocation_gib": self.max_gib, "fill_gbps": round(self.max_gib * wl.GiB / self.fill_s / 1e9, 1),
+                     "launch": self.launch}
+
+    def emit(self, key, row):
+        row = {"key": key, **row}
+        line = json.dumps(row)
+        print(line, flush=True)
+        if self.args.out:
+            with open(self.args.out, "a") as f:
+                f.write(line + "\n")
+
+    def timed_read(self, cfg, wm=None, reps=None, **kw):
+        """Median / min / max over reps (seeds 7, 8, ...) after one warm-up launch."""
+        reps = reps or self.args.reps
+        rl = self.rl
+        call = lambda seed: rl.rand_read(self.region, cfg.line_bytes, cfg.n_reads, cfg.iters_per_wave, seed, wm,
+                                         lanes_per_line=cfg.lanes_per_line, region_bytes=cfg.region_bytes,
+                                         **{**self.launch, **kw})
+        call(1000)
+        res = [call(cfg.read_seed + i) for i in range(reps)]
+        ms = [r.kernel_ms_event for r in res]
+        med = statistics.median(ms)
+        return {"region_gib": cfg.region_bytes / self.wl.GiB, "line_bytes": cfg.line_bytes,
+                "lanes_per_line": cfg.lanes_per_line, "n_reads": cfg.n_reads, "iters_per_wave": cfg.iters_per_wave,
+                "reps": reps, "kernel_ms_median": round(med, 4), "kernel_ms_min": round(min(ms), 4),
+                "kernel_ms_max": round(max(ms), 4),
+                "kernel_ms_device_median": round(statistics.median(r.kernel_ms_device for r in res), 4),
+                "gbps": round(cfg.bytes_read / med / 1e6, 1),
+                "pct_of_hbm_peak": round(cfg.bytes_read / med / 1e6 / HBM_PEAK_GBPS * 100, 1),
+                "checksum_first_seed": res[0].checksum, "waves_run": res[0].waves_run, "launches": res[0].launches}
+
+    # ------------------------------------------------------------------ experiments
+    def region_sweep(self):
+        for cfg in self.wl.region_sweep(self.max_gib * self.wl.GiB, len(self.cus)):
+            key = f"region/{cfg.name}/{json.dumps(self.launch, sort_keys=True)}"
+            if key not in self.seen:
+                self.emit(key, {"experiment": "region", "scheme": "uniform", **self.timed_read(cfg), **self.meta})
+
+    def line_sweep(self):
+        sizes = sorted({min(128, self.max_gib), self.max_gib})
+        for gib in sizes:
+            for cfg in self.wl.line_width_sweep(gib * self.wl.GiB):
+                key = f"lines/{cfg.name}/{json.dumps(self.launch, sort_keys=True)}"
+                if key not in self.seen:
+                    self.emit(key, {"experiment": "lines", **self.timed_read(cfg, reps=3), **self.meta})
+
+    def window_sweep(self):
+        wl, rl = self.wl, self.rl
+        n = len(self.cus)
+        R = self.max_gib * wl.GiB
+        W = wl.resident_logical_waves(n)
+        cfg = wl.ReadConfig(f"windows-{self.max_gib}GiB", R, 128, 32, W, wl.ITERS_PER_WAVE)
+        key = f"windows/none/{cfg.name}"
+        if key not in self.seen:
+            self.emit(key, {"experiment": "windows", "scheme": "none", "n_windows": 1,
+                            **self.timed_read(cfg, mode=rl.MODE_TICKET), **self.meta})
+        for n_windows in (2, 4, 8):
+            for scheme in ("random-per-cu", "xcd"):
+                g, w = (wl.window_map_by_xcd(self.cus, n_windows) if scheme == "xcd"
+                        else wl.window_map_random_per_cu(n, n_windows, seed=n_windows))
+                key = f"windows/{scheme}/{n_windows}/{cfg.name}"
+                if key not in self.seen:
+                    self.emit(key, {"experiment": "windows", "scheme": scheme, "n_windows": n_windows,
+                                    **self.timed_read(cfg, rl.WindowMap(n_windows, g, w)), **self.meta})
+
+    def probe(self):
+        wl, rl = self.wl, self.rl
+        cfg = wl.probe_config(min(16, self.max_gib) * wl.GiB)
+        sample = wl.probe_cu_sample(self.cus, self.args.probe_cus)
+        m = len(sample)
+        key = f"probe/{cfg.name}/{m}"
+        if key in self.seen:
+            return
+        gbps = lambda r: cfg.bytes_read / r.kernel_ms_device / 1e6
+        run = lambda cus: rl.probe_cus(self.region, cus, cfg.n_reads, cfg.iters_per_wave, cfg.read_seed,
+                                       region_bytes=cfg.region_bytes, **self.launch)
+        run([int(sample[0]), int(sample[1])])  # warm-up
+        singles = np.zeros(m)
+        checksums = set()
+        for i, c in enumerate(sample):
+            r = run([int(c)])
+            singles[i] = gbps(r)
+            checksums.add(r.checksum)
+        T = np.zeros((m, m))
+        t0 = time.perf_counter()
+        for i in range(m):
+            for j in range(i + 1, m):
+                r = run([int(sample[i]), int(sample[j])])
+                T[i, j] = T[j, i] = gbps(r)
+                checksums.add(r.checksum)
+            print(f"# probe row {i + 1}/{m} done, {time.perf_counter() - t0:.1f} s", file=sys.stderr, flush=True)
+        group, order, thr = rl.groups_from_heatmap(T, singles, self.args.min_gap)
+        off = T[np.triu_indices(m, 1)]
+        base = os.path.splitext(self.args.out)[0] if self.args.out else None
+        if base:
+            np.savetxt(base + ".probe_heatmap.txt", T, fmt="%.2f")
+            np.savetxt(base + ".probe_singles.txt", singles, fmt="%.2f")
+        self.emit(key, {"experiment": "probe", "n_cus_sampled": m, "cus": sample.tolist(),
+                        "cu_coords": self.cus[sample].tolist(), "n_pairs": m * (m - 1) // 2,
+                        "pair_gbps_min": round(float(off.min()), 2), "pair_gbps_median": round(float(np.median(off)), 2),
+                        "pair_gbps_max": round(float(off.max()), 2),
+                        "single_gbps_median": round(float(np.median(singles)), 2),
+                        "single_gbps_min": round(float(singles.min()), 2),
+                        "single_gbps_max": round(float(singles.max()), 2),
+                        "ratio_min": round(float((T / (singles[:, None] + singles[None, :]))[np.triu_indices(m, 1)].min()), 4),
+                        "ratio_max": round(float((T / (singles[:, None] + singles[None, :]))[np.triu_indices(m, 1)].max()), 4),
+                        "threshold": None if np.isnan(thr) else thr, "n_groups": int(group.max()) + 1,
+                        "group_of_sampled_cu": group.tolist(), "order": order.tolist(),
+                        "distinct_checksums": len(checksums), "checksum": sorted(checksums)[0],
+                        "seconds": round(time.perf_counter() - t0, 1), **self.meta})
+
+    def stream(self):
+        rl, wl = self.rl, self.wl
+        for gib in sorted({min(16, self.max_gib), self.max_gib}):
+            key = f"stream/seq/{gib}"
+            if key in self.seen:
+                continue
+            rl.seq_read(self.region, gib * wl.GiB)
+            res = [rl.seq_read(self.region, gib * wl.GiB) for _ in range(self.args.reps)]
+            med = statistics.median(r.kernel_ms_event for r in res)
+            self.emit(key, {"experiment": "stream", "kind": "sequential read", "region_gib": gib,
+                            "kernel_ms_median": round(med, 4), "gbps": round(gib * wl.GiB / med / 1e6, 1),
+                            "pct_of_hbm_peak": round(gib * wl.GiB / med / 1e6 / HBM_PEAK_GBPS * 100, 1),
+                            "checksum": res[0].checksum, **self.meta})
+        half = (self.max_gib // 2) * wl.GiB
+        key = f"stream/copy/{half // wl.GiB}"
+        if key not in self.seen and half > 0:
+            src, dst = self.region[:half], self.region[half:2 * half]
+            rl.copy(dst, src)
+            ms = statistics.median(rl.copy(dst, src) for _ in range(self.args.reps))
+            rl.fill(self.region, wl.FILL_SEED)  # the second half is a copy of the first now: restore the fill
+            self.emit(key, {"experiment": "stream", "kind": "copy (bytes read + bytes written)",
+                            "copied_gib": half // wl.GiB, "kernel_ms_median": round(ms, 4),
+                            "gbps": round(2 * half / ms / 1e6, 1),
+                            "pct_of_hbm_peak": round(2 * half / ms / 1e6 / HBM_PEAK_GBPS * 100, 1), **self.meta})
+
+    def calib(self):
+        """Three kernels of exactly known traffic, 8 GiB each, for scaling FETCH_SIZE / WRITE_SIZE."""
+        rl, wl = self.rl, self.wl
+        n = min(8, self.max_gib // 2) * wl.GiB
+        ms = rl.copy(self.region[n:2 * n], self.region[:n])
+        rl.fill(self.region, wl.FILL_SEED, region_bytes=2 * n)
+        r = rl.seq_read(self.region, n)
+        self.emit(f"calib/{time.time():.0f}", {"experiment": "calib", "bytes_each": n, "copy_ms": ms,
+                                                "seq_read_ms": r.kernel_ms_event, **self.meta})
+
+
+def main(argv=None):
+    ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
+    ap.add_argument("experiment", choices=["region", "lines", "windows", "probe", "stream", "calib", "all"])
+    ap.add_argument("--out", default=None, help="JSONL file to append to (and to resume from)")
+    ap.add_argument("--reps", type=int, default=5)
+    ap.add_argument("--max-region-gib", type=int, default=256)
+    ap.add_argument("--probe-cus", type=int, default=64)
+    ap.add_argument("--min-gap", type=float, default=0.05)
+    ap.add_argument("--unroll", type=int, default=0)
+    ap.add_argument("--bcast", type=int, default=0)
+    ap.add_argument("--nt", type=int, default=0, help="0 default (on), 1 on, 2 off")
+    ap.add_argument("--block", type=int, default=0)
+    args = ap.parse_args(argv)
+    r = Runner(args)
+    todo = ["region", "lines", "windows", "stream", "probe"] if args.experiment == "all" else [args.experiment]
+    for name in todo:
+        {"region": r.region_sweep, "lines": r.line_sweep, "windows": r.window_sweep, "probe": r.probe,
+         "stream": r.stream, "calib": r.calib}[name]()
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -81,6 +81,41 @@ def test_fill_ragged_sizes_and_other_seed():
     assert not buf.cpu().numpy().any()
 
 
+# ------------------------------------------------------------------ streaming read and copy
+@pytest.mark.parametrize("nbytes", [16, 4096, (1 << 20) + 48, 3 * (1 << 26) + 16 * 5, 1 << 32])
+def test_seq_read_matches_oracle_sum(region, nbytes):
+    got = rl.seq_read(region, nbytes)
+    assert got.checksum == orc.sum_words(wl.FILL_SEED, 0, nbytes // 4, n_threads=ORACLE_THREADS)
+    assert rl.seq_read(region, 0).checksum == 0
+
+
+def test_seq_read_full_region_by_parts(region):
+    """Whole allocation: the sum over the region equals the sum of its 1 GiB slices (GPU), and
+    sampled slices equal the oracle."""
+    n_gib = region.numel() // GiB
+    whole = rl.seq_read(region).checksum
+    total = 0
+    for g in range(n_gib):
+        part = rl.seq_read(region[g * GiB:(g + 1) * GiB]).checksum
+        total += part
+        if g in (0, n_gib // 2, n_gib - 1):
+            assert part == orc.sum_words(wl.FILL_SEED, g * GiB // 4, GiB // 4, n_threads=ORACLE_THREADS), g
+    assert total & M64 == whole
+
+
+def test_copy_kernel():
+    n = (1 << 24) + 16 * 3
+    src = torch.empty(n, dtype=torch.uint8, device="cuda")
+    dst = torch.zeros(n + 32, dtype=torch.uint8, device="cuda")
+    rl.fill(src, 21)
+    ms = rl.copy(dst[:n], src)
+    assert ms > 0
+    host = dst.cpu().numpy()
+    assert np.array_equal(host[:n].view(np.uint32), orc.fill_words(21, 0, n // 4)) and not host[n:].any()
+    with pytest.raises(rl.RandlineError):
+        rl.copy(src[16:n], src[:n - 16])       # overlap
+
+
 # ------------------------------------------------------------------ rand_read, small cases
 SMALL = [
     # region bytes, line, lanes, W, I
@@ -129,7 +164,7 @@ def test_launch_geometry_does_not_change_checksum(region, B, lanes, unrolls):
     want = oracle(R, B, W, I)
     for bcast in (rl.BCAST_LDS, rl.BCAST_DPP, rl.BCAST_READLANE):
         for unroll in unrolls:
-            for nt in (0, 1):
+            for nt in (rl.NT_ON, rl.NT_OFF):
                 got = rl.rand_read(region, B, W * I, I, wl.READ_SEED, lanes_per_line=lanes, region_bytes=R,
                                    bcast=bcast, unroll=unroll, nontemporal=nt)
                 assert got.checksum == want, (bcast, unroll, nt)

@@ -52,7 +52,7 @@ FAKE = (1 << 21, 1 << 20)  # an aligned, non-null "device pointer" that is never
     ((FAKE, 512, 8, 8, 7), {"unroll": 16}, "unroll"),
     ((FAKE, 128, 8, 8, 7), {"bcast": 9}, "bcast"),
     ((FAKE, 128, 8, 8, 7), {"mode": 5}, "mode"),
-    ((FAKE, 128, 8, 8, 7), {"nontemporal": 2}, "nontemporal"),
+    ((FAKE, 128, 8, 8, 7), {"nontemporal": 3}, "nontemporal"),
 ])
 def test_rand_read_rejects_bad_arguments_without_a_device(args, kw, needle):
     with pytest.raises(rl.RandlineError) as e:
