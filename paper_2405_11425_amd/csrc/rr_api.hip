@@ -105,37 +105,28 @@ __global__ void __launch_bounds__(256) reset_kernel(Scratch *s, u32 what) {
         for (u32 i = t; i < kNumKeys; i += blockDim.x) s->key_seen[i] = 0;
 }
 
-// After a read launch (one block of 256 threads): fold the result cells into
-// the head, leave the cells cleared for the next launch, and count the compute
-// units whose share of tickets has not been fully claimed yet.
-__global__ void __launch_bounds__(256) finish_kernel(Scratch *s, const Tables *tb, u32 n_cus, u32 cpw,
-                                                     u32 ticket_mode) {
-    __shared__ u64 sh_sum[256], sh_min[256], sh_max[256];
-    __shared__ u32 sh_waves[256], sh_open[256];
+// After a read launch (one block of kNumCells threads, one result cell each):
+// fold the cells into the head, leave them cleared for the next launch, and
+// count the compute units whose share of tickets has not been fully claimed.
+__global__ void __launch_bounds__(kNumCells) finish_kernel(Scratch *s, const Tables *tb, u32 n_cus, u32 cpw,
+                                                           u32 ticket_mode) {
+    __shared__ u64 sh_sum[kNumCells], sh_min[kNumCells], sh_max[kNumCells];
+    __shared__ u32 sh_waves[kNumCells], sh_open[kNumCells];
     const u32 t = threadIdx.x;
-    u64 sum = 0, tmin = ~0ull, tmax = 0;
-    u32 waves = 0, open = 0;
-    for (u32 i = t; i < kNumCells; i += 256) {
-        Cell *c = &s->cells[i];
-        sum += c->sum;
-        tmin = c->t_min < tmin ? c->t_min : tmin;
-        tmax = c->t_max > tmax ? c->t_max : tmax;
-        waves += c->waves;
-        c->sum = 0;
-        c->t_min = ~0ull;
-        c->t_max = 0;
-        c->waves = 0;
-    }
-    if (ticket_mode)
-        for (u32 c = t; c < n_cus; c += 256)
-            if (s->tickets[c * kTicketStride] < tb->cu_unit_count[c] * cpw) open++;
-    sh_sum[t] = sum;
-    sh_min[t] = tmin;
-    sh_max[t] = tmax;
-    sh_waves[t] = waves;
+    Cell *c = &s->cells[t];
+    sh_sum[t] = c->sum;
+    sh_min[t] = c->t_min;
+    sh_max[t] = c->t_max;
+    sh_waves[t] = c->waves;
+    c->sum = 0;
+    c->t_min = ~0ull;
+    c->t_max = 0;
+    c->waves = 0;
+    u32 open = 0;
+    if (ticket_mode && t < n_cus && s->tickets[t * kTicketStride] < tb->cu_unit_count[t] * cpw) open = 1;
     sh_open[t] = open;
     __syncthreads();
-    for (u32 step = 128; step > 0; step >>= 1) {
+    for (u32 step = kNumCells / 2; step > 0; step >>= 1) {
         if (t < step) {
             sh_sum[t] += sh_sum[t + step];
             sh_min[t] = sh_min[t + step] < sh_min[t] ? sh_min[t + step] : sh_min[t];
@@ -153,6 +144,7 @@ __global__ void __launch_bounds__(256) finish_kernel(Scratch *s, const Tables *t
         s->unfinished = sh_open[0];
     }
 }
+static_assert(kMaxCus <= kNumCells, "finish_kernel checks one compute unit per thread");
 
 }  // namespace rr
 
@@ -207,6 +199,9 @@ struct DeviceState {
     Scratch *scratch = nullptr;
     Tables *tables = nullptr;       // device
     Tables *tables_host = nullptr;  // pinned staging copy
+    Tables *tables_last = nullptr;  // what the device copy holds (plain host memory), to skip equal uploads
+    bool tables_valid = false;
+    bool cells_clean = false;       // result cells are in their cleared state
     u16 *placement = nullptr;
     size_t placement_cap = 0;
     HostHead *head = nullptr;     // pinned
@@ -269,6 +264,7 @@ int get_state(hipStream_t stream, DeviceState **out) {
         if (!st.scratch) HIP_TRY(hipMalloc((void **)&st.scratch, sizeof(Scratch)));
         if (!st.tables) HIP_TRY(hipMalloc((void **)&st.tables, sizeof(Tables)));
         if (!st.tables_host) HIP_TRY(hipHostMalloc((void **)&st.tables_host, sizeof(Tables), hipHostMallocDefault));
+        if (!st.tables_last) st.tables_last = new Tables;
         if (!st.head) HIP_TRY(hipHostMalloc((void **)&st.head, sizeof(HostHead), hipHostMallocDefault));
         if (!st.ev0) HIP_TRY(hipEventCreate(&st.ev0));
         if (!st.ev1) HIP_TRY(hipEventCreate(&st.ev1));
@@ -447,7 +443,11 @@ int run_plan(const Plan &pl, const void *region, uint32_t iters, const rr_window
             tb.cu_unit_count[c] = (u32)(b1 - b0);
         }
     }
-    HIP_TRY(hipMemcpyAsync(st.tables, st.tables_host, sizeof(Tables), hipMemcpyHostToDevice, stream));
+    if (!st.tables_valid || memcmp(st.tables_last, st.tables_host, sizeof(Tables)) != 0) {
+        st.tables_valid = false;
+        HIP_TRY(hipMemcpyAsync(st.tables, st.tables_host, sizeof(Tables), hipMemcpyHostToDevice, stream));
+        memcpy(st.tables_last, st.tables_host, sizeof(Tables));  // trusted only once a later sync succeeded
+    }
     const bool want_placement = opts && opts->placement_out;
     if (want_placement && st.placement_cap < pl.W) {
         HIP_TRY(hipStreamSynchronize(stream));
@@ -495,19 +495,28 @@ int run_plan(const Plan &pl, const void *region, uint32_t iters, const rr_window
 
     if (units * p.chunks_per_wave >= (1ull << 31))
         return fail(RR_EINVAL, "too many tickets per group (%llu)", units * p.chunks_per_wave);
-    hipLaunchKernelGGL(reset_kernel, dim3(1), dim3(256), 0, stream, st.scratch, 1u | 2u | 4u);
-    HIP_TRY(hipGetLastError());
+    // the finish kernel leaves the result cells cleared; counters are needed by ticketed launches only
+    const u32 what = (st.cells_clean ? 0u : 1u) | (p.ticket_mode ? 2u : 0u) |
+                     ((p.ticket_mode || want_placement) ? 4u : 0u);
+    if (what) {
+        hipLaunchKernelGGL(reset_kernel, dim3(1), dim3(256), 0, stream, st.scratch, what);
+        HIP_TRY(hipGetLastError());
+    }
+    st.cells_clean = false;
     const int max_launches = p.ticket_mode ? 32 : 1;
     void *args[] = {(void *)&p};
     for (int launch = 0;; ++launch) {
         HIP_TRY(hipEventRecord(st.ev0, stream));
         HIP_TRY(hipLaunchKernel(pl.kernel, dim3((u32)grid), dim3(pl.block), args, 0, stream));
         HIP_TRY(hipEventRecord(st.ev1, stream));
-        hipLaunchKernelGGL(finish_kernel, dim3(1), dim3(256), 0, stream, st.scratch, st.tables, n_cus,
+        hipLaunchKernelGGL(finish_kernel, dim3(1), dim3(kNumCells), 0, stream, st.scratch, st.tables, n_cus,
                            p.chunks_per_wave, p.ticket_mode);
         HIP_TRY(hipGetLastError());
-        HIP_TRY(hipMemcpyAsync(st.head, st.scratch, sizeof(HostHead), hipMemcpyDeviceToHost, stream));
+        const bool want_cu_waves = opts && opts->cu_waves_out;
+        HIP_TRY(hipMemcpyAsync(st.head, st.scratch, want_cu_waves ? sizeof(HostHead) : 32, hipMemcpyDeviceToHost, stream));
         HIP_TRY(hipStreamSynchronize(stream));
+        st.cells_clean = true;
+        st.tables_valid = true;
         float ms = 0.f;
         HIP_TRY(hipEventElapsedTime(&ms, st.ev0, st.ev1));
         res.launches++;
@@ -641,17 +650,21 @@ extern "C" int rr_seq_read(const void *region, uint64_t region_bytes, void *hip_
     u64 blocks = (n_vec + 255) / 256;
     const u64 cap = (u64)blocks_per_cu * st->cus.size();
     if (blocks > cap) blocks = cap;
-    hipLaunchKernelGGL(reset_kernel, dim3(1), dim3(256), 0, stream, st->scratch, 1u);
-    HIP_TRY(hipGetLastError());
+    if (!st->cells_clean) {
+        hipLaunchKernelGGL(reset_kernel, dim3(1), dim3(256), 0, stream, st->scratch, 1u);
+        HIP_TRY(hipGetLastError());
+    }
+    st->cells_clean = false;
     HIP_TRY(hipEventRecord(st->ev0, stream));
     hipLaunchKernelGGL(seq_read_kernel, dim3((u32)blocks), dim3(256), 0, stream, (const u32x4 *)region, n_vec,
                        st->scratch);
     HIP_TRY(hipGetLastError());
     HIP_TRY(hipEventRecord(st->ev1, stream));
-    hipLaunchKernelGGL(finish_kernel, dim3(1), dim3(256), 0, stream, st->scratch, st->tables, 0u, 1u, 0u);
+    hipLaunchKernelGGL(finish_kernel, dim3(1), dim3(kNumCells), 0, stream, st->scratch, st->tables, 0u, 1u, 0u);
     HIP_TRY(hipGetLastError());
     HIP_TRY(hipMemcpyAsync(st->head, st->scratch, 32, hipMemcpyDeviceToHost, stream));
     HIP_TRY(hipStreamSynchronize(stream));
+    st->cells_clean = true;
     float ms = 0.f;
     HIP_TRY(hipEventElapsedTime(&ms, st->ev0, st->ev1));
     res.checksum = st->head->checksum;
@@ -703,6 +716,7 @@ extern "C" int rr_shutdown(void) {
         if (st.scratch) (void)hipFree(st.scratch);
         if (st.tables) (void)hipFree(st.tables);
         if (st.tables_host) (void)hipHostFree(st.tables_host);
+        delete st.tables_last;
         if (st.placement) (void)hipFree(st.placement);
         if (st.head) (void)hipHostFree(st.head);
         if (st.ev0) (void)hipEventDestroy(st.ev0);

@@ -17,7 +17,7 @@ constexpr u32 kKeyBits = 12;  // xcc[11:8] se[7:5] sh[4] cu[3:0]
 constexpr u32 kNumKeys = 1u << kKeyBits;
 constexpr u16 kExcluded = 0xFFFFu;
 
-constexpr u32 kNumCells = 4096;     // result cells, one 128-byte line each
+constexpr u32 kNumCells = 1024;     // result cells, one 128-byte line each
 constexpr u32 kTicketStride = 32;   // u32 slots between two CUs' ticket counters (one 128-byte line each)
 
 // Same-address device atomics retire at roughly one per 12 ns on this GPU, so
