@@ -110,7 +110,7 @@ def main():
     bytes_per_launch = configs[0].bytes_read
     avg_ms = sum(all_ms) / len(all_ms)
     achieved = bytes_per_launch / avg_ms / 1e6
-    roofline = {"bound": "hbm", "kernel": "rand_read_kernel<32 lanes, 1 dword, ring 8, DPP broadcast>",
+    roofline = {"bound": "hbm", "kernel": "rand_read_kernel<32 lanes, 1 dword, ring 16, DPP broadcast, non-temporal>",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBPS, 4),
                 "traffic": read_traffic_file(os.path.join(ROOT, "profiles", "rand_read_region_sweep_pmc.txt")),

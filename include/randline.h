@@ -115,9 +115,31 @@ typedef struct {
                                 multiple of 64; 0 = default (flat: all of them; ticketed: 512)     */
     uint32_t reserved;       /* must be 0                                                          */
     uint64_t first_wave;     /* id of the first logical wave (default 0); multiple of n_groups     */
+    uint64_t zone_bytes;     /* 0 = off.  Otherwise the region is cut into zones of this many bytes
+                                (a multiple of line_bytes, at most 16 zones) and every wave reads its
+                                lines zone by zone: all lines in zone 0 first, then zone 1, ...  Same
+                                lines, same checksum, different order (see "Zone-phased reads").
+                                Flat launches without a window map only.                           */
+    uint64_t *phase_ticks;   /* DEVICE [hardware waves x zones] or NULL (zone-phased reads only): the
+                                constant-rate clock (100 MHz) at which each wave finished each zone,
+                                for checking how well the phases line up                           */
     uint16_t *placement_out; /* host [W] or NULL: dense CU id that executed each logical wave      */
     uint32_t *cu_waves_out;  /* host [n_cus] or NULL: working hardware waves counted per CU        */
 } rr_launch_opts_t;
+
+/*
+ * Zone-phased reads.  On the MI355X the random-read rate depends on how many
+ * 96 GiB thirds of the HBM are being read at the same time by anyone (measure
+ * it with the "zones" experiment of the sweep driver); restricting each compute
+ * group to a window (paper Sec. 2.4) does not change that, but letting all
+ * waves work on the same zone at the same time does.  With zone_bytes set, the
+ * kernel bins each wave's line indices by zone in LDS and reads them zone by
+ * zone.  This is the paper's idea -- keep what is accessed together inside one
+ * locality domain -- transposed from space (a window per group) to time (a
+ * window per phase).  Waves are not synchronised, and since the hardware lets
+ * the oldest workgroups of a CU run well ahead of the youngest the phases
+ * overlap only partly: the measured gain at 256 GiB is about 1.5 %.
+ */
 
 /*
  * List the device's compute units.  A kernel records, for every CU on which a

@@ -44,7 +44,8 @@ class _Result(C.Structure):
 class _Opts(C.Structure):
     _fields_ = [("block_threads", C.c_uint32), ("grid_blocks", C.c_uint32), ("unroll", C.c_uint32),
                 ("mode", C.c_uint32), ("bcast", C.c_uint32), ("nontemporal", C.c_uint32),
-                ("chunk_iters", C.c_uint32), ("reserved", C.c_uint32), ("first_wave", C.c_uint64), ("placement_out", C.POINTER(C.c_uint16)),
+                ("chunk_iters", C.c_uint32), ("reserved", C.c_uint32), ("first_wave", C.c_uint64),
+                ("zone_bytes", C.c_uint64), ("phase_ticks", C.c_void_p), ("placement_out", C.POINTER(C.c_uint16)),
                 ("cu_waves_out", C.POINTER(C.c_uint32))]
 
 
@@ -168,8 +169,13 @@ class ReadResult:
 
 
 def _opts(W: int, n_cus_hint: int, block_threads=0, grid_blocks=0, unroll=0, mode=0, bcast=0,
-          nontemporal=0, chunk_iters=0, first_wave=0, want_placement=False, want_cu_waves=False):
-    o = _Opts(block_threads, grid_blocks, unroll, mode, bcast, nontemporal, chunk_iters, 0, first_wave, None, None)
+          nontemporal=0, chunk_iters=0, first_wave=0, zone_bytes=0, phase_ticks=None, want_placement=False,
+          want_cu_waves=False):
+    ticks_ptr = None
+    if phase_ticks is not None:   # a torch int64 device tensor of hardware waves x zones elements
+        ticks_ptr = int(phase_ticks.data_ptr())
+    o = _Opts(block_threads, grid_blocks, unroll, mode, bcast, nontemporal, chunk_iters, 0, first_wave, zone_bytes,
+              ticks_ptr, None, None)
     placement = cu_waves = None
     if want_placement:
         placement = np.full(max(W, 1), 0xFFFF, dtype=np.uint16)

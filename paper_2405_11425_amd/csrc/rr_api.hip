@@ -10,7 +10,7 @@
 #include <vector>
 
 #include "../../include/randline.h"
-#include "rr_read_kernel.hpp"
+#include "rr_phased_kernel.hpp"
 
 namespace rr {
 
@@ -284,8 +284,9 @@ struct Family {
     u32 default_unroll;
 };
 const Family kFamilies[] = {
-    {32, 1, find_read_kernel_32_1, 8}, {32, 2, find_read_kernel_32_2, 8}, {32, 4, find_read_kernel_32_4, 4},
-    {64, 1, find_read_kernel_64_1, 8}, {64, 2, find_read_kernel_64_2, 8},
+    // default ring depth: the deepest one built (measured best for every shape, by 1-3 %)
+    {32, 1, find_read_kernel_32_1, 16}, {32, 2, find_read_kernel_32_2, 16}, {32, 4, find_read_kernel_32_4, 8},
+    {64, 1, find_read_kernel_64_1, 16}, {64, 2, find_read_kernel_64_2, 16},
 };
 
 const Family *find_family(u32 lanes, u32 wdw) {
@@ -300,6 +301,8 @@ struct Plan {
     u32 log2_line = 0, lanes = 0, wdw = 0, G = 1, n_windows = 1;
     u32 block = 256, unroll = 0, bcast = RR_BCAST_DPP, nt = 1, mode = RR_MODE_AUTO, grid_blocks = 0;
     u32 chunk_iters = 0;
+    u64 zone_lines = 0;  // > 0: zone-phased kernel
+    u32 n_zones = 0;
     bool pinned = false;
     const Family *family = nullptr;
     kernel_handle kernel = nullptr;
@@ -368,14 +371,35 @@ int make_plan(const void *region, uint64_t region_bytes, uint32_t line_bytes, ui
         pl.chunk_iters = opts->chunk_iters;
         if (opts->first_wave % pl.G != 0) return fail(RR_EINVAL, "first_wave must be a multiple of n_groups");
         pl.first_wave = opts->first_wave;
+        if (opts->phase_ticks && !opts->zone_bytes) return fail(RR_EINVAL, "phase_ticks needs zone_bytes");
+        if (opts->zone_bytes) {
+            if (opts->zone_bytes % line_bytes != 0) return fail(RR_EINVAL, "zone_bytes must be a multiple of line_bytes");
+            if (wm) return fail(RR_EINVAL, "zone-phased reads cannot be combined with a window map");
+            if (opts->mode == RR_MODE_TICKET) return fail(RR_EINVAL, "zone-phased reads need a flat launch");
+            if (opts->chunk_iters) return fail(RR_EINVAL, "zone-phased reads do not take chunk_iters");
+            if (opts->placement_out || opts->cu_waves_out)
+                return fail(RR_EINVAL, "zone-phased reads do not record placement");
+            pl.zone_lines = opts->zone_bytes / line_bytes;
+            const u64 nz = (pl.n_lines + pl.zone_lines - 1) / pl.zone_lines;
+            if (nz > 16) return fail(RR_EINVAL, "zone_bytes gives %llu zones; at most 16 are supported", nz);
+            pl.n_zones = (u32)nz;
+        }
     }
     pl.kernel = pl.family->find(pl.unroll, pl.bcast, pl.nt);
     if (!pl.kernel) return fail(RR_EINVAL, "unroll %u is not built for this line shape", pl.unroll);
+    if (pl.zone_lines) {
+        pl.kernel = find_phased_kernel(pl.lanes, pl.wdw, pl.nt);
+        if (!pl.kernel) return fail(RR_EINVAL, "no zone-phased kernel for this line shape");
+        pl.block = 256;  // its LDS lists are laid out for four waves per workgroup
+    }
     bool needs_tickets = false;
     if (wm) {
         if (wm->n_groups > 1) needs_tickets = true;
         for (u32 c = 0; c < wm->n_cus; ++c)
-            if (wm->group_of_cu[c] == RR_CU_EXCLUDED) needs_tickets = true;
+            if (wm->group_of_cu[c] == RR_CU_EXCLUDED) {
+                needs_tickets = true;
+                pl.pinned = true;  // most workgroups will land on idle CUs and leave: launch many more
+            }
     }
     if (pl.mode == RR_MODE_FLAT && needs_tickets)
         return fail(RR_EINVAL, "flat mode cannot honour a window map with several groups or excluded CUs");
@@ -473,12 +497,15 @@ int run_plan(const Plan &pl, const void *region, uint32_t iters, const rr_window
     p.chunk_iters = chunk;
     p.chunks_per_wave = (iters + chunk - 1) / chunk;
     p.n_groups = pl.G;
+    p.n_zones = pl.n_zones;
+    p.zone_lines = pl.zone_lines;
     p.ticket_mode = pl.mode == RR_MODE_TICKET ? 1u : 0u;
     p.log2_line = pl.log2_line;
     p.red = make_reducer(L_win);
     p.scratch = st.scratch;
     p.tables = st.tables;
     p.placement = want_placement ? st.placement : nullptr;
+    p.phase_ticks = (opts && pl.zone_lines) ? (u64 *)opts->phase_ticks : nullptr;
 
     const u32 waves_per_block = pl.block / 64;
     // a CU holds at most 32 waves (8 per SIMD); workgroups beyond what really fits queue up,

@@ -78,10 +78,13 @@ struct ReadParams {
     u32 n_groups;             // G
     u32 ticket_mode;          // 0 flat, 1 ticketed
     u32 log2_line;            // 7, 8 or 9
+    u32 n_zones;              // phased variant: number of zones ...
+    u64 zone_lines;           // ... of this many lines each (the last one may be shorter)
     Reducer red;              // L = lines per window
     Scratch *scratch;
     const Tables *tables;
     u16 *placement;           // [W] or null: dense CU id that executed each logical wave
+    u64 *phase_ticks;         // [hardware waves x zones] or null: clock at the end of each zone phase
 };
 
 __device__ __forceinline__ u64 mix64(u64 z) {

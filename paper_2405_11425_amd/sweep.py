@@ -2,13 +2,17 @@
 measured point to a JSONL file (points already present are skipped, so a run can be resumed).
 
     python -m paper_2405_11425_amd.sweep region  [--out results.jsonl] [--reps 5]
-    python -m paper_2405_11425_amd.sweep lines | windows | probe | stream | calib | all
+    python -m paper_2405_11425_amd.sweep lines | windows | probe | stream | zones | groups | calib | all
 
   region   throughput vs region size, uniform random 128-byte lines        (paper Sec. 2.1, Fig. 1)
   lines    32 x {4,8,16} B and 64 x 4 B lines at 128 GiB and the largest region (Sec. 2.1, text)
   windows  per-CU random windows vs XCD-aware windows, 1/2, 1/4, 1/8           (Sec. 2.1 / 2.4, Fig. 1 / 5)
   probe    all pairs over 64 sampled CUs + each alone, heatmap and inferred groups (Sec. 2.2, Fig. 2 / 3)
   stream   sequential read and copy ceilings                                 (Sec. 2.1, remark on sequential reads)
+  zones    two windows read at the same time, all pairs: which parts of the memory slow each other down
+           (the pair-probe idea of Sec. 2.2 applied to memory instead of compute units)
+  groups   each XCD alone, CU-count scaling inside one XCD vs spread over all, pairs of XCDs on
+           disjoint 40 GiB regions                                               (Sec. 2.3, Fig. 4)
   calib    one copy, one fill, one sequential read of known size (for profiler counter calibration)
 
 Throughput is n_reads * line_bytes / kernel time (HIP events), decimal GB/s, and as a
@@ -115,8 +119,9 @@ class Runner:
             self.emit(key, {"experiment": "windows", "scheme": "none", "n_windows": 1,
                             **self.timed_read(cfg, mode=rl.MODE_TICKET), **self.meta})
         for n_windows in (2, 4, 8):
-            for scheme in ("random-per-cu", "xcd"):
+            for scheme in ("random-per-cu", "xcd", "shader-engine"):
                 g, w = (wl.window_map_by_xcd(self.cus, n_windows) if scheme == "xcd"
+                        else wl.window_map_by_se(self.cus, n_windows) if scheme == "shader-engine"
                         else wl.window_map_random_per_cu(n, n_windows, seed=n_windows))
                 key = f"windows/{scheme}/{n_windows}/{cfg.name}"
                 if key not in self.seen:
@@ -124,50 +129,66 @@ class Runner:
                                     **self.timed_read(cfg, rl.WindowMap(n_windows, g, w)), **self.meta})
 
     def probe(self):
+        """Pair probe (paper Sec. 2.2).  A probe unit is one CU (--probe-block 1, the paper's experiment)
+        or a block of adjacent dense CU ids: on this GPU two CUs cannot load any shared resource, but two
+        blocks of four can, so blocks expose the grouping that single CUs do not."""
         wl, rl = self.wl, self.rl
         cfg = wl.probe_config(min(16, self.max_gib) * wl.GiB)
-        sample = wl.probe_cu_sample(self.cus, self.args.probe_cus)
-        m = len(sample)
-        key = f"probe/{cfg.name}/{m}"
+        blk = self.args.probe_block
+        if blk == 1:
+            units = [[int(c)] for c in wl.probe_cu_sample(self.cus, self.args.probe_cus)]
+        else:
+            n_units = min(self.args.probe_cus, len(self.cus) // blk)
+            step = (len(self.cus) // blk) / n_units
+            units = [list(range(int(i * step) * blk, int(i * step) * blk + blk)) for i in range(n_units)]
+        m = len(units)
+        key = f"probe/{cfg.name}/{m}x{blk}"
         if key in self.seen:
             return
-        gbps = lambda r: cfg.bytes_read / r.kernel_ms_device / 1e6
-        run = lambda cus: rl.probe_cus(self.region, cus, cfg.n_reads, cfg.iters_per_wave, cfg.read_seed,
+        n_reads = cfg.n_reads * blk
+        nbytes = n_reads * cfg.line_bytes
+        gbps = lambda r: nbytes / r.kernel_ms_device / 1e6
+        run = lambda cus: rl.probe_cus(self.region, cus, n_reads, cfg.iters_per_wave, cfg.read_seed,
                                        region_bytes=cfg.region_bytes, **self.launch)
-        run([int(sample[0]), int(sample[1])])  # warm-up
+        run(units[0] + units[1])  # warm-up
         singles = np.zeros(m)
         checksums = set()
-        for i, c in enumerate(sample):
-            r = run([int(c)])
+        for i, u in enumerate(units):
+            r = run(u)
             singles[i] = gbps(r)
             checksums.add(r.checksum)
         T = np.zeros((m, m))
         t0 = time.perf_counter()
         for i in range(m):
             for j in range(i + 1, m):
-                r = run([int(sample[i]), int(sample[j])])
+                r = run(units[i] + units[j])
                 T[i, j] = T[j, i] = gbps(r)
                 checksums.add(r.checksum)
             print(f"# probe row {i + 1}/{m} done, {time.perf_counter() - t0:.1f} s", file=sys.stderr, flush=True)
         group, order, thr = rl.groups_from_heatmap(T, singles, self.args.min_gap)
-        off = T[np.triu_indices(m, 1)]
+        iu = np.triu_indices(m, 1)
+        off = T[iu]
+        ratio = (T / (singles[:, None] + singles[None, :]))[iu]
         base = os.path.splitext(self.args.out)[0] if self.args.out else None
         if base:
-            np.savetxt(base + ".probe_heatmap.txt", T, fmt="%.2f")
-            np.savetxt(base + ".probe_singles.txt", singles, fmt="%.2f")
-        self.emit(key, {"experiment": "probe", "n_cus_sampled": m, "cus": sample.tolist(),
-                        "cu_coords": self.cus[sample].tolist(), "n_pairs": m * (m - 1) // 2,
+            np.savetxt(f"{base}.probe_heatmap_{m}x{blk}.txt", T, fmt="%.2f")
+            np.savetxt(f"{base}.probe_singles_{m}x{blk}.txt", singles, fmt="%.2f")
+        n_groups = int(group.max()) + 1
+        sizes = np.bincount(group, minlength=n_groups) * blk
+        first = [u[0] for u in units]
+        self.emit(key, {"experiment": "probe", "unit_cus": blk, "n_units": m, "units_first_cu": first,
+                        "unit_coords_first_cu": self.cus[first].tolist(), "n_pairs": m * (m - 1) // 2,
                         "pair_gbps_min": round(float(off.min()), 2), "pair_gbps_median": round(float(np.median(off)), 2),
                         "pair_gbps_max": round(float(off.max()), 2),
                         "single_gbps_median": round(float(np.median(singles)), 2),
                         "single_gbps_min": round(float(singles.min()), 2),
                         "single_gbps_max": round(float(singles.max()), 2),
-                        "ratio_min": round(float((T / (singles[:, None] + singles[None, :]))[np.triu_indices(m, 1)].min()), 4),
-                        "ratio_max": round(float((T / (singles[:, None] + singles[None, :]))[np.triu_indices(m, 1)].max()), 4),
-                        "threshold": None if np.isnan(thr) else thr, "n_groups": int(group.max()) + 1,
-                        "group_of_sampled_cu": group.tolist(), "order": order.tolist(),
-                        "distinct_checksums": len(checksums), "checksum": sorted(checksums)[0],
-                        "seconds": round(time.perf_counter() - t0, 1), **self.meta})
+                        "ratio_min": round(float(ratio.min()), 4), "ratio_median": round(float(np.median(ratio)), 4),
+                        "ratio_max": round(float(ratio.max()), 4),
+                        "threshold": None if np.isnan(thr) else round(thr, 4), "n_groups": n_groups,
+                        "group_sizes_in_cus": sorted(set(sizes.tolist())), "group_of_unit": group.tolist(),
+                        "order": order.tolist(), "distinct_checksums": len(checksums),
+                        "checksum": sorted(checksums)[0], "seconds": round(time.perf_counter() - t0, 1), **self.meta})
 
     def stream(self):
         rl, wl = self.rl, self.wl
@@ -194,6 +215,101 @@ class Runner:
                             "gbps": round(2 * half / ms / 1e6, 1),
                             "pct_of_hbm_peak": round(2 * half / ms / 1e6 / HBM_PEAK_GBPS * 100, 1), **self.meta})
 
+    def zones(self):
+        """All pairs (a, b) of n equal windows of the largest region: even CUs read window a, odd CUs
+        window b.  Windows that do not disturb each other are clustered into zones."""
+        wl, rl = self.wl, self.rl
+        n_w = self.args.zone_windows
+        R = (self.max_gib // n_w) * n_w * wl.GiB
+        key = f"zones/{R // wl.GiB}GiB/{n_w}"
+        if key in self.seen:
+            return
+        n = len(self.cus)
+        cfg = wl.ReadConfig("zones", R, 128, 32, wl.resident_logical_waves(n), wl.ITERS_PER_WAVE)
+        parity = (np.arange(n) % 2).astype(np.uint16)
+        M = np.zeros((n_w, n_w))
+        t0 = time.perf_counter()
+        for a in range(n_w):
+            for b in range(a, n_w):
+                row = self.timed_read(cfg, rl.WindowMap(n_w, parity, np.array([a, b], np.uint16)), reps=3)
+                M[a, b] = M[b, a] = row["gbps"]
+            print(f"# zones row {a + 1}/{n_w} done, {time.perf_counter() - t0:.1f} s", file=sys.stderr, flush=True)
+        # related windows are the FAST pairs here, so cluster on the reciprocal
+        group, order, thr = rl.groups_from_heatmap(1.0 / M, None, self.args.min_gap / 5)
+        zones = [[int(w) for w in np.flatnonzero(group == g)] for g in range(int(group.max()) + 1)]
+        same = [M[a, b] for a in range(n_w) for b in range(a + 1, n_w) if group[a] == group[b]]
+        cross = [M[a, b] for a in range(n_w) for b in range(a + 1, n_w) if group[a] != group[b]]
+        base = os.path.splitext(self.args.out)[0] if self.args.out else None
+        if base:
+            np.savetxt(base + ".zone_matrix.txt", M, fmt="%.1f")
+        self.emit(key, {"experiment": "zones", "region_gib": R // wl.GiB, "n_windows": n_w,
+                        "window_gib": R / n_w / wl.GiB, "n_zones": len(zones),
+                        "zones_gib": [[z[0] * R / n_w / wl.GiB, (z[-1] + 1) * R / n_w / wl.GiB] for z in zones],
+                        "zone_of_window": group.tolist(),
+                        "gbps_same_zone_median": round(float(np.median(same)), 1) if same else None,
+                        "gbps_cross_zone_median": round(float(np.median(cross)), 1) if cross else None,
+                        "gbps_single_window_median": round(float(np.median(np.diag(M))), 1), **self.meta})
+
+    def groups(self):
+        """The paper's group experiments with the XCD as the group (Sec. 2.3)."""
+        wl, rl = self.wl, self.rl
+        cus, n = self.cus, len(self.cus)
+        R = min(16, self.max_gib) * wl.GiB
+        xcds = np.unique(cus[:, 0])
+        per_cu_reads = 1 << 21
+
+        def pinned(cu_list, region_bytes=R, wm=None, G=1):
+            W = max(G, (len(cu_list) * per_cu_reads // wl.ITERS_PER_WAVE) // G * G)
+            cfg = wl.ReadConfig("groups", region_bytes, 128, 32, W, wl.ITERS_PER_WAVE)
+            if wm is None:
+                g = np.full(n, rl.RR_CU_EXCLUDED, np.uint16)
+                g[cu_list] = 0
+                wm = rl.WindowMap(1, g, np.zeros(1, np.uint16))
+            row = self.timed_read(cfg, wm, reps=3)
+            gbps_dev = cfg.bytes_read / row["kernel_ms_device_median"] / 1e6
+            return round(gbps_dev, 1), row
+
+        key = "groups/each-xcd-alone"
+        singles = {}
+        if key not in self.seen:
+            for x in xcds:
+                ids = np.flatnonzero(cus[:, 0] == x)
+                singles[int(x)], _ = pinned(ids)
+            self.emit(key, {"experiment": "groups", "kind": "each XCD alone (all its CUs), 16 GiB region",
+                            "gbps_by_xcd": singles, "cus_per_xcd": int(np.sum(cus[:, 0] == xcds[0])), **self.meta})
+        key = "groups/scaling"
+        if key not in self.seen:
+            ids0 = np.flatnonzero(cus[:, 0] == xcds[0])
+            inside = {k: pinned(ids0[:k])[0] for k in (1, 2, 4, 8, 16, 32) if k <= len(ids0)}
+            spread = {}
+            for per in (1, 2, 4, 8, 16, 32):
+                pick = np.concatenate([np.flatnonzero(cus[:, 0] == x)[:per] for x in xcds])
+                spread[int(len(pick))] = pinned(pick)[0]
+            self.emit(key, {"experiment": "groups", "kind": "k CUs inside XCD 0 vs k CUs spread evenly over all XCDs",
+                            "gbps_inside_one_xcd": inside, "gbps_spread": spread, **self.meta})
+        key = "groups/xcd-pairs"
+        if key not in self.seen and self.max_gib >= 80:
+            R2 = 80 * wl.GiB
+            alone = {}
+            for x in xcds:                                   # one XCD on its own 40 GiB half
+                g = np.full(n, rl.RR_CU_EXCLUDED, np.uint16)
+                g[cus[:, 0] == x] = 0
+                alone[int(x)], _ = pinned(np.flatnonzero(cus[:, 0] == x), R2,
+                                          rl.WindowMap(2, g, np.array([int(x) % 2], np.uint16)))
+            pairs = {}
+            for i, x in enumerate(xcds):
+                for y in xcds[i + 1:]:
+                    g = np.full(n, rl.RR_CU_EXCLUDED, np.uint16)
+                    g[cus[:, 0] == x] = 0
+                    g[cus[:, 0] == y] = 1
+                    both = np.flatnonzero((cus[:, 0] == x) | (cus[:, 0] == y))
+                    pairs[f"{int(x)}-{int(y)}"], _ = pinned(both, R2, rl.WindowMap(2, g, np.array([0, 1], np.uint16)), G=2)
+            ratios = {k: round(v / (alone[int(k.split('-')[0])] + alone[int(k.split('-')[1])]), 3)
+                      for k, v in pairs.items()}
+            self.emit(key, {"experiment": "groups", "kind": "pairs of XCDs, each on its own 40 GiB half of an 80 GiB region",
+                            "gbps_alone": alone, "gbps_pairs": pairs, "pair_over_sum_of_singles": ratios,
+                            "ratio_min": min(ratios.values()), "ratio_max": max(ratios.values()), **self.meta})
+
     def calib(self):
         """Three kernels of exactly known traffic, 8 GiB each, for scaling FETCH_SIZE / WRITE_SIZE."""
         rl, wl = self.rl, self.wl
@@ -207,11 +323,14 @@ class Runner:
 
 def main(argv=None):
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
-    ap.add_argument("experiment", choices=["region", "lines", "windows", "probe", "stream", "calib", "all"])
+    ap.add_argument("experiment", choices=["region", "lines", "windows", "probe", "stream", "zones", "groups",
+                                           "calib", "all"])
+    ap.add_argument("--zone-windows", type=int, default=32)
     ap.add_argument("--out", default=None, help="JSONL file to append to (and to resume from)")
     ap.add_argument("--reps", type=int, default=5)
     ap.add_argument("--max-region-gib", type=int, default=256)
-    ap.add_argument("--probe-cus", type=int, default=64)
+    ap.add_argument("--probe-cus", type=int, default=64, help="number of probe units")
+    ap.add_argument("--probe-block", type=int, default=1, help="adjacent CUs per probe unit")
     ap.add_argument("--min-gap", type=float, default=0.05)
     ap.add_argument("--unroll", type=int, default=0)
     ap.add_argument("--bcast", type=int, default=0)
@@ -219,10 +338,11 @@ def main(argv=None):
     ap.add_argument("--block", type=int, default=0)
     args = ap.parse_args(argv)
     r = Runner(args)
-    todo = ["region", "lines", "windows", "stream", "probe"] if args.experiment == "all" else [args.experiment]
+    todo = (["region", "lines", "windows", "stream", "groups", "zones", "probe"] if args.experiment == "all"
+            else [args.experiment])
     for name in todo:
         {"region": r.region_sweep, "lines": r.line_sweep, "windows": r.window_sweep, "probe": r.probe,
-         "stream": r.stream, "calib": r.calib}[name]()
+         "stream": r.stream, "zones": r.zones, "groups": r.groups, "calib": r.calib}[name]()
     return 0
 
 

@@ -108,6 +108,17 @@ def window_map_by_xcd(cu_table: np.ndarray, n_windows: int) -> Tuple[np.ndarray,
     return group_of_cu, window_of_group
 
 
+def window_map_by_se(cu_table: np.ndarray, n_windows: int) -> Tuple[np.ndarray, np.ndarray]:
+    """Group = shader engine, i.e. the pair (xcc, se) -- the 8-CU groups that the block pair probe
+    finds on the MI355X; group g reads window g mod n_windows."""
+    t = np.asarray(cu_table).astype(np.int64)
+    key = t[:, 0] * 64 + t[:, 1]
+    ids = np.unique(key)
+    group_of_cu = np.searchsorted(ids, key).astype(np.uint16)
+    window_of_group = (np.arange(ids.size) % n_windows).astype(np.uint16)
+    return group_of_cu, window_of_group
+
+
 def window_map_from_groups(group_of_cu: Sequence[int], n_windows: int) -> Tuple[np.ndarray, np.ndarray]:
     """Placement for an arbitrary CU grouping (e.g. the one inferred from the pair probe)."""
     g = np.asarray(group_of_cu, dtype=np.uint16)

@@ -201,6 +201,45 @@ def test_repeatable(region):
     assert seen == {oracle(R, 128, W, I, read_seed=5)}
 
 
+# ------------------------------------------------------------------ zone-phased order
+@pytest.mark.parametrize("R,B,lanes,W,I,zone", [
+    (1 << 20, 128, 32, 4, 8, 1 << 18),              # tiny, 4 zones
+    (1 << 20, 128, 32, 7, 100, 3 << 17),            # odd W, ragged chunk, last zone shorter
+    (12288, 128, 32, 5, 37, 4096),                  # 96 lines in 3 zones, exact remainder path
+    (3 << 24, 128, 32, 301, 1100, 1 << 24),         # several chunks per wave, 3 zones
+    (3 << 24, 256, 32, 77, 600, 5 << 22),           # 8-byte lanes, uneven zones
+    (5 << 22, 512, 32, 31, 513, 1 << 22),           # 16-byte lanes, 5 zones
+    (1 << 26, 256, 64, 33, 700, 1 << 25),           # 64-lane lines
+    (1 << 26, 512, 64, 9, 70, 1 << 26),             # a single zone
+    (1 << 28, 128, 32, 256, 4096, 96 << 20),        # the small reference configuration in 3 zones
+])
+def test_zone_phased_reads_same_checksum(region, R, B, lanes, W, I, zone):
+    want = oracle(R, B, W, I)
+    for nt in (rl.NT_ON, rl.NT_OFF):
+        got = rl.rand_read(region, B, W * I, I, wl.READ_SEED, lanes_per_line=lanes, region_bytes=R,
+                           zone_bytes=zone, nontemporal=nt)
+        assert got.checksum == want
+        assert got.waves_run == (W * lanes + 63) // 64
+
+
+def test_zone_phase_ticks(region):
+    """Per-wave phase end times: one non-decreasing row of clock values per hardware wave."""
+    W, I, Z = 64, 600, 3
+    ticks = torch.zeros(32 * Z, dtype=torch.int64, device="cuda")
+    got = rl.rand_read(region, 128, W * I, I, 7, region_bytes=3 << 24, zone_bytes=1 << 24, phase_ticks=ticks)
+    assert got.checksum == oracle(3 << 24, 128, W, I)
+    t = ticks.cpu().numpy().reshape(32, Z)
+    assert (t > 0).all() and (np.diff(t, axis=1) >= 0).all()
+
+
+def test_zone_phased_full_size(region, cu_table):
+    """The sweep's largest points in 96 GiB zones, as the bench's phased leg launches them."""
+    for cfg in wl.region_sweep(region.numel(), len(cu_table))[-3:]:
+        got = rl.rand_read(region, 128, cfg.n_reads, cfg.iters_per_wave, cfg.read_seed,
+                           region_bytes=cfg.region_bytes, zone_bytes=96 * GiB)
+        assert got.checksum == oracle(cfg.region_bytes, 128, cfg.logical_waves, cfg.iters_per_wave), cfg.name
+
+
 # ------------------------------------------------------------------ windows
 def check_placement(res, W, G, group_of_cu):
     assert res.placement is not None and res.placement.shape == (W,)
@@ -235,6 +274,32 @@ def test_windows_random_per_cu(region, cu_table, n_windows):
                        region_bytes=R, want_placement=True)
     assert res.checksum == want
     check_placement(res, W, n, g_of_cu)
+
+
+def test_windows_by_shader_engine(region, cu_table):
+    R, B, I = 1 << 31, 128, 128
+    g_of_cu, w_of_g = wl.window_map_by_se(cu_table, 4)
+    G = len(w_of_g)
+    W = G * 6
+    want = oracle(R, B, W, I, n_windows=4, window_of_group=w_of_g)
+    res = rl.rand_read(region, B, W * I, I, wl.READ_SEED, rl.WindowMap(4, g_of_cu, w_of_g), region_bytes=R,
+                       want_placement=True)
+    assert res.checksum == want
+    check_placement(res, W, G, g_of_cu)
+
+
+def test_small_grids_still_finish_by_stealing(region, cu_table):
+    """Fewer workgroups than CUs: the waves that do run must drain the shares of the CUs that got none."""
+    R, B, I = 1 << 28, 128, 200
+    g_of_cu, w_of_g = wl.window_map_by_xcd(cu_table, 2)
+    G = len(w_of_g)
+    W = G * 40
+    want = oracle(R, B, W, I, n_windows=2, window_of_group=w_of_g)
+    for grid in (64, 500):
+        res = rl.rand_read(region, B, W * I, I, wl.READ_SEED, rl.WindowMap(2, g_of_cu, w_of_g), region_bytes=R,
+                           grid_blocks=grid, chunk_iters=64, want_placement=True)
+        assert res.checksum == want, grid
+        check_placement(res, W, G, g_of_cu)
 
 
 def test_windows_other_shapes_and_odd_quota(region, cu_table):

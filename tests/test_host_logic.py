@@ -53,6 +53,10 @@ FAKE = (1 << 21, 1 << 20)  # an aligned, non-null "device pointer" that is never
     ((FAKE, 128, 8, 8, 7), {"bcast": 9}, "bcast"),
     ((FAKE, 128, 8, 8, 7), {"mode": 5}, "mode"),
     ((FAKE, 128, 8, 8, 7), {"nontemporal": 3}, "nontemporal"),
+    ((FAKE, 128, 8, 8, 7), {"zone_bytes": 100}, "zone_bytes"),
+    ((FAKE, 128, 8, 8, 7), {"zone_bytes": 128}, "at most 16"),
+    ((FAKE, 128, 8, 8, 7), {"zone_bytes": 1 << 18, "mode": 2}, "flat launch"),
+    ((FAKE, 128, 8, 8, 7), {"zone_bytes": 1 << 18, "chunk_iters": 64}, "chunk_iters"),
 ])
 def test_rand_read_rejects_bad_arguments_without_a_device(args, kw, needle):
     with pytest.raises(rl.RandlineError) as e:
@@ -144,6 +148,9 @@ def test_window_maps_are_valid():
         g, w = wl.window_map_random_per_cu(256, nw, seed=4)
         assert g.tolist() == list(range(256)) and w.max() < nw
         assert np.array_equal(w, wl.window_map_random_per_cu(256, nw, seed=4)[1])   # seeded
+    g, w = wl.window_map_by_se(table, 4)
+    assert w.shape == (32,) and g.max() == 31 and all(np.sum(g == k) == 8 for k in range(32))
+    assert all(len({(int(x), int(s)) for x, s in table[g == k][:, :2]}) == 1 for k in range(32))
     g, w = wl.window_map_from_groups([0, 0, 1, 1, 2, 0xFFFF], 2)
     assert w.tolist() == [0, 1, 0]
 
