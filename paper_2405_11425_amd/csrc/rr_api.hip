@@ -79,17 +79,10 @@ __global__ void __launch_bounds__(256) copy_kernel(u32x4 *dst, const u32x4 *src,
         __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
 }
 
-// what: bit 0 head and result cells; bit 1 ticket counters; bit 2 per-CU wave counts; bit 3 key marks
+// what: bit 0 result cells; bit 1 ticket counters; bit 2 per-CU wave counts; bit 3 key marks
 __global__ void __launch_bounds__(256) reset_kernel(Scratch *s, u32 what) {
     const u32 t = threadIdx.x;
     if (what & 1u) {
-        if (t == 0) {
-            s->checksum = 0;
-            s->t_min = ~0ull;
-            s->t_max = 0;
-            s->waves_run = 0;
-            s->unfinished = 0;
-        }
         for (u32 i = t; i < kNumCells; i += blockDim.x) {
             s->cells[i].sum = 0;
             s->cells[i].t_min = ~0ull;
@@ -106,10 +99,11 @@ __global__ void __launch_bounds__(256) reset_kernel(Scratch *s, u32 what) {
 }
 
 // After a read launch (one block of kNumCells threads, one result cell each):
-// fold the cells into the head, leave them cleared for the next launch, and
-// count the compute units whose share of tickets has not been fully claimed.
-__global__ void __launch_bounds__(kNumCells) finish_kernel(Scratch *s, const Tables *tb, u32 n_cus, u32 cpw,
-                                                           u32 ticket_mode) {
+// fold the cells into the result head (pinned host memory mapped into the
+// device, so no copy follows), leave them cleared for the next launch, and count
+// the compute units whose share of tickets has not been fully claimed.
+__global__ void __launch_bounds__(kNumCells) finish_kernel(Scratch *s, ResultHead *head, const Tables *tb,
+                                                           u32 n_cus, u32 cpw, u32 ticket_mode) {
     __shared__ u64 sh_sum[kNumCells], sh_min[kNumCells], sh_max[kNumCells];
     __shared__ u32 sh_waves[kNumCells], sh_open[kNumCells];
     const u32 t = threadIdx.x;
@@ -137,11 +131,11 @@ __global__ void __launch_bounds__(kNumCells) finish_kernel(Scratch *s, const Tab
         __syncthreads();
     }
     if (t == 0) {
-        s->checksum = sh_sum[0];
-        s->t_min = sh_min[0];
-        s->t_max = sh_max[0];
-        s->waves_run = sh_waves[0];
-        s->unfinished = sh_open[0];
+        head->checksum = sh_sum[0];
+        head->t_min = sh_min[0];
+        head->t_max = sh_max[0];
+        head->waves_run = sh_waves[0];
+        head->unfinished = sh_open[0];
     }
 }
 static_assert(kMaxCus <= kNumCells, "finish_kernel checks one compute unit per thread");
@@ -188,11 +182,6 @@ extern "C" const char *rr_last_error(void) { return g_last_error.c_str(); }
 
 namespace {
 
-struct HostHead {  // mirror of the head of Scratch, in pinned memory
-    u64 checksum, t_min, t_max;
-    u32 waves_run, unfinished;
-    u32 cu_waves[kMaxCus];
-};
 
 struct DeviceState {
     bool ready = false;
@@ -204,7 +193,10 @@ struct DeviceState {
     bool cells_clean = false;       // result cells are in their cleared state
     u16 *placement = nullptr;
     size_t placement_cap = 0;
-    HostHead *head = nullptr;     // pinned
+    ResultHead *head = nullptr;      // pinned host memory, mapped ...
+    ResultHead *head_dev = nullptr;  // ... and its address as the device sees it
+    u32 *cu_waves_host = nullptr;    // pinned staging for the per-CU wave counts
+    bool flat_tables_ready = false;  // the device tables are those of a call without a window map
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
     int wall_khz = 0;
     std::vector<rr_cu_t> cus;             // dense id -> coordinates
@@ -265,7 +257,11 @@ int get_state(hipStream_t stream, DeviceState **out) {
         if (!st.tables) HIP_TRY(hipMalloc((void **)&st.tables, sizeof(Tables)));
         if (!st.tables_host) HIP_TRY(hipHostMalloc((void **)&st.tables_host, sizeof(Tables), hipHostMallocDefault));
         if (!st.tables_last) st.tables_last = new Tables;
-        if (!st.head) HIP_TRY(hipHostMalloc((void **)&st.head, sizeof(HostHead), hipHostMallocDefault));
+        if (!st.head) {
+            HIP_TRY(hipHostMalloc((void **)&st.head, sizeof(ResultHead), hipHostMallocMapped));
+            HIP_TRY(hipHostGetDevicePointer((void **)&st.head_dev, st.head, 0));
+        }
+        if (!st.cu_waves_host) HIP_TRY(hipHostMalloc((void **)&st.cu_waves_host, kMaxCus * sizeof(u32), hipHostMallocDefault));
         if (!st.ev0) HIP_TRY(hipEventCreate(&st.ev0));
         if (!st.ev1) HIP_TRY(hipEventCreate(&st.ev1));
         HIP_TRY(hipDeviceGetAttribute(&st.wall_khz, hipDeviceAttributeWallClockRate, dev));
@@ -437,7 +433,9 @@ int run_plan(const Plan &pl, const void *region, uint32_t iters, const rr_window
     const u64 L_win = pl.n_lines / pl.n_windows;
     const u64 quota = pl.W / pl.G;
     const u64 units = (quota + lpw - 1) / lpw;  // per group
+    const bool flat_no_map = !wm && pl.mode == RR_MODE_FLAT;
     Tables &tb = *st.tables_host;
+    if (!(flat_no_map && st.flat_tables_ready)) {  // a flat launch without a map reads none of the per-call fields
     memset(&tb, 0, sizeof tb);
     for (u32 k = 0; k < kNumKeys; ++k) {
         tb.group_of_key[k] = kExcluded;
@@ -469,8 +467,10 @@ int run_plan(const Plan &pl, const void *region, uint32_t iters, const rr_window
     }
     if (!st.tables_valid || memcmp(st.tables_last, st.tables_host, sizeof(Tables)) != 0) {
         st.tables_valid = false;
+        st.flat_tables_ready = false;
         HIP_TRY(hipMemcpyAsync(st.tables, st.tables_host, sizeof(Tables), hipMemcpyHostToDevice, stream));
         memcpy(st.tables_last, st.tables_host, sizeof(Tables));  // trusted only once a later sync succeeded
+    }
     }
     const bool want_placement = opts && opts->placement_out;
     if (want_placement && st.placement_cap < pl.W) {
@@ -536,14 +536,13 @@ int run_plan(const Plan &pl, const void *region, uint32_t iters, const rr_window
         HIP_TRY(hipEventRecord(st.ev0, stream));
         HIP_TRY(hipLaunchKernel(pl.kernel, dim3((u32)grid), dim3(pl.block), args, 0, stream));
         HIP_TRY(hipEventRecord(st.ev1, stream));
-        hipLaunchKernelGGL(finish_kernel, dim3(1), dim3(kNumCells), 0, stream, st.scratch, st.tables, n_cus,
-                           p.chunks_per_wave, p.ticket_mode);
+        hipLaunchKernelGGL(finish_kernel, dim3(1), dim3(kNumCells), 0, stream, st.scratch, st.head_dev, st.tables,
+                           n_cus, p.chunks_per_wave, p.ticket_mode);
         HIP_TRY(hipGetLastError());
-        const bool want_cu_waves = opts && opts->cu_waves_out;
-        HIP_TRY(hipMemcpyAsync(st.head, st.scratch, want_cu_waves ? sizeof(HostHead) : 32, hipMemcpyDeviceToHost, stream));
         HIP_TRY(hipStreamSynchronize(stream));
         st.cells_clean = true;
         st.tables_valid = true;
+        if (flat_no_map) st.flat_tables_ready = true;
         float ms = 0.f;
         HIP_TRY(hipEventElapsedTime(&ms, st.ev0, st.ev1));
         res.launches++;
@@ -561,7 +560,11 @@ int run_plan(const Plan &pl, const void *region, uint32_t iters, const rr_window
         HIP_TRY(hipMemcpyAsync(opts->placement_out, st.placement, pl.W * sizeof(u16), hipMemcpyDeviceToHost, stream));
         HIP_TRY(hipStreamSynchronize(stream));
     }
-    if (opts && opts->cu_waves_out) memcpy(opts->cu_waves_out, st.head->cu_waves, n_cus * sizeof(u32));
+    if (opts && opts->cu_waves_out) {
+        HIP_TRY(hipMemcpyAsync(st.cu_waves_host, st.scratch->cu_waves, n_cus * sizeof(u32), hipMemcpyDeviceToHost, stream));
+        HIP_TRY(hipStreamSynchronize(stream));
+        memcpy(opts->cu_waves_out, st.cu_waves_host, n_cus * sizeof(u32));
+    }
     *out = res;
     return RR_OK;
 }
@@ -687,9 +690,9 @@ extern "C" int rr_seq_read(const void *region, uint64_t region_bytes, void *hip_
                        st->scratch);
     HIP_TRY(hipGetLastError());
     HIP_TRY(hipEventRecord(st->ev1, stream));
-    hipLaunchKernelGGL(finish_kernel, dim3(1), dim3(kNumCells), 0, stream, st->scratch, st->tables, 0u, 1u, 0u);
+    hipLaunchKernelGGL(finish_kernel, dim3(1), dim3(kNumCells), 0, stream, st->scratch, st->head_dev, st->tables, 0u,
+                       1u, 0u);
     HIP_TRY(hipGetLastError());
-    HIP_TRY(hipMemcpyAsync(st->head, st->scratch, 32, hipMemcpyDeviceToHost, stream));
     HIP_TRY(hipStreamSynchronize(stream));
     st->cells_clean = true;
     float ms = 0.f;
@@ -746,6 +749,7 @@ extern "C" int rr_shutdown(void) {
         delete st.tables_last;
         if (st.placement) (void)hipFree(st.placement);
         if (st.head) (void)hipHostFree(st.head);
+        if (st.cu_waves_host) (void)hipHostFree(st.cu_waves_host);
         if (st.ev0) (void)hipEventDestroy(st.ev0);
         if (st.ev1) (void)hipEventDestroy(st.ev1);
         st = DeviceState();

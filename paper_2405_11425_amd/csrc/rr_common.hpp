@@ -33,13 +33,17 @@ struct Cell {
 };
 static_assert(sizeof(Cell) == 128, "one cell per 128-byte line");
 
-// Device scratch, one per GPU.  The head (up to cu_waves) is copied back after every launch.
-struct Scratch {
-    u64 checksum;              // filled by finish_kernel from the cells
+// Result of one launch, written by finish_kernel straight into pinned host memory.
+struct ResultHead {
+    u64 checksum;              // wrapping sum over all result cells
     u64 t_min;
     u64 t_max;
     u32 waves_run;
     u32 unfinished;            // ticket mode: compute units whose share is not yet fully claimed
+};
+
+// Device scratch, one per GPU.
+struct Scratch {
     u32 cu_waves[kMaxCus];     // working hardware waves per dense CU id
     u32 tickets[kMaxCus * kTicketStride];  // next unclaimed ticket of each CU's share
     u32 key_seen[kNumKeys];    // CU enumeration: 1 if a workgroup ran on the CU with this key
