@@ -43,6 +43,22 @@ def _rows(path):
     return seen
 
 
+def _runs(windows, width):
+    """Contiguous runs of window ids as [start, end) ranges in units of `width`."""
+    out, start, prev = [], None, None
+    for w in windows:
+        if start is None:
+            start = prev = w
+        elif w == prev + 1:
+            prev = w
+        else:
+            out.append([start * width, (prev + 1) * width])
+            start = prev = w
+    if start is not None:
+        out.append([start * width, (prev + 1) * width])
+    return out
+
+
 class Runner:
     def __init__(self, args):
         import torch
@@ -244,7 +260,8 @@ class Runner:
             np.savetxt(base + ".zone_matrix.txt", M, fmt="%.1f")
         self.emit(key, {"experiment": "zones", "region_gib": R // wl.GiB, "n_windows": n_w,
                         "window_gib": R / n_w / wl.GiB, "n_zones": len(zones),
-                        "zones_gib": [[z[0] * R / n_w / wl.GiB, (z[-1] + 1) * R / n_w / wl.GiB] for z in zones],
+                        "zone_ranges_gib": [_runs(z, R / n_w / wl.GiB) for z in zones],
+                        "zone_sizes_gib": [len(z) * R / n_w / wl.GiB for z in zones],
                         "zone_of_window": group.tolist(),
                         "gbps_same_zone_median": round(float(np.median(same)), 1) if same else None,
                         "gbps_cross_zone_median": round(float(np.median(cross)), 1) if cross else None,
