@@ -78,6 +78,15 @@ def test_worked_first_configuration(worked):
     assert np.unique(idx).size == worked["pr1_distinct_lines"][0]
 
 
+def test_stored_values_are_reproduced_by_the_numpy_script():
+    """tests/golden/make_worked_values.py (numpy only, no oracle, no GPU) regenerates the fixture."""
+    import subprocess
+    import sys
+    script = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "make_worked_values.py")
+    out = subprocess.run([sys.executable, script, "--check"], capture_output=True, text=True)
+    assert out.returncode == 0 and "all 15 entries reproduced" in out.stdout, out.stdout + out.stderr
+
+
 # ---------------------------------------------------------------- brute force via byte addresses
 @pytest.mark.parametrize("R,B,W,I,nw,wog", [
     (4096, 128, 4, 8, 1, None),
