@@ -202,6 +202,29 @@ int rr_probe_cus(const void *region, uint64_t region_bytes, const uint32_t *cus,
 int rr_seq_read(const void *region, uint64_t region_bytes, void *hip_stream, rr_result_t *out);
 
 /*
+ * Dependent-load walk: one wavefront follows a chain of `hops` loads in which
+ * every address depends on the word just loaded, so the time per hop is the
+ * full load-to-use latency at this footprint (cache levels, then HBM, then
+ * address translation misses).  This is the latency/footprint probe of the
+ * TLB-probing literature the paper points to (Sec. 1.3, last paragraph); the
+ * paper itself argues from throughput only.
+ *   next = (line + stride + ((word0(line) ^ salt_k) & mask)) mod L,  L = region_bytes/line_bytes,
+ *   salt_k = (k * 0x9E3779B9) mod 2^32 for hop k (keeps the walk from closing into a short, cached cycle)
+ * mask 0: strided walk; mask 0xFFFFFFFF, stride 0: data-driven random walk.
+ * region: device, aligned to line_bytes; start < L; hops >= 1.
+ * out (host): line reached, wrapping sum of the words loaded, HIP-event time,
+ * and nanoseconds per hop from the in-kernel constant-rate clock.
+ */
+typedef struct {
+    uint64_t final_line;
+    uint64_t word_sum;
+    double kernel_ms_event;
+    double ns_per_hop;
+} rr_chase_result_t;
+int rr_chase(const void *region, uint64_t region_bytes, uint32_t line_bytes, uint64_t start, uint64_t stride,
+             uint32_t mask, uint64_t hops, void *hip_stream, rr_chase_result_t *out);
+
+/*
  * Plain device-to-device copy kernel of exactly known traffic (bytes read =
  * bytes written = bytes); used to calibrate profiler byte counters and as a
  * read+write streaming figure.  dst, src: device, 16-byte aligned, not

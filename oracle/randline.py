@@ -42,6 +42,8 @@ def lib():
         L.rlo_fill_words.argtypes = [u64, u64, u64, C.POINTER(u32)]
         L.rlo_sum_words.restype = i32
         L.rlo_sum_words.argtypes = [u64, u64, u64, i32, C.POINTER(u64)]
+        L.rlo_chase.restype = i32
+        L.rlo_chase.argtypes = [u64, u32, u64, u64, u64, u32, u64, C.POINTER(u64), C.POINTER(u64)]
         _lib = L
     return _lib
 
@@ -141,3 +143,14 @@ def sum_words(fill_seed: int, first_word: int, n_words: int, n_threads: int = 1)
     if rc != 0:
         raise ValueError("rlo_sum_words: invalid argument")
     return int(out.value)
+
+
+def chase(region_bytes: int, line_bytes: int, fill_seed: int, start: int, stride: int, mask: int,
+          hops: int) -> Tuple[int, int]:
+    """Dependent-load walk: (line reached, wrapping sum of the words loaded)."""
+    final, total = C.c_uint64(0), C.c_uint64(0)
+    rc = lib().rlo_chase(region_bytes, line_bytes, fill_seed, start, stride, mask, hops,
+                         C.byref(final), C.byref(total))
+    if rc != 0:
+        raise ValueError("rlo_chase: invalid argument")
+    return int(final.value), int(total.value)

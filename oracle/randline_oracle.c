@@ -238,3 +238,34 @@ int rlo_sum_words(uint64_t fill_seed, uint64_t first_word, uint64_t n_words, int
     *sum = total;
     return RLO_OK;
 }
+
+/*
+ * Dependent-load walk (a latency probe in the spirit of the TLB-probing work
+ * the paper cites in Sec. 1.3; the paper itself does not run one).  Starting at
+ * line `start`, each hop loads 32-bit word 0 of the current line and moves to
+ *     next = (line + stride + ((word ^ salt_k) & mask)) mod L ,   L = region_bytes/line_bytes,
+ * where salt_k = (k * 0x9E3779B9) mod 2^32 for hop k = 0, 1, ...  The salt makes the step depend
+ * on the hop number as well, so the walk is not the iteration of one fixed map and cannot fall
+ * into a short cycle (which would sit in the caches).  mask = 0 gives a plain strided walk,
+ * mask = 0xFFFFFFFF with stride 0 a data-driven pseudo-random walk.  Returns the line reached
+ * after `hops` hops and the wrapping 64-bit sum of the words loaded on the way.
+ */
+int rlo_chase(uint64_t region_bytes, uint32_t line_bytes, uint64_t fill_seed, uint64_t start,
+              uint64_t stride, uint32_t mask, uint64_t hops, uint64_t *final_line, uint64_t *word_sum) {
+    if (line_bytes != 128 && line_bytes != 256 && line_bytes != 512) return RLO_EINVAL;
+    if (region_bytes == 0 || region_bytes % line_bytes != 0) return RLO_EINVAL;
+    if (final_line == NULL || word_sum == NULL) return RLO_EINVAL;
+    uint64_t L = region_bytes / line_bytes;
+    if (start >= L) return RLO_EINVAL;
+    uint64_t words_per_line = line_bytes / 4;
+    uint64_t line = start, sum = 0;
+    for (uint64_t k = 0; k < hops; ++k) {
+        uint32_t word = rlo_fill_word(fill_seed, line * words_per_line);
+        sum += (uint64_t)word;
+        uint32_t salt = (uint32_t)(k * 0x9E3779B9ULL);
+        line = (line + stride % L + (uint64_t)((word ^ salt) & mask)) % L;
+    }
+    *final_line = line;
+    *word_sum = sum;
+    return RLO_OK;
+}

@@ -41,6 +41,11 @@ class _Result(C.Structure):
                 ("kernel_ms_device", C.c_double), ("waves_run", C.c_uint32), ("launches", C.c_uint32)]
 
 
+class _ChaseResult(C.Structure):
+    _fields_ = [("final_line", C.c_uint64), ("word_sum", C.c_uint64), ("kernel_ms_event", C.c_double),
+                ("ns_per_hop", C.c_double)]
+
+
 class _Opts(C.Structure):
     _fields_ = [("block_threads", C.c_uint32), ("grid_blocks", C.c_uint32), ("unroll", C.c_uint32),
                 ("mode", C.c_uint32), ("bcast", C.c_uint32), ("nontemporal", C.c_uint32),
@@ -49,7 +54,7 @@ class _Opts(C.Structure):
                 ("cu_waves_out", C.POINTER(C.c_uint32))]
 
 
-EXPORTS = ["rr_enumerate_cus", "rr_fill", "rr_rand_read", "rr_probe_pair", "rr_probe_cus", "rr_seq_read", "rr_copy",
+EXPORTS = ["rr_enumerate_cus", "rr_fill", "rr_rand_read", "rr_probe_pair", "rr_probe_cus", "rr_seq_read", "rr_copy", "rr_chase",
            "rr_groups_from_heatmap", "rr_shutdown", "rr_strerror", "rr_last_error"]
 
 _lib = None
@@ -90,6 +95,8 @@ def lib():
         L.rr_seq_read.argtypes = [vp, u64, vp, C.POINTER(_Result)]
         L.rr_copy.restype = C.c_int
         L.rr_copy.argtypes = [vp, vp, u64, vp, C.POINTER(C.c_double)]
+        L.rr_chase.restype = C.c_int
+        L.rr_chase.argtypes = [vp, u64, u32, u64, u64, u32, u64, vp, C.POINTER(_ChaseResult)]
         L.rr_groups_from_heatmap.restype = C.c_int
         L.rr_groups_from_heatmap.argtypes = [C.POINTER(C.c_double), u32, C.POINTER(C.c_double), C.c_double,
                                              C.POINTER(C.c_uint16), C.POINTER(u32), C.POINTER(u32),
@@ -255,6 +262,23 @@ def copy(dst, src, nbytes: Optional[int] = None, stream=None) -> float:
     ms = C.c_double(0.0)
     _check(lib().rr_copy(dptr, sptr, min(dbytes, sbytes), _stream(stream), C.byref(ms)))
     return float(ms.value)
+
+
+@dataclass
+class ChaseResult:
+    final_line: int
+    word_sum: int
+    kernel_ms_event: float
+    ns_per_hop: float
+
+
+def chase(region, line_bytes: int, start: int, stride: int, mask: int, hops: int,
+          region_bytes: Optional[int] = None, stream=None) -> ChaseResult:
+    """Dependent-load walk by one wavefront (latency probe); see rr_chase."""
+    ptr, nbytes = _region(region, region_bytes)
+    res = _ChaseResult()
+    _check(lib().rr_chase(ptr, nbytes, line_bytes, start, stride, mask, hops, _stream(stream), C.byref(res)))
+    return ChaseResult(int(res.final_line), int(res.word_sum), res.kernel_ms_event, res.ns_per_hop)
 
 
 def groups_from_heatmap(T: np.ndarray, singles: Optional[np.ndarray] = None, min_gap: float = 0.05):

@@ -71,6 +71,30 @@ __global__ void __launch_bounds__(256) seq_read_kernel(const u32x4 *src, u64 n_v
     }
 }
 
+// Dependent-load walk by a single wavefront; every lane follows the same chain
+// (uniform address, broadcast load), lane 0 reports.
+struct ChaseOut {
+    u64 final_line, word_sum, ticks;
+};
+__global__ void __launch_bounds__(64) chase_kernel(const char *region, Reducer red, u32 log2_line, u64 start,
+                                                   u64 stride, u32 mask, u64 hops, ChaseOut *out) {
+    typedef const u32 __attribute__((address_space(1))) *gptr;
+    u64 line = start, sum = 0;
+    const u64 t0 = clock_ticks();
+    for (u64 k = 0; k < hops; ++k) {
+        const u32 word = *(gptr)((u64)region + (line << log2_line));
+        sum += word;
+        const u32 salt = (u32)k * 0x9E3779B9u;  // hop-dependent, so the walk cannot close into a short cycle
+        line = reduce_to_line(line + stride + (u64)((word ^ salt) & mask), red);
+    }
+    const u64 t1 = clock_ticks();
+    if (threadIdx.x == 0) {
+        out->final_line = line;
+        out->word_sum = sum;
+        out->ticks = t1 - t0;
+    }
+}
+
 // Plain copy, 16 bytes per lane and step, grid-stride: a kernel of exactly known
 // HBM traffic (bytes read = bytes written = n_vec * 16).
 __global__ void __launch_bounds__(256) copy_kernel(u32x4 *dst, const u32x4 *src, u64 n_vec) {
@@ -703,6 +727,44 @@ extern "C" int rr_seq_read(const void *region, uint64_t region_bytes, void *hip_
     res.waves_run = st->head->waves_run;
     res.launches = 1;
     *out = res;
+    return RR_OK;
+}
+
+extern "C" int rr_chase(const void *region, uint64_t region_bytes, uint32_t line_bytes, uint64_t start,
+                        uint64_t stride, uint32_t mask, uint64_t hops, void *hip_stream, rr_chase_result_t *out) {
+    if (!out) return fail(RR_EINVAL, "out is NULL");
+    if (!region) return fail(RR_EINVAL, "region is NULL");
+    if (line_bytes != 128 && line_bytes != 256 && line_bytes != 512)
+        return fail(RR_EINVAL, "line_bytes must be 128, 256 or 512 (got %u)", line_bytes);
+    if (region_bytes == 0 || region_bytes % line_bytes != 0)
+        return fail(RR_EINVAL, "region_bytes must be a positive multiple of line_bytes");
+    if ((uintptr_t)region % line_bytes != 0) return fail(RR_EINVAL, "region is not aligned to line_bytes");
+    const u64 n_lines = region_bytes / line_bytes;
+    if (n_lines > (1ull << 32)) return fail(RR_EINVAL, "region has more than 2^32 lines");
+    if (start >= n_lines) return fail(RR_EINVAL, "start must be below the number of lines");
+    if (hops == 0) return fail(RR_EINVAL, "hops must be at least 1");
+    hipStream_t stream = (hipStream_t)hip_stream;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    DeviceState *st = nullptr;
+    int rc = get_state(stream, &st);
+    if (rc != RR_OK) return rc;
+    // the walk's three result words go through the (otherwise idle) key-mark area of the scratch
+    ChaseOut *dev_out = (ChaseOut *)st->scratch->key_seen;
+    const u32 log2_line = line_bytes == 128 ? 7 : line_bytes == 256 ? 8 : 9;
+    HIP_TRY(hipEventRecord(st->ev0, stream));
+    hipLaunchKernelGGL(chase_kernel, dim3(1), dim3(64), 0, stream, (const char *)region, make_reducer(n_lines),
+                       log2_line, (u64)start, (u64)(stride % n_lines), mask, (u64)hops, dev_out);
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipEventRecord(st->ev1, stream));
+    ChaseOut host;
+    HIP_TRY(hipMemcpyAsync(&host, dev_out, sizeof host, hipMemcpyDeviceToHost, stream));
+    HIP_TRY(hipStreamSynchronize(stream));
+    float ms = 0.f;
+    HIP_TRY(hipEventElapsedTime(&ms, st->ev0, st->ev1));
+    out->final_line = host.final_line;
+    out->word_sum = host.word_sum;
+    out->kernel_ms_event = ms;
+    out->ns_per_hop = (double)host.ticks * 1e6 / (double)st->wall_khz / (double)hops;
     return RR_OK;
 }
 

@@ -2,7 +2,7 @@
 measured point to a JSONL file (points already present are skipped, so a run can be resumed).
 
     python -m paper_2405_11425_amd.sweep region  [--out results.jsonl] [--reps 5]
-    python -m paper_2405_11425_amd.sweep lines | windows | probe | stream | zones | groups | calib | all
+    python -m paper_2405_11425_amd.sweep lines | windows | probe | stream | zones | groups | latency | calib | all
 
   region   throughput vs region size, uniform random 128-byte lines        (paper Sec. 2.1, Fig. 1)
   lines    32 x {4,8,16} B and 64 x 4 B lines at 128 GiB and the largest region (Sec. 2.1, text)
@@ -13,6 +13,8 @@ measured point to a JSONL file (points already present are skipped, so a run can
            (the pair-probe idea of Sec. 2.2 applied to memory instead of compute units)
   groups   each XCD alone, CU-count scaling inside one XCD vs spread over all, pairs of XCDs on
            disjoint 40 GiB regions                                               (Sec. 2.3, Fig. 4)
+  latency  dependent-load walk of one wavefront: nanoseconds per hop vs footprint, 1 MiB .. the largest
+           power-of-two region (the latency/footprint probe of the TLB literature the paper cites)
   calib    one copy, one fill, one sequential read of known size (for profiler counter calibration)
 
 Throughput is n_reads * line_bytes / kernel time (HIP events), decimal GB/s, and as a
@@ -327,6 +329,25 @@ class Runner:
                             "gbps_alone": alone, "gbps_pairs": pairs, "pair_over_sum_of_singles": ratios,
                             "ratio_min": min(ratios.values()), "ratio_max": max(ratios.values()), **self.meta})
 
+    def latency(self):
+        """Nanoseconds per dependent load vs footprint (power-of-two footprints: other sizes put the slower
+        exact-remainder arithmetic into the dependency chain, about 35 ns more per hop)."""
+        rl, wl = self.rl, self.wl
+        hops = 20000
+        mib = 1
+        while mib <= self.max_gib * 1024:
+            key = f"latency/{mib}MiB"
+            R = mib * wl.MiB
+            if key not in self.seen:
+                rl.chase(self.region, 128, 0, 0, 0xFFFFFFFF, 2000, region_bytes=R)
+                runs = [rl.chase(self.region, 128, 7 * i, 0, 0xFFFFFFFF, hops, region_bytes=R) for i in range(5)]
+                ns = [r.ns_per_hop for r in runs]
+                self.emit(key, {"experiment": "latency", "footprint_mib": mib, "hops": hops,
+                                "ns_per_hop": round(statistics.median(ns), 1), "ns_per_hop_min": round(min(ns), 1),
+                                "ns_per_hop_max": round(max(ns), 1), "final_line": runs[0].final_line,
+                                "word_sum": runs[0].word_sum, **self.meta})
+            mib *= 4 if mib < 1024 else 2
+
     def calib(self):
         """Three kernels of exactly known traffic, 8 GiB each, for scaling FETCH_SIZE / WRITE_SIZE."""
         rl, wl = self.rl, self.wl
@@ -341,7 +362,7 @@ class Runner:
 def main(argv=None):
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
     ap.add_argument("experiment", choices=["region", "lines", "windows", "probe", "stream", "zones", "groups",
-                                           "calib", "all"])
+                                           "latency", "calib", "all"])
     ap.add_argument("--zone-windows", type=int, default=32)
     ap.add_argument("--out", default=None, help="JSONL file to append to (and to resume from)")
     ap.add_argument("--reps", type=int, default=5)
@@ -355,11 +376,12 @@ def main(argv=None):
     ap.add_argument("--block", type=int, default=0)
     args = ap.parse_args(argv)
     r = Runner(args)
-    todo = (["region", "lines", "windows", "stream", "groups", "zones", "probe"] if args.experiment == "all"
+    todo = (["region", "lines", "windows", "stream", "latency", "groups", "zones", "probe"] if args.experiment == "all"
             else [args.experiment])
     for name in todo:
         {"region": r.region_sweep, "lines": r.line_sweep, "windows": r.window_sweep, "probe": r.probe,
-         "stream": r.stream, "zones": r.zones, "groups": r.groups, "calib": r.calib}[name]()
+         "stream": r.stream, "zones": r.zones, "groups": r.groups, "latency": r.latency,
+         "calib": r.calib}[name]()
     return 0
 
 

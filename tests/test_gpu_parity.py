@@ -116,6 +116,26 @@ def test_copy_kernel():
         rl.copy(src[16:n], src[:n - 16])       # overlap
 
 
+# ------------------------------------------------------------------ dependent-load walk
+@pytest.mark.parametrize("R,B,start,stride,mask,hops", [
+    (1 << 16, 128, 0, 0, 0xFFFFFFFF, 1000),          # data-driven walk inside the L2
+    (12288, 128, 95, 7, 0xFF, 500),                  # 96 lines, exact remainder
+    (3 << 20, 256, 5, 12345, 0, 2000),               # strided
+    (5 << 19, 512, 1, 0, 0xFFFFFFFF, 1),             # a single hop
+    (1 << 34, 128, 12345, 1 << 14, 0xFFFFFFFF, 5000),  # 16 GiB, one new 2 MiB page per hop on top of the data term
+])
+def test_chase_matches_oracle(region, R, B, start, stride, mask, hops):
+    got = rl.chase(region, B, start, stride, mask, hops, region_bytes=R)
+    assert (got.final_line, got.word_sum) == orc.chase(R, B, wl.FILL_SEED, start, stride, mask, hops)
+    assert got.ns_per_hop > 0
+
+
+def test_chase_full_region(region):
+    R = region.numel()
+    got = rl.chase(region, 128, 0, 0, 0xFFFFFFFF, 20000)
+    assert (got.final_line, got.word_sum) == orc.chase(R, 128, wl.FILL_SEED, 0, 0, 0xFFFFFFFF, 20000)
+
+
 # ------------------------------------------------------------------ rand_read, small cases
 SMALL = [
     # region bytes, line, lanes, W, I

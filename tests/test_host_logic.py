@@ -96,6 +96,15 @@ def test_fill_and_probe_validation():
         rl.probe_cus(FAKE, [], 8, 8, 7)
 
 
+def test_chase_validation():
+    for args, needle in ((((0, 4096), 128, 0, 0, 0, 1), "NULL"), ((FAKE, 100, 0, 0, 0, 1), "line_bytes"),
+                         ((FAKE, 128, 1 << 13, 0, 0, 1), "start"), ((FAKE, 128, 0, 0, 0, 0), "hops"),
+                         (((1 << 21, 1000), 128, 0, 0, 0, 1), "multiple")):
+        with pytest.raises(rl.RandlineError) as e:
+            rl.chase(*args)
+        assert e.value.code == rl.RR_EINVAL and needle in str(e.value)
+
+
 def test_out_left_untouched_on_failure():
     res = rl.binding._Result(123, 1.0, 2.0, 4, 5)
     rc = rl.lib().rr_rand_read(1 << 21, 1000, 128, 32, 8, 8, None, 7, None, None, C.byref(res))

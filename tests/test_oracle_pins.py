@@ -244,3 +244,33 @@ def test_uniformity_statistics(worked):
     mean = orc.checksum(R, B, 256, 4096, 1, 7, n_threads=4) / (n * 32)
     assert int(mean) == worked["pr1_mean_word"][0]
     assert abs(mean - 2 ** 31) < 5 * (2 ** 32 / math.sqrt(12)) / math.sqrt(n * 32) * 40  # lines repeat
+
+
+# ---------------------------------------------------------------- dependent-load walk
+def test_chase_bruteforce_byte_addresses():
+    """The walk through real byte addresses of a materialised region (wrong word, wrong modulus,
+    stride or mask dropped)."""
+    import struct
+    for R, B in ((1 << 16, 128), (96 * 256, 256), (15 * 512, 512)):
+        region = pybrute.region_bytes(R, 1)
+        L = R // B
+        for start, stride, mask, hops in ((0, 0, 0xFFFFFFFF, 100), (5, 7, 0, 1000), (3, 123456789, 0xFFFF, 257),
+                                          (L - 1, 1, 0, 3), (2, 0, 0, 9)):
+            line, total = start, 0
+            for k in range(hops):
+                word = struct.unpack_from("<I", region, line * B)[0]
+                total += word
+                line = (line + stride + ((word ^ (k * 0x9E3779B9 & 0xFFFFFFFF)) & mask)) % L
+            assert orc.chase(R, B, 1, start, stride, mask, hops) == (line, total & M64)
+
+
+def test_chase_closed_forms():
+    R, B = 192 << 30, 128                     # 3 * 2^30 lines: 64-bit line arithmetic
+    L = R // B
+    final, total = orc.chase(R, B, 1, 17, 1 << 14, 0, 1000)
+    assert final == (17 + 1000 * (1 << 14)) % L      # mask 0: a pure strided walk
+    lines = [(17 + k * (1 << 14)) % L for k in range(1000)]
+    assert total == sum(orc.fill_word(1, l * 32) for l in lines) & M64
+    assert orc.chase(R, B, 1, 5, 0, 0, 10) == (5, 10 * orc.fill_word(1, 5 * 32))   # standing still
+    with pytest.raises(ValueError):
+        orc.chase(R, B, 1, L, 0, 0, 1)
