@@ -193,6 +193,26 @@ int rr_probe_cus(const void *region, uint64_t region_bytes, const uint32_t *cus,
                  const rr_launch_opts_t *opts, rr_result_t *out);
 
 /*
+ * Random line write and read-modify-write: the access stream of rr_rand_read
+ * (no windows; logical wave w, iteration it -> line), but every lane stores to
+ * (RR_OP_WRITE) or atomically adds to (RR_OP_ADD) its words of the line.  The
+ * paper motivates the benchmark with an application that wants random access
+ * to a large part of the memory (Sec. 1.3) and measures reads; these are that
+ * application's other two access kinds.
+ *   value of 32-bit word i (64-bit word index): v(i) = low 32 bits of (value_seed + i * 0x9E3779B1)
+ *   RR_OP_WRITE: word i <- v(i)            RR_OP_ADD: word i <- word i + v(i) (mod 2^32, device-scope atomic)
+ * The final content of the region does not depend on the order of execution.
+ * out->checksum = wrapping 64-bit sum of v(i) over all words of all lines hit (repeats count);
+ * throughput = n_updates * line_bytes / time (an add moves twice that in DRAM).
+ * Arguments as for rr_rand_read; region is written.
+ */
+#define RR_OP_WRITE 1
+#define RR_OP_ADD 2
+int rr_rand_update(void *region, uint64_t region_bytes, uint32_t line_bytes, uint32_t lanes_per_line,
+                   uint64_t n_updates, uint32_t iters_per_wave, uint64_t draw_seed, uint32_t op,
+                   uint64_t value_seed, void *hip_stream, rr_result_t *out);
+
+/*
  * Streaming read of the whole region: every 32-bit word is read once, in address
  * order per wave (the sequential access the paper expects to beat random lines,
  * Sec. 2.1).  region: device, 16-byte aligned; region_bytes: multiple of 16.

@@ -44,6 +44,12 @@ def lib():
         L.rlo_sum_words.argtypes = [u64, u64, u64, i32, C.POINTER(u64)]
         L.rlo_chase.restype = i32
         L.rlo_chase.argtypes = [u64, u32, u64, u64, u64, u32, u64, C.POINTER(u64), C.POINTER(u64)]
+        L.rlo_update_value.restype = u32
+        L.rlo_update_value.argtypes = [u64, u64]
+        L.rlo_update_checksum.restype = i32
+        L.rlo_update_checksum.argtypes = [u64, u32, u64, u32, u64, u64, C.POINTER(u64)]
+        L.rlo_apply_updates.restype = i32
+        L.rlo_apply_updates.argtypes = [C.c_void_p, u64, u32, u64, u32, u64, u32, u64]
         _lib = L
     return _lib
 
@@ -154,3 +160,26 @@ def chase(region_bytes: int, line_bytes: int, fill_seed: int, start: int, stride
     if rc != 0:
         raise ValueError("rlo_chase: invalid argument")
     return int(final.value), int(total.value)
+
+
+OP_WRITE, OP_ADD = 1, 2
+
+
+def update_value(value_seed: int, i: int) -> int:
+    return int(lib().rlo_update_value(value_seed, i))
+
+
+def update_checksum(region_bytes: int, line_bytes: int, W: int, I: int, draw_seed: int, value_seed: int) -> int:
+    out = C.c_uint64(0)
+    rc = lib().rlo_update_checksum(region_bytes, line_bytes, W, I, draw_seed, value_seed, C.byref(out))
+    if rc != 0:
+        raise ValueError("rlo_update_checksum: invalid argument")
+    return int(out.value)
+
+
+def apply_updates(buf: np.ndarray, line_bytes: int, W: int, I: int, draw_seed: int, op: int, value_seed: int) -> None:
+    """Perform the random line writes / adds on a host buffer (uint8 array), in place."""
+    assert buf.dtype == np.uint8 and buf.flags["C_CONTIGUOUS"]
+    rc = lib().rlo_apply_updates(buf.ctypes.data_as(C.c_void_p), buf.size, line_bytes, W, I, draw_seed, op, value_seed)
+    if rc != 0:
+        raise ValueError("rlo_apply_updates: invalid argument")

@@ -269,3 +269,53 @@ int rlo_chase(uint64_t region_bytes, uint32_t line_bytes, uint64_t fill_seed, ui
     *word_sum = sum;
     return RLO_OK;
 }
+
+/*
+ * Random line write / read-modify-write (the other two access kinds of the
+ * application the paper has in mind, Sec. 1.3; it measures reads only).  The
+ * lines are those of the read benchmark without windows: logical wave w,
+ * iteration it -> line H(draw_seed, w, it) mod L.  Every 32-bit word i of such a
+ * line receives the value v(i) = low 32 bits of (value_seed + i * 0x9E3779B1):
+ *   op 1 (write): word i = v(i);      op 2 (add): word i = word i + v(i) mod 2^32.
+ * rlo_update_value      : v(i).
+ * rlo_update_checksum   : wrapping 64-bit sum of v(i) over all words of all lines hit (repeats count).
+ * rlo_apply_updates     : performs the updates, one after the other, on a host buffer.
+ */
+uint32_t rlo_update_value(uint64_t value_seed, uint64_t i) {
+    return (uint32_t)((value_seed + i * 0x9E3779B1ULL) & 0xFFFFFFFFULL);
+}
+
+int rlo_update_checksum(uint64_t region_bytes, uint32_t line_bytes, uint64_t W, uint32_t I,
+                        uint64_t draw_seed, uint64_t value_seed, uint64_t *checksum) {
+    int rc = check_args(region_bytes, line_bytes, 1, 1, NULL);
+    if (rc != RLO_OK || checksum == NULL) return RLO_EINVAL;
+    uint64_t L = region_bytes / line_bytes, words_per_line = line_bytes / 4, total = 0;
+    for (uint64_t w = 0; w < W; ++w)
+        for (uint64_t it = 0; it < I; ++it) {
+            uint64_t line = rlo_index_hash(draw_seed, w, it) % L;
+            for (uint64_t j = 0; j < words_per_line; ++j)
+                total += (uint64_t)rlo_update_value(value_seed, line * words_per_line + j);
+        }
+    *checksum = total;
+    return RLO_OK;
+}
+
+int rlo_apply_updates(void *buf, uint64_t region_bytes, uint32_t line_bytes, uint64_t W, uint32_t I,
+                      uint64_t draw_seed, uint32_t op, uint64_t value_seed) {
+    int rc = check_args(region_bytes, line_bytes, 1, 1, NULL);
+    if (rc != RLO_OK || buf == NULL || (op != 1 && op != 2)) return RLO_EINVAL;
+    uint64_t L = region_bytes / line_bytes, words_per_line = line_bytes / 4;
+    unsigned char *base = (unsigned char *)buf;
+    for (uint64_t w = 0; w < W; ++w)
+        for (uint64_t it = 0; it < I; ++it) {
+            uint64_t line = rlo_index_hash(draw_seed, w, it) % L;
+            for (uint64_t j = 0; j < words_per_line; ++j) {
+                uint64_t i = line * words_per_line + j;
+                uint32_t v = rlo_update_value(value_seed, i), old;
+                memcpy(&old, base + 4 * i, 4);
+                uint32_t now = (op == 1) ? v : (uint32_t)(old + v);
+                memcpy(base + 4 * i, &now, 4);
+            }
+        }
+    return RLO_OK;
+}

@@ -19,6 +19,7 @@ RR_CU_EXCLUDED = 0xFFFF
 BCAST_DEFAULT, BCAST_LDS, BCAST_DPP, BCAST_READLANE = 0, 1, 2, 3
 MODE_AUTO, MODE_FLAT, MODE_TICKET = 0, 1, 2
 NT_DEFAULT, NT_ON, NT_OFF = 0, 1, 2
+OP_WRITE, OP_ADD = 1, 2
 
 
 class RandlineError(RuntimeError):
@@ -54,7 +55,7 @@ class _Opts(C.Structure):
                 ("cu_waves_out", C.POINTER(C.c_uint32))]
 
 
-EXPORTS = ["rr_enumerate_cus", "rr_fill", "rr_rand_read", "rr_probe_pair", "rr_probe_cus", "rr_seq_read", "rr_copy", "rr_chase",
+EXPORTS = ["rr_enumerate_cus", "rr_fill", "rr_rand_read", "rr_probe_pair", "rr_probe_cus", "rr_seq_read", "rr_copy", "rr_chase", "rr_rand_update",
            "rr_groups_from_heatmap", "rr_shutdown", "rr_strerror", "rr_last_error"]
 
 _lib = None
@@ -95,6 +96,8 @@ def lib():
         L.rr_seq_read.argtypes = [vp, u64, vp, C.POINTER(_Result)]
         L.rr_copy.restype = C.c_int
         L.rr_copy.argtypes = [vp, vp, u64, vp, C.POINTER(C.c_double)]
+        L.rr_rand_update.restype = C.c_int
+        L.rr_rand_update.argtypes = [vp, u64, u32, u32, u64, u32, u64, u32, u64, vp, C.POINTER(_Result)]
         L.rr_chase.restype = C.c_int
         L.rr_chase.argtypes = [vp, u64, u32, u64, u64, u32, u64, vp, C.POINTER(_ChaseResult)]
         L.rr_groups_from_heatmap.restype = C.c_int
@@ -262,6 +265,18 @@ def copy(dst, src, nbytes: Optional[int] = None, stream=None) -> float:
     ms = C.c_double(0.0)
     _check(lib().rr_copy(dptr, sptr, min(dbytes, sbytes), _stream(stream), C.byref(ms)))
     return float(ms.value)
+
+
+def rand_update(region, line_bytes: int, n_updates: int, iters_per_wave: int, draw_seed: int, op: int,
+                value_seed: int, lanes_per_line: int = 32, region_bytes: Optional[int] = None,
+                stream=None) -> ReadResult:
+    """Random line write (OP_WRITE) or atomic add (OP_ADD); see rr_rand_update."""
+    ptr, nbytes = _region(region, region_bytes)
+    res = _Result()
+    _check(lib().rr_rand_update(ptr, nbytes, line_bytes, lanes_per_line, n_updates, iters_per_wave, draw_seed, op,
+                                value_seed, _stream(stream), C.byref(res)))
+    return ReadResult(int(res.checksum), res.kernel_ms_event, res.kernel_ms_device, int(res.waves_run),
+                      int(res.launches))
 
 
 @dataclass

@@ -11,6 +11,7 @@
 
 #include "../../include/randline.h"
 #include "rr_phased_kernel.hpp"
+#include "rr_update_kernel.hpp"
 
 namespace rr {
 
@@ -713,6 +714,65 @@ extern "C" int rr_seq_read(const void *region, uint64_t region_bytes, void *hip_
     hipLaunchKernelGGL(seq_read_kernel, dim3((u32)blocks), dim3(256), 0, stream, (const u32x4 *)region, n_vec,
                        st->scratch);
     HIP_TRY(hipGetLastError());
+    HIP_TRY(hipEventRecord(st->ev1, stream));
+    hipLaunchKernelGGL(finish_kernel, dim3(1), dim3(kNumCells), 0, stream, st->scratch, st->head_dev, st->tables, 0u,
+                       1u, 0u);
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipStreamSynchronize(stream));
+    st->cells_clean = true;
+    float ms = 0.f;
+    HIP_TRY(hipEventElapsedTime(&ms, st->ev0, st->ev1));
+    res.checksum = st->head->checksum;
+    res.kernel_ms_event = ms;
+    res.kernel_ms_device = (double)(st->head->t_max - st->head->t_min) / (double)st->wall_khz;
+    res.waves_run = st->head->waves_run;
+    res.launches = 1;
+    *out = res;
+    return RR_OK;
+}
+
+extern "C" int rr_rand_update(void *region, uint64_t region_bytes, uint32_t line_bytes, uint32_t lanes_per_line,
+                              uint64_t n_updates, uint32_t iters_per_wave, uint64_t draw_seed, uint32_t op,
+                              uint64_t value_seed, void *hip_stream, rr_result_t *out) {
+    Plan pl;
+    int rc = make_plan(region, region_bytes, line_bytes, lanes_per_line, n_updates, iters_per_wave, nullptr, nullptr,
+                       out, pl);
+    if (rc != RR_OK) return rc;
+    if (op != RR_OP_WRITE && op != RR_OP_ADD) return fail(RR_EINVAL, "op must be RR_OP_WRITE or RR_OP_ADD");
+    kernel_handle kernel = find_update_kernel(pl.lanes, pl.wdw, op);
+    if (!kernel) return fail(RR_EINVAL, "no update kernel for this line shape");
+    rr_result_t res;
+    memset(&res, 0, sizeof res);
+    if (pl.W == 0) {
+        *out = res;
+        return RR_OK;
+    }
+    const u64 hw_waves = (pl.W + 64 / pl.lanes - 1) / (64 / pl.lanes);
+    const u64 grid = (hw_waves + 3) / 4;
+    if (grid > 0x7FFFFFFFull) return fail(RR_EINVAL, "launch of %llu workgroups is out of range", grid);
+    hipStream_t stream = (hipStream_t)hip_stream;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    DeviceState *st = nullptr;
+    rc = get_state(stream, &st);
+    if (rc != RR_OK) return rc;
+    UpdateParams p;
+    memset(&p, 0, sizeof p);
+    p.region = (char *)region;
+    p.draw_seed = draw_seed;
+    p.value_seed = value_seed;
+    p.n_waves = pl.W;
+    p.iters = iters_per_wave;
+    p.log2_line = pl.log2_line;
+    p.red = make_reducer(pl.n_lines);
+    p.scratch = st->scratch;
+    if (!st->cells_clean) {
+        hipLaunchKernelGGL(reset_kernel, dim3(1), dim3(256), 0, stream, st->scratch, 1u);
+        HIP_TRY(hipGetLastError());
+    }
+    st->cells_clean = false;
+    void *args[] = {(void *)&p};
+    HIP_TRY(hipEventRecord(st->ev0, stream));
+    HIP_TRY(hipLaunchKernel(kernel, dim3((u32)grid), dim3(256), args, 0, stream));
     HIP_TRY(hipEventRecord(st->ev1, stream));
     hipLaunchKernelGGL(finish_kernel, dim3(1), dim3(kNumCells), 0, stream, st->scratch, st->head_dev, st->tables, 0u,
                        1u, 0u);

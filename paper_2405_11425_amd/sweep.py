@@ -2,7 +2,7 @@
 measured point to a JSONL file (points already present are skipped, so a run can be resumed).
 
     python -m paper_2405_11425_amd.sweep region  [--out results.jsonl] [--reps 5]
-    python -m paper_2405_11425_amd.sweep lines | windows | probe | stream | zones | groups | latency | calib | all
+    python -m paper_2405_11425_amd.sweep lines | windows | probe | stream | zones | groups | latency | updates | calib | all
 
   region   throughput vs region size, uniform random 128-byte lines        (paper Sec. 2.1, Fig. 1)
   lines    32 x {4,8,16} B and 64 x 4 B lines at 128 GiB and the largest region (Sec. 2.1, text)
@@ -13,6 +13,7 @@ measured point to a JSONL file (points already present are skipped, so a run can
            (the pair-probe idea of Sec. 2.2 applied to memory instead of compute units)
   groups   each XCD alone, CU-count scaling inside one XCD vs spread over all, pairs of XCDs on
            disjoint 40 GiB regions                                               (Sec. 2.3, Fig. 4)
+  updates  random 128-byte line writes and atomic adds vs region size      (the application of Sec. 1.3)
   latency  dependent-load walk of one wavefront: nanoseconds per hop vs footprint, 1 MiB .. the largest
            power-of-two region (the latency/footprint probe of the TLB literature the paper cites)
   calib    one copy, one fill, one sequential read of known size (for profiler counter calibration)
@@ -329,6 +330,31 @@ class Runner:
                             "gbps_alone": alone, "gbps_pairs": pairs, "pair_over_sum_of_singles": ratios,
                             "ratio_min": min(ratios.values()), "ratio_max": max(ratios.values()), **self.meta})
 
+    def updates(self):
+        """Random 128-byte line writes and atomic adds vs region size (the fill is restored afterwards)."""
+        rl, wl = self.rl, self.wl
+        n = len(self.cus)
+        touched = False
+        for gib in sorted({min(16, self.max_gib), min(64, self.max_gib), self.max_gib}):
+            cfg = wl.ReadConfig(f"update-{gib}GiB", gib * wl.GiB, 128, 32, wl.resident_logical_waves(n), wl.ITERS_PER_WAVE)
+            for op, name in ((rl.OP_WRITE, "write"), (rl.OP_ADD, "add")):
+                key = f"updates/{name}/{cfg.name}"
+                if key in self.seen:
+                    continue
+                touched = True
+                call = lambda seed: rl.rand_update(self.region, 128, cfg.n_reads, cfg.iters_per_wave, seed, op, 99,
+                                                   region_bytes=cfg.region_bytes)
+                call(1000)
+                res = [call(cfg.read_seed + i) for i in range(self.args.reps)]
+                med = statistics.median(r.kernel_ms_event for r in res)
+                self.emit(key, {"experiment": "updates", "op": name, "region_gib": gib, "n_updates": cfg.n_reads,
+                                "kernel_ms_median": round(med, 4), "gbps_lines": round(cfg.bytes_read / med / 1e6, 1),
+                                "pct_of_hbm_peak": round(cfg.bytes_read / med / 1e6 / HBM_PEAK_GBPS * 100, 1),
+                                "note": "line bytes per second; an add reads and writes every line",
+                                "checksum_first_seed": res[0].checksum, **self.meta})
+        if touched:
+            rl.fill(self.region, wl.FILL_SEED)
+
     def latency(self):
         """Nanoseconds per dependent load vs footprint (power-of-two footprints: other sizes put the slower
         exact-remainder arithmetic into the dependency chain, about 35 ns more per hop)."""
@@ -362,7 +388,7 @@ class Runner:
 def main(argv=None):
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
     ap.add_argument("experiment", choices=["region", "lines", "windows", "probe", "stream", "zones", "groups",
-                                           "latency", "calib", "all"])
+                                           "latency", "updates", "calib", "all"])
     ap.add_argument("--zone-windows", type=int, default=32)
     ap.add_argument("--out", default=None, help="JSONL file to append to (and to resume from)")
     ap.add_argument("--reps", type=int, default=5)
@@ -376,12 +402,13 @@ def main(argv=None):
     ap.add_argument("--block", type=int, default=0)
     args = ap.parse_args(argv)
     r = Runner(args)
-    todo = (["region", "lines", "windows", "stream", "latency", "groups", "zones", "probe"] if args.experiment == "all"
+    todo = (["region", "lines", "windows", "stream", "latency", "updates", "groups", "zones", "probe"]
+            if args.experiment == "all"
             else [args.experiment])
     for name in todo:
         {"region": r.region_sweep, "lines": r.line_sweep, "windows": r.window_sweep, "probe": r.probe,
          "stream": r.stream, "zones": r.zones, "groups": r.groups, "latency": r.latency,
-         "calib": r.calib}[name]()
+         "updates": r.updates, "calib": r.calib}[name]()
     return 0
 
 

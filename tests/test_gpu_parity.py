@@ -136,6 +136,51 @@ def test_chase_full_region(region):
     assert (got.final_line, got.word_sum) == orc.chase(R, 128, wl.FILL_SEED, 0, 0, 0xFFFFFFFF, 20000)
 
 
+# ------------------------------------------------------------------ random line write / add
+@pytest.mark.parametrize("R,B,lanes,W,I", [
+    (4096, 128, 32, 4, 8), (12288, 128, 32, 5, 37), (1 << 20, 128, 32, 7, 100), (3 << 20, 256, 32, 77, 95),
+    (5 << 19, 512, 32, 31, 129), (1 << 20, 256, 64, 9, 70), (3 << 20, 512, 64, 33, 257), (128, 128, 32, 3, 50),
+    (1 << 24, 128, 32, 1024, 256),     # heavy reuse: every line hit about twice
+])
+@pytest.mark.parametrize("op", [rl.OP_WRITE, rl.OP_ADD])
+def test_rand_update_region_content(R, B, lanes, W, I, op):
+    """Whole region compared byte for byte with the oracle's sequential application of the updates."""
+    dev = torch.zeros(R + 512, dtype=torch.uint8, device="cuda")
+    rl.fill(dev, wl.FILL_SEED, region_bytes=R)
+    got = rl.rand_update(dev, B, W * I, I, 7, op, 0x1234567890ABC, lanes_per_line=lanes, region_bytes=R)
+    host = orc.fill_buffer(R, wl.FILL_SEED)
+    orc.apply_updates(host, B, W, I, 7, op, 0x1234567890ABC)
+    out = dev.cpu().numpy()
+    assert np.array_equal(out[:R], host)
+    assert not out[R:].any()                                   # nothing written past the region
+    assert got.checksum == orc.update_checksum(R, B, W, I, 7, 0x1234567890ABC)
+    assert got.waves_run == (W * lanes + 63) // 64
+
+
+def test_rand_update_large_region_sampled():
+    """4 GiB region, 2^22 updates: checksum, and the lines drawn by a few logical waves read back
+    and compared with old + hits * value (add) resp. value (write)."""
+    R, B, W, I = 4 * GiB, 128, 1024, 4096
+    dev = torch.empty(R, dtype=torch.uint8, device="cuda")
+    idx = orc.indices(R, B, W, I, 11)
+    lines, hits = np.unique(idx, return_counts=True)
+    count = dict(zip(lines.tolist(), hits.tolist()))
+    for op in (rl.OP_WRITE, rl.OP_ADD):
+        rl.fill(dev, wl.FILL_SEED)
+        got = rl.rand_update(dev, B, W * I, I, 11, op, 99)
+        assert got.checksum == orc.update_checksum(R, B, W, I, 11, 99)
+        for line in list(idx[0, :8]) + list(idx[W - 1, -8:]) + [int(lines[np.argmax(hits)])]:
+            line = int(line)
+            now = dev[line * B:(line + 1) * B].cpu().numpy().view(np.uint32).astype(np.uint64)
+            old = orc.fill_words(wl.FILL_SEED, line * 32, 32).astype(np.uint64)
+            v = np.array([orc.update_value(99, line * 32 + j) for j in range(32)], dtype=np.uint64)
+            want = v if op == rl.OP_WRITE else (old + count[line] * v) % (1 << 32)
+            assert np.array_equal(now, want), (op, line)
+        probe = int(np.setdiff1d(np.arange(1000), lines)[0])         # a line nobody hit keeps the fill
+        now = dev[probe * B:(probe + 1) * B].cpu().numpy().view(np.uint32)
+        assert np.array_equal(now, orc.fill_words(wl.FILL_SEED, probe * 32, 32))
+
+
 # ------------------------------------------------------------------ rand_read, small cases
 SMALL = [
     # region bytes, line, lanes, W, I

@@ -96,6 +96,16 @@ def test_fill_and_probe_validation():
         rl.probe_cus(FAKE, [], 8, 8, 7)
 
 
+def test_rand_update_validation():
+    with pytest.raises(rl.RandlineError) as e:
+        rl.rand_update(FAKE, 128, 8, 8, 7, 3, 1)
+    assert "op must be" in str(e.value)
+    with pytest.raises(rl.RandlineError):
+        rl.rand_update(FAKE, 100, 8, 8, 7, rl.OP_WRITE, 1)
+    with pytest.raises(rl.RandlineError):
+        rl.rand_update((0, 4096), 128, 8, 8, 7, rl.OP_ADD, 1)
+
+
 def test_chase_validation():
     for args, needle in ((((0, 4096), 128, 0, 0, 0, 1), "NULL"), ((FAKE, 100, 0, 0, 0, 1), "line_bytes"),
                          ((FAKE, 128, 1 << 13, 0, 0, 1), "start"), ((FAKE, 128, 0, 0, 0, 0), "hops"),

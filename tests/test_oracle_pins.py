@@ -274,3 +274,54 @@ def test_chase_closed_forms():
     assert orc.chase(R, B, 1, 5, 0, 0, 10) == (5, 10 * orc.fill_word(1, 5 * 32))   # standing still
     with pytest.raises(ValueError):
         orc.chase(R, B, 1, L, 0, 0, 1)
+
+
+# ---------------------------------------------------------------- random line write / add
+def test_update_bruteforce_on_bytes():
+    """Writes and adds applied with struct on a bytearray (wrong word index, value not truncated to
+    32 bits, add without wrap, write that depends on the old content)."""
+    import struct
+    for R, B, W, I in ((4096, 128, 4, 8), (96 * 256, 256, 5, 13), (15 * 512, 512, 3, 40)):
+        L = R // B
+        for op in (orc.OP_WRITE, orc.OP_ADD):
+            ref = bytearray(pybrute.region_bytes(R, 1))
+            total = 0
+            for w in range(W):
+                for h in pybrute.wave_draws(7, w, I):
+                    line = h % L
+                    for j in range(B // 4):
+                        i = line * (B // 4) + j
+                        v = (0xABCDEF0123 + i * 0x9E3779B1) & 0xFFFFFFFF
+                        total += v
+                        old = struct.unpack_from("<I", ref, 4 * i)[0]
+                        struct.pack_into("<I", ref, 4 * i, v if op == orc.OP_WRITE else (old + v) & 0xFFFFFFFF)
+            buf = orc.fill_buffer(R, 1)
+            orc.apply_updates(buf, B, W, I, 7, op, 0xABCDEF0123)
+            assert buf.tobytes() == bytes(ref)
+            assert orc.update_checksum(R, B, W, I, 7, 0xABCDEF0123) == total & M64
+
+
+def test_update_closed_forms():
+    B = 128
+    old = orc.fill_words(1, 0, 32).astype(np.uint64)
+    v = np.array([orc.update_value(5, j) for j in range(32)], dtype=np.uint64)
+    buf = orc.fill_buffer(B, 1)                      # one-line region: every update hits line 0
+    orc.apply_updates(buf, B, 3, 7, 9, orc.OP_ADD, 5)
+    assert np.array_equal(buf.view("<u4").astype(np.uint64), (old + 21 * v) % (1 << 32))
+    buf = orc.fill_buffer(B, 1)
+    orc.apply_updates(buf, B, 3, 7, 9, orc.OP_WRITE, 5)
+    assert np.array_equal(buf.view("<u4").astype(np.uint64), v)
+    assert orc.update_checksum(B, B, 3, 7, 9, 5) == 21 * int(v.sum())
+    # a write is idempotent, and lines that were not hit keep the fill
+    R = 1 << 16
+    a, b = orc.fill_buffer(R, 1), orc.fill_buffer(R, 1)
+    orc.apply_updates(a, B, 4, 9, 7, orc.OP_WRITE, 3)
+    orc.apply_updates(b, B, 4, 9, 7, orc.OP_WRITE, 3)
+    orc.apply_updates(b, B, 4, 9, 7, orc.OP_WRITE, 3)
+    assert np.array_equal(a, b)
+    hit = set(orc.indices(R, B, 4, 9, 7).reshape(-1).tolist())
+    words = a.view("<u4").reshape(-1, 32)
+    fill = orc.fill_words(1, 0, R // 4).reshape(-1, 32)
+    for line in range(R // B):
+        assert np.array_equal(words[line], fill[line]) == (line not in hit)
+    assert orc.update_value(0xFFFFFFFFFFFFFFFF, 1 << 36) == (0xFFFFFFFFFFFFFFFF + (1 << 36) * 0x9E3779B1) & 0xFFFFFFFF
