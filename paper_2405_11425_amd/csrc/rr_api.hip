@@ -436,6 +436,49 @@ Reducer make_reducer(u64 L) {
     return r;
 }
 
+// Lookup tables of one call: CU key -> group and dense id, group -> window, group -> its CUs, and each
+// CU's share of its group's units.  Built in the pinned staging copy and uploaded only if they differ
+// from what the device already holds.
+int prepare_tables(DeviceState &st, const Plan &pl, const rr_window_map_t *wm, u64 units, u64 L_win,
+                   hipStream_t stream) {
+    const u32 n_cus = (u32)st.cus.size();
+    Tables &tb = *st.tables_host;
+    memset(&tb, 0, sizeof tb);
+    for (u32 k = 0; k < kNumKeys; ++k) {
+        tb.group_of_key[k] = kExcluded;
+        tb.dense_of_key[k] = st.dense_of_key_host[k];
+    }
+    std::vector<u32> cus_in_group(pl.G, 0);
+    for (u32 c = 0; c < n_cus; ++c) {
+        const u16 g = wm ? wm->group_of_cu[c] : 0;
+        tb.group_of_key[key_of(st.cus[c])] = g;
+        if (g != kExcluded) cus_in_group[g]++;
+    }
+    for (u32 g = 0; g < pl.G; ++g) {
+        if (cus_in_group[g] == 0) return fail(RR_EPLACE, "group %u has no compute unit", g);
+        tb.window_base[g] = wm ? (u32)(wm->window_of_group[g] * L_win) : 0u;
+        tb.group_begin[g + 1] = tb.group_begin[g] + cus_in_group[g];
+    }
+    std::vector<u32> fill_pos(pl.G, 0);
+    for (u32 c = 0; c < n_cus; ++c) {  // ascending dense id within each group
+        const u16 g = wm ? wm->group_of_cu[c] : 0;
+        if (g == kExcluded) continue;
+        const u32 k = fill_pos[g]++, n = cus_in_group[g];
+        tb.group_cus[tb.group_begin[g] + k] = (u16)c;
+        tb.cu_pos[c] = (u16)k;
+        const u64 b0 = units * k / n, b1 = units * (k + 1) / n;  // even split of the group's units
+        tb.cu_unit_begin[c] = (u32)b0;
+        tb.cu_unit_count[c] = (u32)(b1 - b0);
+    }
+    if (!st.tables_valid || memcmp(st.tables_last, st.tables_host, sizeof(Tables)) != 0) {
+        st.tables_valid = false;  // trusted again once a later synchronisation has succeeded
+        st.flat_tables_ready = false;
+        HIP_TRY(hipMemcpyAsync(st.tables, st.tables_host, sizeof(Tables), hipMemcpyHostToDevice, stream));
+        memcpy(st.tables_last, st.tables_host, sizeof(Tables));
+    }
+    return RR_OK;
+}
+
 int run_plan(const Plan &pl, const void *region, uint32_t iters, const rr_window_map_t *wm,
              uint64_t read_seed, hipStream_t stream, const rr_launch_opts_t *opts, rr_result_t *out) {
     rr_result_t res;
@@ -453,49 +496,15 @@ int run_plan(const Plan &pl, const void *region, uint32_t iters, const rr_window
     if (wm && wm->n_cus != n_cus)
         return fail(RR_EINVAL, "window map describes %u compute units, the device has %u", wm->n_cus, n_cus);
 
-    // tables: CU key -> group and dense id, group -> window, and each CU's share of its group's units
     const u32 lpw = 64 / pl.lanes;
     const u64 L_win = pl.n_lines / pl.n_windows;
     const u64 quota = pl.W / pl.G;
     const u64 units = (quota + lpw - 1) / lpw;  // per group
+    // a flat launch without a map reads none of the per-call table fields: reuse what is there
     const bool flat_no_map = !wm && pl.mode == RR_MODE_FLAT;
-    Tables &tb = *st.tables_host;
-    if (!(flat_no_map && st.flat_tables_ready)) {  // a flat launch without a map reads none of the per-call fields
-    memset(&tb, 0, sizeof tb);
-    for (u32 k = 0; k < kNumKeys; ++k) {
-        tb.group_of_key[k] = kExcluded;
-        tb.dense_of_key[k] = st.dense_of_key_host[k];
-    }
-    std::vector<u32> cus_in_group(pl.G, 0);
-    for (u32 c = 0; c < n_cus; ++c) {
-        const u16 g = wm ? wm->group_of_cu[c] : 0;
-        tb.group_of_key[key_of(st.cus[c])] = g;
-        if (g != kExcluded) cus_in_group[g]++;
-    }
-    for (u32 g = 0; g < pl.G; ++g) {
-        if (cus_in_group[g] == 0) return fail(RR_EPLACE, "group %u has no compute unit", g);
-        tb.window_base[g] = wm ? (u32)(wm->window_of_group[g] * L_win) : 0u;
-        tb.group_begin[g + 1] = tb.group_begin[g] + cus_in_group[g];
-    }
-    {
-        std::vector<u32> fill_pos(pl.G, 0);
-        for (u32 c = 0; c < n_cus; ++c) {  // ascending dense id within each group
-            const u16 g = wm ? wm->group_of_cu[c] : 0;
-            if (g == kExcluded) continue;
-            const u32 k = fill_pos[g]++, n = cus_in_group[g];
-            tb.group_cus[tb.group_begin[g] + k] = (u16)c;
-            tb.cu_pos[c] = (u16)k;
-            const u64 b0 = units * k / n, b1 = units * (k + 1) / n;  // even split of the group's units
-            tb.cu_unit_begin[c] = (u32)b0;
-            tb.cu_unit_count[c] = (u32)(b1 - b0);
-        }
-    }
-    if (!st.tables_valid || memcmp(st.tables_last, st.tables_host, sizeof(Tables)) != 0) {
-        st.tables_valid = false;
-        st.flat_tables_ready = false;
-        HIP_TRY(hipMemcpyAsync(st.tables, st.tables_host, sizeof(Tables), hipMemcpyHostToDevice, stream));
-        memcpy(st.tables_last, st.tables_host, sizeof(Tables));  // trusted only once a later sync succeeded
-    }
+    if (!(flat_no_map && st.flat_tables_ready)) {
+        rc = prepare_tables(st, pl, wm, units, L_win, stream);
+        if (rc != RR_OK) return rc;
     }
     const bool want_placement = opts && opts->placement_out;
     if (want_placement && st.placement_cap < pl.W) {
@@ -530,6 +539,8 @@ int run_plan(const Plan &pl, const void *region, uint32_t iters, const rr_window
     p.scratch = st.scratch;
     p.tables = st.tables;
     p.placement = want_placement ? st.placement : nullptr;
+    const bool want_cu_waves = opts && opts->cu_waves_out;
+    p.locate = (want_placement || want_cu_waves) ? 1u : 0u;
     p.phase_ticks = (opts && pl.zone_lines) ? (u64 *)opts->phase_ticks : nullptr;
 
     const u32 waves_per_block = pl.block / 64;
@@ -549,7 +560,7 @@ int run_plan(const Plan &pl, const void *region, uint32_t iters, const rr_window
         return fail(RR_EINVAL, "too many tickets per group (%llu)", units * p.chunks_per_wave);
     // the finish kernel leaves the result cells cleared; counters are needed by ticketed launches only
     const u32 what = (st.cells_clean ? 0u : 1u) | (p.ticket_mode ? 2u : 0u) |
-                     ((p.ticket_mode || want_placement) ? 4u : 0u);
+                     ((p.ticket_mode || p.locate) ? 4u : 0u);
     if (what) {
         hipLaunchKernelGGL(reset_kernel, dim3(1), dim3(256), 0, stream, st.scratch, what);
         HIP_TRY(hipGetLastError());
@@ -585,7 +596,7 @@ int run_plan(const Plan &pl, const void *region, uint32_t iters, const rr_window
         HIP_TRY(hipMemcpyAsync(opts->placement_out, st.placement, pl.W * sizeof(u16), hipMemcpyDeviceToHost, stream));
         HIP_TRY(hipStreamSynchronize(stream));
     }
-    if (opts && opts->cu_waves_out) {
+    if (want_cu_waves) {
         HIP_TRY(hipMemcpyAsync(st.cu_waves_host, st.scratch->cu_waves, n_cus * sizeof(u32), hipMemcpyDeviceToHost, stream));
         HIP_TRY(hipStreamSynchronize(stream));
         memcpy(opts->cu_waves_out, st.cu_waves_host, n_cus * sizeof(u32));

@@ -81,6 +81,7 @@ struct ReadParams {
     u32 chunks_per_wave;      // ceil(iters / chunk_iters)
     u32 n_groups;             // G
     u32 ticket_mode;          // 0 flat, 1 ticketed
+    u32 locate;               // 1: look up the CU even in flat mode (placement log or per-CU counts wanted)
     u32 log2_line;            // 7, 8 or 9
     u32 n_zones;              // phased variant: number of zones ...
     u64 zone_lines;           // ... of this many lines each (the last one may be shorter)

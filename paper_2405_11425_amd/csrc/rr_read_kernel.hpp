@@ -167,7 +167,7 @@ __global__ void __launch_bounds__(256) rand_read_kernel(const ReadParams p) {
     const u32 launch_index = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
 
     u32 group = 0, dense = 0;
-    if (p.ticket_mode || p.placement) {
+    if (p.ticket_mode || p.locate) {
         u32 key = cu_key();
         group = tb->group_of_key[key];
         dense = tb->dense_of_key[key];
@@ -265,7 +265,7 @@ __global__ void __launch_bounds__(256) rand_read_kernel(const ReadParams p) {
         atomicMin(&c->t_min, t0);
         atomicMax(&c->t_max, t1);
         atomicAdd(&c->waves, 1u);
-        if (p.ticket_mode || p.placement) atomicAdd(&s->cu_waves[dense], 1u);
+        if (p.ticket_mode || p.locate) atomicAdd(&s->cu_waves[dense], 1u);
     }
 }
 

@@ -260,6 +260,16 @@ def test_line_shapes_with_equal_bytes_agree(region):
     assert a == b == oracle(R, 256, W, I)
 
 
+def test_per_cu_counts_in_flat_mode(region, cu_table):
+    R, W, I = 1 << 28, 1000, 64
+    res = rl.rand_read(region, 128, W * I, I, 7, region_bytes=R, want_cu_waves=True)
+    assert res.checksum == oracle(R, 128, W, I)
+    assert int(res.cu_waves[:len(cu_table)].sum()) == res.waves_run == 500
+    res = rl.rand_read(region, 128, W * I, I, 7, region_bytes=R, want_cu_waves=True, want_placement=True)
+    counts = np.bincount(res.placement, minlength=len(cu_table))
+    assert np.array_equal(counts, 2 * res.cu_waves[:len(cu_table)])       # two logical waves per wavefront
+
+
 def test_repeatable(region):
     R, W, I = 1 << 30, 2048, 512
     seen = {rl.rand_read(region, 128, W * I, I, 5, region_bytes=R).checksum for _ in range(5)}
