@@ -14,43 +14,48 @@ from . import build as _build
 _lib = None
 
 
+def bind(path: str):
+    """Load an oracle shared object and declare the signatures of its functions."""
+    L = C.CDLL(path)
+    u64, u32, i32 = C.c_uint64, C.c_uint32, C.c_int
+    p16 = C.POINTER(C.c_uint16)
+    L.rlo_mix64.restype = u64
+    L.rlo_mix64.argtypes = [u64]
+    L.rlo_sm.restype = u64
+    L.rlo_sm.argtypes = [u64, u64]
+    L.rlo_fill_word.restype = u32
+    L.rlo_fill_word.argtypes = [u64, u64]
+    L.rlo_index_hash.restype = u64
+    L.rlo_index_hash.argtypes = [u64, u64, u64]
+    L.rlo_indices.restype = i32
+    L.rlo_indices.argtypes = [u64, u32, u64, u64, u32, u32, u32, p16, u64, C.POINTER(u64)]
+    L.rlo_checksum.restype = i32
+    L.rlo_checksum.argtypes = [u64, u32, u64, u64, u32, u32, u32, p16, u64, u64, i32,
+                               C.POINTER(u64), C.POINTER(i32)]
+    L.rlo_fill_buffer.restype = i32
+    L.rlo_fill_buffer.argtypes = [C.c_void_p, u64, u64]
+    L.rlo_checksum_materialised.restype = i32
+    L.rlo_checksum_materialised.argtypes = [C.c_void_p, u64, u32, u64, u64, u32, u32, u32, p16,
+                                            u64, i32, C.POINTER(u64), C.POINTER(i32)]
+    L.rlo_fill_words.restype = i32
+    L.rlo_fill_words.argtypes = [u64, u64, u64, C.POINTER(u32)]
+    L.rlo_sum_words.restype = i32
+    L.rlo_sum_words.argtypes = [u64, u64, u64, i32, C.POINTER(u64)]
+    L.rlo_chase.restype = i32
+    L.rlo_chase.argtypes = [u64, u32, u64, u64, u64, u32, u64, C.POINTER(u64), C.POINTER(u64)]
+    L.rlo_update_value.restype = u32
+    L.rlo_update_value.argtypes = [u64, u64]
+    L.rlo_update_checksum.restype = i32
+    L.rlo_update_checksum.argtypes = [u64, u32, u64, u32, u64, u64, C.POINTER(u64)]
+    L.rlo_apply_updates.restype = i32
+    L.rlo_apply_updates.argtypes = [C.c_void_p, u64, u32, u64, u32, u64, u32, u64]
+    return L
+
+
 def lib():
     global _lib
     if _lib is None:
-        L = C.CDLL(_build.build())
-        u64, u32, i32 = C.c_uint64, C.c_uint32, C.c_int
-        p16 = C.POINTER(C.c_uint16)
-        L.rlo_mix64.restype = u64
-        L.rlo_mix64.argtypes = [u64]
-        L.rlo_sm.restype = u64
-        L.rlo_sm.argtypes = [u64, u64]
-        L.rlo_fill_word.restype = u32
-        L.rlo_fill_word.argtypes = [u64, u64]
-        L.rlo_index_hash.restype = u64
-        L.rlo_index_hash.argtypes = [u64, u64, u64]
-        L.rlo_indices.restype = i32
-        L.rlo_indices.argtypes = [u64, u32, u64, u64, u32, u32, u32, p16, u64, C.POINTER(u64)]
-        L.rlo_checksum.restype = i32
-        L.rlo_checksum.argtypes = [u64, u32, u64, u64, u32, u32, u32, p16, u64, u64, i32,
-                                   C.POINTER(u64), C.POINTER(i32)]
-        L.rlo_fill_buffer.restype = i32
-        L.rlo_fill_buffer.argtypes = [C.c_void_p, u64, u64]
-        L.rlo_checksum_materialised.restype = i32
-        L.rlo_checksum_materialised.argtypes = [C.c_void_p, u64, u32, u64, u64, u32, u32, u32, p16,
-                                                u64, i32, C.POINTER(u64), C.POINTER(i32)]
-        L.rlo_fill_words.restype = i32
-        L.rlo_fill_words.argtypes = [u64, u64, u64, C.POINTER(u32)]
-        L.rlo_sum_words.restype = i32
-        L.rlo_sum_words.argtypes = [u64, u64, u64, i32, C.POINTER(u64)]
-        L.rlo_chase.restype = i32
-        L.rlo_chase.argtypes = [u64, u32, u64, u64, u64, u32, u64, C.POINTER(u64), C.POINTER(u64)]
-        L.rlo_update_value.restype = u32
-        L.rlo_update_value.argtypes = [u64, u64]
-        L.rlo_update_checksum.restype = i32
-        L.rlo_update_checksum.argtypes = [u64, u32, u64, u32, u64, u64, C.POINTER(u64)]
-        L.rlo_apply_updates.restype = i32
-        L.rlo_apply_updates.argtypes = [C.c_void_p, u64, u32, u64, u32, u64, u32, u64]
-        _lib = L
+        _lib = bind(_build.build())
     return _lib
 
 
