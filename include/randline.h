@@ -116,11 +116,17 @@ typedef struct {
     uint32_t reserved;       /* must be 0                                                          */
     uint64_t first_wave;     /* id of the first logical wave (default 0); multiple of n_groups     */
     uint64_t zone_bytes;     /* 0 = off.  Otherwise the region is cut into zones of this many bytes
-                                (a multiple of line_bytes, at most 16 zones) and every wave reads its
-                                lines zone by zone: all lines in zone 0 first, then zone 1, ...  Same
+                                (a multiple of line_bytes, at most 16 zones, made of at most 64 windows
+                                of a power-of-two number of lines) and the lines are read zone by
+                                zone: all lines in zone 0 first, then zone 1, ...  Same
                                 lines, same checksum, different order (see "Zone-phased reads").
-                                Flat launches without a window map only.                           */
-    uint64_t *phase_ticks;   /* DEVICE [hardware waves x zones] or NULL (zone-phased reads only): the
+                                Not with a window map.  Default mode: ticketed, zone-major order.  */
+    const uint8_t *zone_of_window; /* host [n_zone_windows] or NULL: instead of zone_bytes, a zone id (< 16) for   */
+    uint32_t n_zone_windows;       /* each of n_zone_windows (<= 64) equal windows of the region, each a power of
+                                      two lines long -- for zones that are not contiguous (the "zones" experiment
+                                      of the sweep driver produces such a map)                               */
+    uint32_t reserved2;            /* must be 0                                                              */
+    uint64_t *phase_ticks;   /* DEVICE [hardware waves x zones] or NULL (flat zone-phased reads only): the
                                 constant-rate clock (100 MHz) at which each wave finished each zone,
                                 for checking how well the phases line up                           */
     uint16_t *placement_out; /* host [W] or NULL: dense CU id that executed each logical wave      */
@@ -133,12 +139,15 @@ typedef struct {
  * it with the "zones" experiment of the sweep driver); restricting each compute
  * group to a window (paper Sec. 2.4) does not change that, but letting all
  * waves work on the same zone at the same time does.  With zone_bytes set, the
- * kernel bins each wave's line indices by zone in LDS and reads them zone by
- * zone.  This is the paper's idea -- keep what is accessed together inside one
- * locality domain -- transposed from space (a window per group) to time (a
- * window per phase).  Waves are not synchronised, and since the hardware lets
- * the oldest workgroups of a CU run well ahead of the youngest the phases
- * overlap only partly: the measured gain at 256 GiB is about 1.5 %.
+ * work is cut into items (zone, pair of logical waves, chunk of iterations); an
+ * item bins its chunk's line indices in LDS and reads only those inside its
+ * zone.  Ticketed launches hand the items out zone-major, so the whole device
+ * works on one zone, then on the next, however unevenly the individual waves
+ * advance; a flat launch lets every wave go through the zones on its own, and
+ * because the hardware serves the oldest workgroups of a CU first the phases
+ * then overlap widely.  This is the paper's idea -- keep what is accessed
+ * together inside one locality domain -- transposed from space (a window per
+ * group) to time (a window per phase).  Zones must be contiguous in the region.
  */
 
 /*

@@ -51,7 +51,8 @@ class _Opts(C.Structure):
     _fields_ = [("block_threads", C.c_uint32), ("grid_blocks", C.c_uint32), ("unroll", C.c_uint32),
                 ("mode", C.c_uint32), ("bcast", C.c_uint32), ("nontemporal", C.c_uint32),
                 ("chunk_iters", C.c_uint32), ("reserved", C.c_uint32), ("first_wave", C.c_uint64),
-                ("zone_bytes", C.c_uint64), ("phase_ticks", C.c_void_p), ("placement_out", C.POINTER(C.c_uint16)),
+                ("zone_bytes", C.c_uint64), ("zone_of_window", C.POINTER(C.c_uint8)), ("n_zone_windows", C.c_uint32),
+                ("reserved2", C.c_uint32), ("phase_ticks", C.c_void_p), ("placement_out", C.POINTER(C.c_uint16)),
                 ("cu_waves_out", C.POINTER(C.c_uint32))]
 
 
@@ -179,13 +180,18 @@ class ReadResult:
 
 
 def _opts(W: int, n_cus_hint: int, block_threads=0, grid_blocks=0, unroll=0, mode=0, bcast=0,
-          nontemporal=0, chunk_iters=0, first_wave=0, zone_bytes=0, phase_ticks=None, want_placement=False,
-          want_cu_waves=False):
+          nontemporal=0, chunk_iters=0, first_wave=0, zone_bytes=0, zone_of_window=None, phase_ticks=None,
+          want_placement=False, want_cu_waves=False):
     ticks_ptr = None
     if phase_ticks is not None:   # a torch int64 device tensor of hardware waves x zones elements
         ticks_ptr = int(phase_ticks.data_ptr())
+    zmap_ptr, zmap_len = None, 0
+    if zone_of_window is not None:
+        zmap = np.ascontiguousarray(zone_of_window, dtype=np.uint8)
+        zmap_ptr, zmap_len = zmap.ctypes.data_as(C.POINTER(C.c_uint8)), int(zmap.size)
     o = _Opts(block_threads, grid_blocks, unroll, mode, bcast, nontemporal, chunk_iters, 0, first_wave, zone_bytes,
-              ticks_ptr, None, None)
+              zmap_ptr, zmap_len, 0, ticks_ptr, None, None)
+    o._keepalive = zone_of_window if zone_of_window is None else zmap
     placement = cu_waves = None
     if want_placement:
         placement = np.full(max(W, 1), 0xFFFF, dtype=np.uint16)

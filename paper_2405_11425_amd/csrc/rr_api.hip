@@ -330,8 +330,9 @@ struct Plan {
     u32 log2_line = 0, lanes = 0, wdw = 0, G = 1, n_windows = 1;
     u32 block = 256, unroll = 0, bcast = RR_BCAST_DPP, nt = 1, mode = RR_MODE_AUTO, grid_blocks = 0;
     u32 chunk_iters = 0;
-    u64 zone_lines = 0;  // > 0: zone-phased kernel
-    u32 n_zones = 0;
+    u32 n_zones = 0;     // > 0: zone-phased kernel
+    u32 zone_shift = 0;
+    u64 zone_mask[16] = {};
     bool pinned = false;
     const Family *family = nullptr;
     kernel_handle kernel = nullptr;
@@ -400,23 +401,48 @@ int make_plan(const void *region, uint64_t region_bytes, uint32_t line_bytes, ui
         pl.chunk_iters = opts->chunk_iters;
         if (opts->first_wave % pl.G != 0) return fail(RR_EINVAL, "first_wave must be a multiple of n_groups");
         pl.first_wave = opts->first_wave;
-        if (opts->phase_ticks && !opts->zone_bytes) return fail(RR_EINVAL, "phase_ticks needs zone_bytes");
-        if (opts->zone_bytes) {
-            if (opts->zone_bytes % line_bytes != 0) return fail(RR_EINVAL, "zone_bytes must be a multiple of line_bytes");
+        const bool zoned = opts->zone_bytes || opts->zone_of_window;
+        if (opts->reserved2 != 0) return fail(RR_EINVAL, "reserved2 must be 0");
+        if (opts->phase_ticks && (!zoned || opts->mode != RR_MODE_FLAT))
+            return fail(RR_EINVAL, "phase_ticks needs zones and a flat launch");
+        if (zoned) {
+            if (opts->zone_bytes && opts->zone_of_window)
+                return fail(RR_EINVAL, "give either zone_bytes or zone_of_window, not both");
             if (wm) return fail(RR_EINVAL, "zone-phased reads cannot be combined with a window map");
-            if (opts->mode == RR_MODE_TICKET) return fail(RR_EINVAL, "zone-phased reads need a flat launch");
             if (opts->chunk_iters) return fail(RR_EINVAL, "zone-phased reads do not take chunk_iters");
             if (opts->placement_out || opts->cu_waves_out)
                 return fail(RR_EINVAL, "zone-phased reads do not record placement");
-            pl.zone_lines = opts->zone_bytes / line_bytes;
-            const u64 nz = (pl.n_lines + pl.zone_lines - 1) / pl.zone_lines;
-            if (nz > 16) return fail(RR_EINVAL, "zone_bytes gives %llu zones; at most 16 are supported", nz);
-            pl.n_zones = (u32)nz;
+            u64 window_lines;  // a power of two; the region has at most 64 such windows
+            if (opts->zone_bytes) {
+                if (opts->zone_bytes % line_bytes != 0) return fail(RR_EINVAL, "zone_bytes must be a multiple of line_bytes");
+                const u64 zone_lines = opts->zone_bytes / line_bytes;
+                const u64 nz = (pl.n_lines + zone_lines - 1) / zone_lines;
+                if (nz > 16) return fail(RR_EINVAL, "zone_bytes gives %llu zones; at most 16 are supported", nz);
+                window_lines = zone_lines & (~zone_lines + 1);  // largest power of two dividing the zone
+                const u64 n_win = (pl.n_lines + window_lines - 1) / window_lines;
+                if (n_win > 64) return fail(RR_EINVAL, "zone_bytes would need %llu windows; at most 64 are supported", n_win);
+                pl.n_zones = (u32)nz;
+                for (u64 v = 0; v < n_win; ++v) pl.zone_mask[v * window_lines / zone_lines] |= 1ull << v;
+            } else {
+                const u32 n_win = opts->n_zone_windows;
+                if (n_win == 0 || n_win > 64) return fail(RR_EINVAL, "n_zone_windows must be in [1, 64]");
+                if (pl.n_lines % n_win != 0) return fail(RR_EINVAL, "n_zone_windows must divide the number of lines");
+                window_lines = pl.n_lines / n_win;
+                if (window_lines & (window_lines - 1))
+                    return fail(RR_EINVAL, "a zone window must hold a power-of-two number of lines");
+                for (u32 v = 0; v < n_win; ++v) {
+                    const u32 z = opts->zone_of_window[v];
+                    if (z >= 16) return fail(RR_EINVAL, "zone_of_window[%u] = %u is not below 16", v, z);
+                    pl.zone_mask[z] |= 1ull << v;
+                    if (z + 1 > pl.n_zones) pl.n_zones = z + 1;
+                }
+            }
+            while ((1ull << pl.zone_shift) < window_lines) pl.zone_shift++;
         }
     }
     pl.kernel = pl.family->find(pl.unroll, pl.bcast, pl.nt);
     if (!pl.kernel) return fail(RR_EINVAL, "unroll %u is not built for this line shape", pl.unroll);
-    if (pl.zone_lines) {
+    if (pl.n_zones) {
         pl.kernel = find_phased_kernel(pl.lanes, pl.wdw, pl.nt);
         if (!pl.kernel) return fail(RR_EINVAL, "no zone-phased kernel for this line shape");
         pl.block = 256;  // its LDS lists are laid out for four waves per workgroup
@@ -432,7 +458,8 @@ int make_plan(const void *region, uint64_t region_bytes, uint32_t line_bytes, ui
     }
     if (pl.mode == RR_MODE_FLAT && needs_tickets)
         return fail(RR_EINVAL, "flat mode cannot honour a window map with several groups or excluded CUs");
-    if (pl.mode == RR_MODE_AUTO) pl.mode = needs_tickets ? RR_MODE_TICKET : RR_MODE_FLAT;
+    // zone-phased reads line their phases up only when the work is handed out zone-major by tickets
+    if (pl.mode == RR_MODE_AUTO) pl.mode = (needs_tickets || pl.n_zones) ? RR_MODE_TICKET : RR_MODE_FLAT;
     return RR_OK;
 }
 
@@ -534,13 +561,15 @@ int run_plan(const Plan &pl, const void *region, uint32_t iters, const rr_window
     p.iters = iters;
     // flat launches default to one hardware wave per whole logical wave (pair); ticketed ones to
     // chunks of 512 iterations so that resident waves finish together
-    u32 chunk = pl.chunk_iters ? pl.chunk_iters : (pl.mode == RR_MODE_TICKET ? 512u : iters);
+    const bool phased = pl.n_zones > 0;  // its chunks are what one pass through the LDS lists holds
+    u32 chunk = phased ? kPhaseChunk : pl.chunk_iters ? pl.chunk_iters : (pl.mode == RR_MODE_TICKET ? 512u : iters);
     if (chunk > iters) chunk = iters;
     p.chunk_iters = chunk;
     p.chunks_per_wave = (iters + chunk - 1) / chunk;
     p.n_groups = pl.G;
     p.n_zones = pl.n_zones;
-    p.zone_lines = pl.zone_lines;
+    p.zone_shift = pl.zone_shift;
+    memcpy(p.zone_mask, pl.zone_mask, sizeof p.zone_mask);
     p.ticket_mode = pl.mode == RR_MODE_TICKET ? 1u : 0u;
     p.log2_line = pl.log2_line;
     p.red = make_reducer(L_win);
@@ -549,7 +578,7 @@ int run_plan(const Plan &pl, const void *region, uint32_t iters, const rr_window
     p.placement = want_placement ? st.placement : nullptr;
     const bool want_cu_waves = opts && opts->cu_waves_out;
     p.locate = (want_placement || want_cu_waves) ? 1u : 0u;
-    p.phase_ticks = (opts && pl.zone_lines) ? (u64 *)opts->phase_ticks : nullptr;
+    p.phase_ticks = (opts && pl.n_zones) ? (u64 *)opts->phase_ticks : nullptr;
 
     const u32 waves_per_block = pl.block / 64;
     // a CU holds at most 32 waves (8 per SIMD); workgroups beyond what really fits queue up,
@@ -559,13 +588,14 @@ int run_plan(const Plan &pl, const void *region, uint32_t iters, const rr_window
     if (p.ticket_mode) {
         grid = pl.grid_blocks ? pl.grid_blocks : (u64)blocks_per_cu * n_cus * (pl.pinned ? 64u : 1u);
     } else {
-        const u64 hw_waves = (pl.W + lpw - 1) / lpw * p.chunks_per_wave;
+        const u64 hw_waves = (pl.W + lpw - 1) / lpw * (phased ? 1u : p.chunks_per_wave);
         grid = (hw_waves + waves_per_block - 1) / waves_per_block;
     }
     if (grid == 0 || grid > 0x7FFFFFFFull) return fail(RR_EINVAL, "launch of %llu workgroups is out of range", grid);
 
-    if (units * p.chunks_per_wave >= (1ull << 31))
-        return fail(RR_EINVAL, "too many tickets per group (%llu)", units * p.chunks_per_wave);
+    const u64 tickets_per_unit = (u64)p.chunks_per_wave * (phased ? pl.n_zones : 1u);
+    if (units * tickets_per_unit >= (1ull << 31))
+        return fail(RR_EINVAL, "too many tickets per group (%llu)", units * tickets_per_unit);
     // the finish kernel leaves the result cells cleared; counters are needed by ticketed launches only
     const u32 what = (st.cells_clean ? 0u : 1u) | (p.ticket_mode ? 2u : 0u) |
                      ((p.ticket_mode || p.locate) ? 4u : 0u);
@@ -581,7 +611,7 @@ int run_plan(const Plan &pl, const void *region, uint32_t iters, const rr_window
         HIP_TRY(hipLaunchKernel(pl.kernel, dim3((u32)grid), dim3(pl.block), args, 0, stream));
         HIP_TRY(hipEventRecord(st.ev1, stream));
         hipLaunchKernelGGL(finish_kernel, dim3(1), dim3(kNumCells), 0, stream, st.scratch, st.head_dev, st.tables,
-                           n_cus, p.chunks_per_wave, p.ticket_mode);
+                           n_cus, (u32)tickets_per_unit, p.ticket_mode);
         HIP_TRY(hipGetLastError());
         HIP_TRY(hipStreamSynchronize(stream));
         st.cells_clean = true;

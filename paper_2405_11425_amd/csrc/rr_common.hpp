@@ -83,8 +83,9 @@ struct ReadParams {
     u32 ticket_mode;          // 0 flat, 1 ticketed
     u32 locate;               // 1: look up the CU even in flat mode (placement log or per-CU counts wanted)
     u32 log2_line;            // 7, 8 or 9
-    u32 n_zones;              // phased variant: number of zones ...
-    u64 zone_lines;           // ... of this many lines each (the last one may be shorter)
+    u32 n_zones;              // phased variant: number of zones; the region is cut into at most 64 windows of
+    u32 zone_shift;           // 2^zone_shift lines, and bit v of zone_mask[z] says that window v belongs to zone z
+    u64 zone_mask[16];
     Reducer red;              // L = lines per window
     Scratch *scratch;
     const Tables *tables;

@@ -261,7 +261,10 @@ class Runner:
         base = os.path.splitext(self.args.out)[0] if self.args.out else None
         if base:
             np.savetxt(base + ".zone_matrix.txt", M, fmt="%.1f")
-        self.emit(key, {"experiment": "zones", "region_gib": R // wl.GiB, "n_windows": n_w,
+        # the same uniform read over the whole region: plain, and zone by zone with the map just found
+        plain = self.timed_read(cfg)["gbps"]
+        phased = self.timed_read(cfg, zone_of_window=group.astype(np.uint8))["gbps"] if len(zones) <= 16 else None
+        self.emit(key, {"experiment": "zones", "gbps_uniform_plain": plain, "gbps_uniform_zone_by_zone": phased, "region_gib": R // wl.GiB, "n_windows": n_w,
                         "window_gib": R / n_w / wl.GiB, "n_zones": len(zones),
                         "zone_ranges_gib": [_runs(z, R / n_w / wl.GiB) for z in zones],
                         "zone_sizes_gib": [len(z) * R / n_w / wl.GiB for z in zones],

@@ -292,16 +292,33 @@ def test_zone_phased_reads_same_checksum(region, R, B, lanes, W, I, zone):
     want = oracle(R, B, W, I)
     for nt in (rl.NT_ON, rl.NT_OFF):
         got = rl.rand_read(region, B, W * I, I, wl.READ_SEED, lanes_per_line=lanes, region_bytes=R,
-                           zone_bytes=zone, nontemporal=nt)
+                           zone_bytes=zone, nontemporal=nt, mode=rl.MODE_FLAT)
         assert got.checksum == want
         assert got.waves_run == (W * lanes + 63) // 64
+        for grid in (0, 5):                      # zone-major tickets; a tiny grid finishes by stealing
+            got = rl.rand_read(region, B, W * I, I, wl.READ_SEED, lanes_per_line=lanes, region_bytes=R,
+                               zone_bytes=zone, nontemporal=nt, mode=rl.MODE_TICKET, grid_blocks=grid)
+            assert got.checksum == want, grid
+
+
+def test_zone_map_with_scattered_zones(region):
+    """Zones given window by window, not contiguous (the way physical zones show up in an allocation)."""
+    R, W, I = 1 << 30, 200, 777
+    want = oracle(R, 128, W, I)
+    zmap = [0] * 8 + [1] * 8 + [2] * 4 + [0] * 4 + [2] * 6 + [1] * 2
+    for mode in (rl.MODE_FLAT, rl.MODE_TICKET):
+        got = rl.rand_read(region, 128, W * I, I, wl.READ_SEED, region_bytes=R, zone_of_window=zmap, mode=mode)
+        assert got.checksum == want, mode
+    got = rl.rand_read(region, 256, W * I, I, wl.READ_SEED, lanes_per_line=64, region_bytes=R, zone_of_window=[3, 0])
+    assert got.checksum == oracle(R, 256, W, I)
 
 
 def test_zone_phase_ticks(region):
     """Per-wave phase end times: one non-decreasing row of clock values per hardware wave."""
     W, I, Z = 64, 600, 3
     ticks = torch.zeros(32 * Z, dtype=torch.int64, device="cuda")
-    got = rl.rand_read(region, 128, W * I, I, 7, region_bytes=3 << 24, zone_bytes=1 << 24, phase_ticks=ticks)
+    got = rl.rand_read(region, 128, W * I, I, 7, region_bytes=3 << 24, zone_bytes=1 << 24, phase_ticks=ticks,
+                       mode=rl.MODE_FLAT)
     assert got.checksum == oracle(3 << 24, 128, W, I)
     t = ticks.cpu().numpy().reshape(32, Z)
     assert (t > 0).all() and (np.diff(t, axis=1) >= 0).all()

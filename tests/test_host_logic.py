@@ -55,8 +55,12 @@ FAKE = (1 << 21, 1 << 20)  # an aligned, non-null "device pointer" that is never
     ((FAKE, 128, 8, 8, 7), {"nontemporal": 3}, "nontemporal"),
     ((FAKE, 128, 8, 8, 7), {"zone_bytes": 100}, "zone_bytes"),
     ((FAKE, 128, 8, 8, 7), {"zone_bytes": 128}, "at most 16"),
-    ((FAKE, 128, 8, 8, 7), {"zone_bytes": 1 << 18, "mode": 2}, "flat launch"),
     ((FAKE, 128, 8, 8, 7), {"zone_bytes": 1 << 18, "chunk_iters": 64}, "chunk_iters"),
+    ((FAKE, 128, 8, 8, 7), {"zone_bytes": 1 << 18, "zone_of_window": [0, 1]}, "not both"),
+    ((FAKE, 128, 8, 8, 7), {"zone_of_window": [0, 1, 2]}, "divide"),
+    ((FAKE, 128, 8, 8, 7), {"zone_of_window": [0, 16]}, "below 16"),
+    ((FAKE, 128, 8, 8, 7), {"zone_of_window": [0] * 65}, "n_zone_windows"),
+    (((1 << 21, 3 << 20), 128, 8, 8, 7), {"zone_of_window": [0, 1]}, "power-of-two"),
 ])
 def test_rand_read_rejects_bad_arguments_without_a_device(args, kw, needle):
     with pytest.raises(rl.RandlineError) as e:
