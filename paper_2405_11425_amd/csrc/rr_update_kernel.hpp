@@ -30,7 +30,6 @@ struct UpdateParams {
 
 template <int LANES, int WDW, int OP>
 __global__ void __launch_bounds__(256) rand_update_kernel(const UpdateParams p) {
-    typedef typename Vec<WDW>::type V;
     constexpr u32 LPW = 64 / LANES;
     constexpr int ITB = 16;  // iterations generated per batch (DPP row broadcast)
     const u32 lane = threadIdx.x & 63;

@@ -2,7 +2,7 @@
 measured point to a JSONL file (points already present are skipped, so a run can be resumed).
 
     python -m paper_2405_11425_amd.sweep region  [--out results.jsonl] [--reps 5]
-    python -m paper_2405_11425_amd.sweep lines | windows | probe | stream | zones | groups | latency | updates | calib | all
+    python -m paper_2405_11425_amd.sweep lines | windows | probe | stream | zones | groups | latency | pages | updates | calib | all
 
   region   throughput vs region size, uniform random 128-byte lines        (paper Sec. 2.1, Fig. 1)
   lines    32 x {4,8,16} B and 64 x 4 B lines at 128 GiB and the largest region (Sec. 2.1, text)
@@ -16,6 +16,8 @@ measured point to a JSONL file (points already present are skipped, so a run can
   updates  random 128-byte line writes and atomic adds vs region size      (the application of Sec. 1.3)
   latency  dependent-load walk of one wavefront: nanoseconds per hop vs footprint, 1 MiB .. the largest
            power-of-two region (the latency/footprint probe of the TLB literature the paper cites)
+  pages    the same walk over N lines that lie one per stride (128 B .. 1 GiB apart): the lines stay cached, so
+           what grows with the stride is the cost of translating N different pages (reach of the TLBs)
   calib    one copy, one fill, one sequential read of known size (for profiler counter calibration)
 
 Throughput is n_reads * line_bytes / kernel time (HIP events), decimal GB/s, and as a
@@ -377,6 +379,35 @@ class Runner:
                                 "word_sum": runs[0].word_sum, **self.meta})
             mib *= 4 if mib < 1024 else 2
 
+    def pages(self):
+        """Nanoseconds per dependent load over a closed cycle of N lines, one line per stride.  The stride is the
+        nominal distance plus one line so that the N lines spread over the cache sets; the region is exactly
+        N strides long, so the walk (stride taken mod the region, data term masked off) returns to its start
+        after N hops and a warm-up lap leaves every line in whatever cache holds N lines.  Rows with the same
+        N differ only in how many pages the N lines lie on."""
+        rl, wl = self.rl, self.wl
+        max_bytes = self.max_gib * wl.GiB
+        for dist in (0, 4 << 10, 64 << 10, 2 << 20, 32 << 20, 1 << 30):
+            stride = dist + 128
+            counts = [16 << i for i in range(14)]
+            if dist >= (32 << 20):
+                counts = sorted(counts + [24, 30, 31, 33, 34, 36, 40, 48, 96])  # resolve the first-level reach
+            for n in counts:
+                if n * stride > max_bytes:
+                    break
+                key = f"pages/{dist}/{n}"
+                if key in self.seen:
+                    continue
+                R = n * stride
+                hops = max(2 * n, 16384)
+                rl.chase(self.region, 128, 0, stride // 128, 0, n, region_bytes=R)
+                runs = [rl.chase(self.region, 128, 0, stride // 128, 0, hops, region_bytes=R) for _ in range(3)]
+                ns = [r.ns_per_hop for r in runs]
+                self.emit(key, {"experiment": "pages", "distance_bytes": dist, "n_lines": n,
+                                "span_mib": round(R / wl.MiB, 3), "hops": hops,
+                                "ns_per_hop": round(statistics.median(ns), 1), "ns_per_hop_min": round(min(ns), 1),
+                                "final_line": runs[0].final_line, **self.meta})
+
     def calib(self):
         """Three kernels of exactly known traffic, 8 GiB each, for scaling FETCH_SIZE / WRITE_SIZE."""
         rl, wl = self.rl, self.wl
@@ -391,7 +422,7 @@ class Runner:
 def main(argv=None):
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
     ap.add_argument("experiment", choices=["region", "lines", "windows", "probe", "stream", "zones", "groups",
-                                           "latency", "updates", "calib", "all"])
+                                           "latency", "pages", "updates", "calib", "all"])
     ap.add_argument("--zone-windows", type=int, default=32)
     ap.add_argument("--out", default=None, help="JSONL file to append to (and to resume from)")
     ap.add_argument("--reps", type=int, default=5)
@@ -405,12 +436,12 @@ def main(argv=None):
     ap.add_argument("--block", type=int, default=0)
     args = ap.parse_args(argv)
     r = Runner(args)
-    todo = (["region", "lines", "windows", "stream", "latency", "updates", "groups", "zones", "probe"]
+    todo = (["region", "lines", "windows", "stream", "latency", "pages", "updates", "groups", "zones", "probe"]
             if args.experiment == "all"
             else [args.experiment])
     for name in todo:
         {"region": r.region_sweep, "lines": r.line_sweep, "windows": r.window_sweep, "probe": r.probe,
-         "stream": r.stream, "zones": r.zones, "groups": r.groups, "latency": r.latency,
+         "stream": r.stream, "zones": r.zones, "groups": r.groups, "latency": r.latency, "pages": r.pages,
          "updates": r.updates, "calib": r.calib}[name]()
     return 0
 

@@ -136,6 +136,20 @@ def test_chase_full_region(region):
     assert (got.final_line, got.word_sum) == orc.chase(R, 128, wl.FILL_SEED, 0, 0, 0xFFFFFFFF, 20000)
 
 
+@pytest.mark.parametrize("dist,n", [(4 << 10, 16), (2 << 20, 33), (32 << 20, 128), (1 << 30, 64)])
+def test_chase_closed_cycle_over_pages(region, dist, n):
+    """The walk of the page-reach experiment: n lines, one per (dist + 128) bytes, region of exactly n strides,
+    data term masked off.  It returns to its start after every n hops, and visits what the oracle visits."""
+    stride = dist + 128
+    R = n * stride
+    if R > region.numel():
+        pytest.skip("region too small")
+    for hops in (n, 3 * n + 5):
+        got = rl.chase(region, 128, 0, stride // 128, 0, hops, region_bytes=R)
+        assert (got.final_line, got.word_sum) == orc.chase(R, 128, wl.FILL_SEED, 0, stride // 128, 0, hops)
+        assert got.final_line == (hops % n) * (stride // 128)
+
+
 # ------------------------------------------------------------------ random line write / add
 @pytest.mark.parametrize("R,B,lanes,W,I", [
     (4096, 128, 32, 4, 8), (12288, 128, 32, 5, 37), (1 << 20, 128, 32, 7, 100), (3 << 20, 256, 32, 77, 95),
