@@ -263,6 +263,30 @@ int rr_chase(const void *region, uint64_t region_bytes, uint32_t line_bytes, uin
 int rr_copy(void *dst, const void *src, uint64_t bytes, void *hip_stream, double *kernel_ms);
 
 /*
+ * A device-memory region mapped in pieces.  The paper's effect hinges on how
+ * much memory one translation entry covers (2 MiB pages on the A100, Sec. 1.2,
+ * Sec. 2.1); an ordinary allocation on this GPU is mapped with entries as
+ * large as its physical layout allows.  rr_region_create reserves `bytes` of
+ * virtual address space and backs it with separate physical allocations of
+ * piece_bytes each, so that no entry can cover more than one piece; the
+ * region is then used like any other (rr_fill, rr_rand_read, ...).
+ *   bytes        positive multiple of piece_bytes; at most 30000 pieces (the
+ *                driver runs out of handles a little above 32 000)
+ *   piece_bytes  multiple of 4096 and of the device's minimum allocation
+ *                granularity (rr_region_granularity; RR_EINVAL otherwise)
+ *   *region_out  (host) receives the device pointer, aligned to the largest
+ *                power of two dividing piece_bytes (at most 1 GiB)
+ * The library owns the region until rr_region_destroy (or rr_shutdown), which
+ * waits for the device first.  On failure (RR_EHIP, e.g. out of memory) nothing
+ * stays allocated and *region_out is untouched.  Argument checks come before
+ * any HIP call.  rr_region_destroy returns RR_EINVAL for a pointer that
+ * rr_region_create did not return.
+ */
+int rr_region_granularity(uint64_t *minimum, uint64_t *recommended); /* host outputs, either may be NULL */
+int rr_region_create(uint64_t bytes, uint64_t piece_bytes, void **region_out);
+int rr_region_destroy(void *region);
+
+/*
  * Groups of CUs from the pair heatmap (paper Sec. 2.2, Fig. 2 -> Fig. 3; the
  * paper gives no algorithm).  T is a host n x n row-major symmetric matrix of
  * pair throughputs (diagonal ignored); singles is NULL or host [n] single-CU

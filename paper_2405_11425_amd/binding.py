@@ -57,6 +57,7 @@ class _Opts(C.Structure):
 
 
 EXPORTS = ["rr_enumerate_cus", "rr_fill", "rr_rand_read", "rr_probe_pair", "rr_probe_cus", "rr_seq_read", "rr_copy", "rr_chase", "rr_rand_update",
+           "rr_region_granularity", "rr_region_create", "rr_region_destroy",
            "rr_groups_from_heatmap", "rr_shutdown", "rr_strerror", "rr_last_error"]
 
 _lib = None
@@ -101,6 +102,12 @@ def lib():
         L.rr_rand_update.argtypes = [vp, u64, u32, u32, u64, u32, u64, u32, u64, vp, C.POINTER(_Result)]
         L.rr_chase.restype = C.c_int
         L.rr_chase.argtypes = [vp, u64, u32, u64, u64, u32, u64, vp, C.POINTER(_ChaseResult)]
+        L.rr_region_granularity.restype = C.c_int
+        L.rr_region_granularity.argtypes = [C.POINTER(u64), C.POINTER(u64)]
+        L.rr_region_create.restype = C.c_int
+        L.rr_region_create.argtypes = [u64, u64, C.POINTER(vp)]
+        L.rr_region_destroy.restype = C.c_int
+        L.rr_region_destroy.argtypes = [vp]
         L.rr_groups_from_heatmap.restype = C.c_int
         L.rr_groups_from_heatmap.argtypes = [C.POINTER(C.c_double), u32, C.POINTER(C.c_double), C.c_double,
                                              C.POINTER(C.c_uint16), C.POINTER(u32), C.POINTER(u32),
@@ -271,6 +278,47 @@ def copy(dst, src, nbytes: Optional[int] = None, stream=None) -> float:
     ms = C.c_double(0.0)
     _check(lib().rr_copy(dptr, sptr, min(dbytes, sbytes), _stream(stream), C.byref(ms)))
     return float(ms.value)
+
+
+class Region:
+    """A device region made by rr_region_create; accepted wherever a region tensor is (it has data_ptr/numel)."""
+
+    def __init__(self, ptr: int, nbytes: int, piece_bytes: int):
+        self.ptr, self.nbytes, self.piece_bytes = ptr, nbytes, piece_bytes
+
+    def data_ptr(self) -> int:
+        return self.ptr
+
+    def numel(self) -> int:
+        return self.nbytes
+
+    def element_size(self) -> int:
+        return 1
+
+    def destroy(self) -> None:
+        if self.ptr:
+            _check(lib().rr_region_destroy(self.ptr))
+            self.ptr = 0
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.destroy()
+
+
+def region_granularity() -> Tuple[int, int]:
+    """(minimum, recommended) physical allocation granularity of the current device, in bytes."""
+    lo, rec = C.c_uint64(0), C.c_uint64(0)
+    _check(lib().rr_region_granularity(C.byref(lo), C.byref(rec)))
+    return int(lo.value), int(rec.value)
+
+
+def region_create(nbytes: int, piece_bytes: int) -> Region:
+    """Device region of nbytes backed by separate physical pieces of piece_bytes; see rr_region_create."""
+    out = C.c_void_p(None)
+    _check(lib().rr_region_create(nbytes, piece_bytes, C.byref(out)))
+    return Region(int(out.value), nbytes, piece_bytes)
 
 
 def rand_update(region, line_bytes: int, n_updates: int, iters_per_wave: int, draw_seed: int, op: int,

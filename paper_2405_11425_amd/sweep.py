@@ -2,7 +2,7 @@
 measured point to a JSONL file (points already present are skipped, so a run can be resumed).
 
     python -m paper_2405_11425_amd.sweep region  [--out results.jsonl] [--reps 5]
-    python -m paper_2405_11425_amd.sweep lines | windows | probe | stream | zones | groups | latency | pages | updates | calib | all
+    python -m paper_2405_11425_amd.sweep lines | windows | probe | stream | zones | groups | latency | pages | pieces | updates | calib | all
 
   region   throughput vs region size, uniform random 128-byte lines        (paper Sec. 2.1, Fig. 1)
   lines    32 x {4,8,16} B and 64 x 4 B lines at 128 GiB and the largest region (Sec. 2.1, text)
@@ -18,6 +18,11 @@ measured point to a JSONL file (points already present are skipped, so a run can
            power-of-two region (the latency/footprint probe of the TLB literature the paper cites)
   pages    the same walk over N lines that lie one per stride (128 B .. 1 GiB apart): the lines stay cached, so
            what grows with the stride is the cost of translating N different pages (reach of the TLBs)
+  pieces   the paper's situation made on purpose: a region mapped in small separate pieces (--piece-kib), so that a
+           translation covers little and the caches of translations run out.  Throughput vs region size for uniform
+           reads and for windows per CU / XCD / shader engine (Fig. 1 / Fig. 5), one CU's reach, how many CUs of an
+           XCD can run out of their first level together, and the pair probe of 4-CU blocks on windows of their
+           own, which finds the groups that share the second level (Sec. 2.2, 2.3)
   calib    one copy, one fill, one sequential read of known size (for profiler counter calibration)
 
 Throughput is n_reads * line_bytes / kernel time (HIP events), decimal GB/s, and as a
@@ -75,6 +80,8 @@ class Runner:
         free, _ = torch.cuda.mem_get_info()
         self.max_gib = min(args.max_region_gib, int((free - 4 * wl.GiB) // wl.GiB))
         self.cus = rl.enumerate_cus()
+        if args.experiment == "pieces":  # makes its own region
+            self.max_gib = 1
         self.region = torch.empty(self.max_gib * wl.GiB, dtype=torch.uint8, device="cuda")
         t0 = time.perf_counter()
         rl.fill(self.region, wl.FILL_SEED)
@@ -408,6 +415,115 @@ class Runner:
                                 "ns_per_hop": round(statistics.median(ns), 1), "ns_per_hop_min": round(min(ns), 1),
                                 "final_line": runs[0].final_line, **self.meta})
 
+    def pieces(self):
+        """Random reads in a region whose translations are small (rr_region_create)."""
+        rl, wl = self.rl, self.wl
+        piece = self.args.piece_kib * 1024
+        n_pieces = self.args.pieces
+        cus = np.asarray(self.cus)
+        n = len(cus)
+        tag = f"pieces/{self.args.piece_kib}KiB"
+        iters = 1024
+        t0 = time.perf_counter()
+        reg = rl.region_create(n_pieces * piece, piece)
+        created_s = time.perf_counter() - t0
+        rl.fill(reg, wl.FILL_SEED)
+        meta = {"piece_kib": self.args.piece_kib, "n_pieces": n_pieces, "created_s": round(created_s, 2), **self.meta}
+
+        def rate(region_bytes, waves, wm=None, reps=3):
+            call = lambda seed: rl.rand_read(reg, 128, waves * iters, iters, seed, wm, region_bytes=region_bytes)
+            call(1000)
+            res = [call(wl.READ_SEED + i) for i in range(reps)]
+            med = statistics.median(r.kernel_ms_event for r in res)
+            return round(waves * iters * 128 / med / 1e6, 2), res[0].checksum
+
+        def own_windows(selected, w):
+            """The selected CUs, each on a window of w pieces of its own (windows spread over the region)."""
+            n_windows = n_pieces // w
+            windows = [(i * 7919) % n_windows for i in range(len(selected))]
+            assert len(set(windows)) == len(selected)
+            g, wog = wl.window_map_for_selected_cus(n, selected, windows)
+            gbps, _ = rate(n_windows * w * piece, 64 * len(selected), rl.WindowMap(n_windows, g, wog))
+            return gbps
+
+        try:
+            # (A) throughput vs region size, by placement
+            W = wl.resident_logical_waves(n)
+            sizes = [16 * piece << i for i in range(32) if 16 << i <= n_pieces]
+            if sizes[-1] != n_pieces * piece:
+                sizes.append(n_pieces * piece)
+            for size in sizes:
+                key = f"{tag}/size/{size // piece}"
+                if key not in self.seen:
+                    row = {"experiment": "pieces-size", "region_mib": size / wl.MiB, "pieces_in_region": size // piece}
+                    row["gbps_uniform"], row["checksum_uniform"] = rate(size, W)
+                    for name, (g, wog), nw in (("random_per_cu_8", wl.window_map_random_per_cu(n, 8, 8), 8),
+                                               ("random_per_cu_32", wl.window_map_random_per_cu(n, 32, 32), 32),
+                                               ("xcd_8", wl.window_map_by_xcd(cus, 8), 8),
+                                               ("shader_engine_32", wl.window_map_by_se(cus, 32), 32),
+                                               ("own_per_cu", wl.window_map_own_per_cu(n), n)):
+                        G = len(wog)
+                        if (size // 128) % nw == 0:
+                            row[f"gbps_{name}"], _ = rate(size, (W + G - 1) // G * G, rl.WindowMap(nw, g, wog))
+                    self.emit(key, {**row, **meta})
+            # (B) one CU alone on a window of w pieces
+            key = f"{tag}/reach"
+            if key not in self.seen:
+                widths = [w for w in (4, 8, 16, 24, 28, 32, 36, 40, 48, 56, 64, 72, 80, 96, 128, 256, 512, 1024, 4096)
+                          if w <= n_pieces]
+                self.emit(key, {"experiment": "pieces-reach", "cu": 0, "window_pieces": widths,
+                                "gbps": [own_windows([0], w) for w in widths], **meta})
+            # (C) several CUs, each inside a window of its own: of one XCD, and spread over the XCDs
+            # CUs of an XCD taken round-robin over its shader engines, so that no shader engine saturates first
+            per_xcd = [sorted((c for c in range(n) if cus[c][0] == x), key=lambda c: (int(cus[c][3]), int(cus[c][1])))
+                       for x in sorted(set(cus[:, 0].tolist()))]
+            xcd0 = per_xcd[0]
+            for w in (16, 48):
+                key = f"{tag}/share/{w}"
+                if key in self.seen or n_pieces // w < n:
+                    continue
+                counts = [k for k in (1, 2, 4, 6, 8, 16, len(xcd0)) if k <= len(xcd0)]
+                spread = [k for k in (1, 2, 4, 6, 8, 16, len(xcd0)) if k <= min(len(x) for x in per_xcd)]
+                self.emit(key, {"experiment": "pieces-share", "window_pieces": w, "cus_of_one_xcd": counts,
+                                "gbps_per_cu_one_xcd": [round(own_windows(xcd0[:k], w) / k, 2) for k in counts],
+                                "cus_per_xcd_all_xcds": spread,
+                                "gbps_per_cu_all_xcds": [round(own_windows([c for x in per_xcd for c in x[:k]], w)
+                                                               / (k * len(per_xcd)), 2) for k in spread], **meta})
+            # (D) pair probe: blocks of four CUs, every CU on its own window of 48 pieces
+            blk, w = 4, 48
+            key = f"{tag}/probe/{blk}x{w}"
+            if key not in self.seen and n_pieces // w >= 2 * blk:
+                n_units = min(self.args.probe_cus, n // blk)
+                step = (n // blk) / n_units
+                units = [list(range(int(i * step) * blk, int(i * step) * blk + blk)) for i in range(n_units)]
+                singles = np.array([own_windows(u, w) for u in units])
+                T = np.zeros((n_units, n_units))
+                t0 = time.perf_counter()
+                for i in range(n_units):
+                    for j in range(i + 1, n_units):
+                        T[i, j] = T[j, i] = own_windows(units[i] + units[j], w)
+                    print(f"# pieces probe row {i + 1}/{n_units}, {time.perf_counter() - t0:.1f} s", file=sys.stderr,
+                          flush=True)
+                group, order, thr = rl.groups_from_heatmap(T, singles, self.args.min_gap)
+                ratio = (T / (singles[:, None] + singles[None, :]))[np.triu_indices(n_units, 1)]
+                base = os.path.splitext(self.args.out)[0] if self.args.out else None
+                if base:
+                    np.savetxt(f"{base}.pieces_probe_heatmap.txt", T, fmt="%.2f")
+                n_groups = int(group.max()) + 1
+                xcd_of_unit = [int(cus[u[0]][0]) for u in units]
+                same_xcd = all(len({xcd_of_unit[i] for i in range(n_units) if group[i] == g}) == 1 for g in range(n_groups))
+                self.emit(key, {"experiment": "pieces-probe", "unit_cus": blk, "window_pieces": w, "n_units": n_units,
+                                "single_gbps_median": round(float(np.median(singles)), 2),
+                                "ratio_min": round(float(ratio.min()), 3), "ratio_median": round(float(np.median(ratio)), 3),
+                                "ratio_max": round(float(ratio.max()), 3),
+                                "threshold": None if np.isnan(thr) else round(thr, 3), "n_groups": n_groups,
+                                "group_sizes_in_cus": sorted(set((np.bincount(group) * blk).tolist())),
+                                "groups_are_xcds": bool(same_xcd and n_groups == len(per_xcd)),
+                                "group_of_unit": group.tolist(), "xcd_of_unit": xcd_of_unit,
+                                "seconds": round(time.perf_counter() - t0, 1), **meta})
+        finally:
+            reg.destroy()
+
     def calib(self):
         """Three kernels of exactly known traffic, 8 GiB each, for scaling FETCH_SIZE / WRITE_SIZE."""
         rl, wl = self.rl, self.wl
@@ -422,7 +538,9 @@ class Runner:
 def main(argv=None):
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
     ap.add_argument("experiment", choices=["region", "lines", "windows", "probe", "stream", "zones", "groups",
-                                           "latency", "pages", "updates", "calib", "all"])
+                                           "latency", "pages", "pieces", "updates", "calib", "all"])
+    ap.add_argument("--piece-kib", type=int, default=128, help="pieces: size of a separately mapped piece")
+    ap.add_argument("--pieces", type=int, default=24576, help="pieces: how many (at most 30000)")
     ap.add_argument("--zone-windows", type=int, default=32)
     ap.add_argument("--out", default=None, help="JSONL file to append to (and to resume from)")
     ap.add_argument("--reps", type=int, default=5)
@@ -436,12 +554,12 @@ def main(argv=None):
     ap.add_argument("--block", type=int, default=0)
     args = ap.parse_args(argv)
     r = Runner(args)
-    todo = (["region", "lines", "windows", "stream", "latency", "pages", "updates", "groups", "zones", "probe"]
+    todo = (["region", "lines", "windows", "stream", "latency", "pages", "updates", "groups", "zones", "probe", "pieces"]
             if args.experiment == "all"
             else [args.experiment])
     for name in todo:
         {"region": r.region_sweep, "lines": r.line_sweep, "windows": r.window_sweep, "probe": r.probe,
-         "stream": r.stream, "zones": r.zones, "groups": r.groups, "latency": r.latency, "pages": r.pages,
+         "stream": r.stream, "zones": r.zones, "groups": r.groups, "latency": r.latency, "pages": r.pages, "pieces": r.pieces,
          "updates": r.updates, "calib": r.calib}[name]()
     return 0
 

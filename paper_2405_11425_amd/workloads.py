@@ -98,6 +98,19 @@ def window_map_random_per_cu(n_cus: int, n_windows: int, seed: int) -> Tuple[np.
     return group_of_cu, window_of_group
 
 
+def window_map_own_per_cu(n_cus: int) -> Tuple[np.ndarray, np.ndarray]:
+    """Every CU is its own group with a window of its own (n_windows = n_cus): the finest placement."""
+    ids = np.arange(n_cus, dtype=np.uint16)
+    return ids, ids.copy()
+
+
+def window_map_for_selected_cus(n_cus: int, selected: Sequence[int], windows: Sequence[int]) -> Tuple[np.ndarray, np.ndarray]:
+    """Only the selected CUs take part, the i-th of them as group i reading windows[i]; all others are excluded."""
+    group_of_cu = np.full(n_cus, 0xFFFF, dtype=np.uint16)
+    group_of_cu[np.asarray(selected, dtype=np.int64)] = np.arange(len(selected), dtype=np.uint16)
+    return group_of_cu, np.asarray(windows, dtype=np.uint16)
+
+
 def window_map_by_xcd(cu_table: np.ndarray, n_windows: int) -> Tuple[np.ndarray, np.ndarray]:
     """Group = XCD (the first hardware coordinate); XCD x reads window x mod n_windows
     (the paper's group-to-chunk placement, Sec. 2.4, with the XCD as the group)."""

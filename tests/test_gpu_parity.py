@@ -150,6 +150,40 @@ def test_chase_closed_cycle_over_pages(region, dist, n):
         assert got.final_line == (hops % n) * (stride // 128)
 
 
+# ------------------------------------------------------------------ regions mapped in pieces
+def test_piecewise_region_behaves_like_any_region():
+    """A region backed by separate 128 KiB allocations: same bytes after the fill, same checksums (with and
+    without windows, pinned CUs included), and the library gives the memory back."""
+    lo, rec = rl.region_granularity()
+    assert lo > 0 and rec >= lo
+    piece = 128 << 10
+    assert piece % lo == 0
+    reg = rl.region_create(96 * piece, piece)
+    assert reg.ptr % piece == 0
+    R = reg.numel()
+    rl.fill(reg, wl.FILL_SEED)
+    back = torch.empty(R, dtype=torch.uint8, device="cuda")
+    rl.copy(back, reg)
+    assert np.array_equal(back.cpu().numpy(), orc.fill_buffer(R, wl.FILL_SEED))
+    got = rl.rand_read(reg, 128, 300 * 200, 200, 7)
+    assert got.checksum == orc.checksum(R, 128, 300, 200, wl.FILL_SEED, 7)
+    n = len(rl.enumerate_cus())
+    g, w = wl.window_map_for_selected_cus(n, [5, n - 1, 17], [1, 3, 0])
+    got = rl.rand_read(reg, 128, 30 * 64, 64, 9, rl.WindowMap(4, g, w))
+    assert got.checksum == orc.checksum(R, 128, 30, 64, wl.FILL_SEED, 9, 4, w)
+    reg.destroy()
+    reg.destroy()                                              # a second call is a no-op of the wrapper
+    with pytest.raises(rl.RandlineError):
+        rl.binding._check(rl.lib().rr_region_destroy(back.data_ptr()))   # not ours
+    free_before, _ = torch.cuda.mem_get_info()
+    with rl.region_create(128 << 21, 2 << 20) as again:        # the library can map again: 256 MiB in 2 MiB pieces
+        free_during, _ = torch.cuda.mem_get_info()
+        rl.fill(again, 3)
+        assert rl.seq_read(again, again.numel()).checksum == orc.sum_words(3, 0, again.numel() // 4)
+    free_after, _ = torch.cuda.mem_get_info()
+    assert free_before - free_during >= 200 << 20 and free_after - free_during >= 200 << 20   # taken, and given back
+
+
 # ------------------------------------------------------------------ random line write / add
 @pytest.mark.parametrize("R,B,lanes,W,I", [
     (4096, 128, 32, 4, 8), (12288, 128, 32, 5, 37), (1 << 20, 128, 32, 7, 100), (3 << 20, 256, 32, 77, 95),

@@ -119,6 +119,21 @@ def test_chase_validation():
         assert e.value.code == rl.RR_EINVAL and needle in str(e.value)
 
 
+def test_region_create_validation():
+    """Argument checks of the piecewise region come before any HIP call."""
+    for args, needle in (((0, 4096), "multiple of piece_bytes"), ((8192, 0), "multiple of piece_bytes"),
+                         ((8192, 12288), "multiple of piece_bytes"), ((3000, 1000), "4096"),
+                         ((1 << 40, 4096), "30000 pieces")):
+        with pytest.raises(rl.RandlineError) as e:
+            rl.region_create(*args)
+        assert e.value.code == rl.RR_EINVAL and needle in str(e.value)
+    out = C.c_void_p(77)
+    assert rl.lib().rr_region_create(0, 4096, C.byref(out)) == rl.RR_EINVAL and out.value == 77
+    assert rl.lib().rr_region_create(4096, 4096, None) == rl.RR_EINVAL
+    assert rl.lib().rr_region_destroy(12345) == rl.RR_EINVAL
+    assert rl.lib().rr_region_granularity(None, None) == rl.RR_EINVAL
+
+
 def test_out_left_untouched_on_failure():
     res = rl.binding._Result(123, 1.0, 2.0, 4, 5)
     rc = rl.lib().rr_rand_read(1 << 21, 1000, 128, 32, 8, 8, None, 7, None, None, C.byref(res))
@@ -176,6 +191,10 @@ def test_window_maps_are_valid():
     assert all(len({(int(x), int(s)) for x, s in table[g == k][:, :2]}) == 1 for k in range(32))
     g, w = wl.window_map_from_groups([0, 0, 1, 1, 2, 0xFFFF], 2)
     assert w.tolist() == [0, 1, 0]
+    g, w = wl.window_map_own_per_cu(256)
+    assert g.tolist() == list(range(256)) == w.tolist()
+    g, w = wl.window_map_for_selected_cus(16, [9, 3], [5, 0])
+    assert w.tolist() == [5, 0] and g[9] == 0 and g[3] == 1 and (np.delete(g, [3, 9]) == 0xFFFF).all()
 
 
 def test_probe_sample_and_configs():
