@@ -54,6 +54,8 @@ def main():
               "(no multi-GPU path is built: see DESIGN.md, 'How the path would shard').", file=sys.stderr)
         return 2
 
+    from paper_2405_11425_amd import envinfo
+    env = envinfo.environment()          # before this process touches the GPU
     import torch
     import paper_2405_11425_amd as rl
     from paper_2405_11425_amd import workloads as wl
@@ -61,6 +63,7 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback.", file=sys.stderr)
         return 3
+    env.update(envinfo.device_facts())
     if not os.path.exists(rl.library_path()):
         print("bench.py: librandline.so is not built (run __graft_entry__.build()).", file=sys.stderr)
         return 3
@@ -132,6 +135,7 @@ def main():
                    "n_cus": n_cus},
         "pct_of_hbm_peak": round(value / HBM_PEAK_GBPS * 100, 1),
         "curve": curve,
+        "environment": env,
         "gbps_at_largest_region": curve[-1]["gbps"],
         "fill_gbps": round(max_gib * GiB / fill_s / 1e9, 1),
         "roofline": roofline,

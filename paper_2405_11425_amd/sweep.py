@@ -71,12 +71,15 @@ def _runs(windows, width):
 
 class Runner:
     def __init__(self, args):
+        from . import envinfo
+        env = envinfo.environment()  # before this process touches the GPU
         import torch
         from . import binding as rl
         from . import workloads as wl
         self.torch, self.rl, self.wl, self.args = torch, rl, wl, args
         if not torch.cuda.is_available():
             raise SystemExit("sweep: no GPU visible (the HIP path has no CPU fallback)")
+        env.update(envinfo.device_facts())
         free, _ = torch.cuda.mem_get_info()
         self.max_gib = min(args.max_region_gib, int((free - 4 * wl.GiB) // wl.GiB))
         self.cus = rl.enumerate_cus()
@@ -89,7 +92,7 @@ class Runner:
         self.seen = _rows(args.out)
         self.launch = {k: v for k, v in dict(unroll=args.unroll, bcast=args.bcast, nontemporal=args.nt,
                                              block_threads=args.block).items() if v}
-        self.meta = {"device": torch.cuda.get_device_name(0), "n_cus": len(self.cus),
+        self.meta = {"device": torch.cuda.get_device_name(0), "environment": env, "n_cus": len(self.cus),
                      "allocation_gib": self.max_gib, "fill_gbps": round(self.max_gib * wl.GiB / self.fill_s / 1e9, 1),
                      "launch": self.launch}
 
