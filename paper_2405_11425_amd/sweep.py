@@ -419,8 +419,11 @@ class Runner:
                                 "final_line": runs[0].final_line, **self.meta})
 
     def pieces(self):
-        """Random reads in a region whose translations are small (rr_region_create)."""
+        """Random reads in a region whose translations are small (rr_region_create).  Runs last: it gives the
+        large region back first, so that the pieces find memory."""
         rl, wl = self.rl, self.wl
+        self.region = None
+        self.torch.cuda.empty_cache()
         piece = self.args.piece_kib * 1024
         n_pieces = self.args.pieces
         cus = np.asarray(self.cus)
