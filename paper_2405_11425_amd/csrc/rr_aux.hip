@@ -1,0 +1,226 @@
+// The streaming and latency companions of the random read: fill, sequential read, plain copy and
+// the dependent-load walk, with their entry points.
+#include <cstring>
+
+#include "rr_host.hpp"
+#include "rr_read_kernel.hpp"
+
+namespace rr {
+
+// Region as uint64[]: element j = mix64(seed + (j+1)*gamma).  Each thread writes
+// 16 bytes per step (two consecutive elements), grid-stride.
+typedef u64 u64x2 __attribute__((ext_vector_type(2)));
+__global__ void __launch_bounds__(256) fill_kernel(u64x2 *out, u64 n_pairs, u64 seed) {
+    const u64 stride = (u64)gridDim.x * blockDim.x;
+    u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x;
+    u64 ctr = seed + (2 * i + 1) * kGamma;  // state of element 2i
+    const u64 ctr_step = 2 * stride * kGamma;
+    for (; i < n_pairs; i += stride) {
+        u64x2 v;
+        v.x = mix64(ctr);
+        v.y = mix64(ctr + kGamma);
+        __builtin_nontemporal_store(v, &out[i]);  // one 16-byte store per lane
+        ctr += ctr_step;
+    }
+}
+
+// Streaming counterpart of the random read: every 32-bit word of the region is
+// read once (the sequential reads the paper expects to be faster than random
+// lines, Sec. 2.1).  Each wave owns contiguous 8 KiB chunks (eight 16-byte loads
+// per lane in flight, consecutive lanes on consecutive addresses), chunks dealt
+// round-robin to the waves -- measured 3 % faster than a plain grid-stride loop;
+// what does not fill a chunk is read grid-stride.  Same checksum convention:
+// wrapping 64-bit sum of zero-extended words, one atomic per wave.
+__global__ void __launch_bounds__(256) seq_read_kernel(const u32x4 *src, u64 n_vec, Scratch *s) {
+    typedef const u32x4 __attribute__((address_space(1))) *gptr;
+    constexpr u32 kLoads = 8;
+    gptr g = (gptr)(u64)src;
+    const u32 lane = threadIdx.x & 63;
+    const u64 wave = ((u64)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const u64 n_waves = ((u64)gridDim.x * blockDim.x) >> 6;
+    const u64 n_chunks = n_vec / (64 * kLoads);
+    const u64 t0 = clock_ticks();
+    Acc acc{0u, 0u};
+    for (u64 c = wave; c < n_chunks; c += n_waves) {
+        const u64 base = c * (64 * kLoads) + lane;
+        u32x4 v[kLoads];
+#pragma unroll
+        for (u32 k = 0; k < kLoads; ++k) v[k] = __builtin_nontemporal_load(g + base + k * 64);
+#pragma unroll
+        for (u32 k = 0; k < kLoads; ++k) acc.add(v[k]);
+    }
+    const u64 stride = (u64)gridDim.x * blockDim.x;
+    for (u64 i = n_chunks * (64 * kLoads) + (u64)blockIdx.x * blockDim.x + threadIdx.x; i < n_vec; i += stride)
+        acc.add(__builtin_nontemporal_load(g + i));
+    const u64 total = wave_sum(acc.value());
+    const u64 t1 = clock_ticks();
+    if (lane == 0) {
+        Cell *c = &s->cells[wave & (kNumCells - 1)];
+        atomicAdd(&c->sum, total);
+        atomicMin(&c->t_min, t0);
+        atomicMax(&c->t_max, t1);
+        atomicAdd(&c->waves, 1u);
+    }
+}
+
+// Dependent-load walk by a single wavefront; every lane follows the same chain
+// (uniform address, broadcast load), lane 0 reports.
+struct ChaseOut {
+    u64 final_line, word_sum, ticks;
+};
+__global__ void __launch_bounds__(64) chase_kernel(const char *region, Reducer red, u32 log2_line, u64 start,
+                                                   u64 stride, u32 mask, u64 hops, ChaseOut *out) {
+    typedef const u32 __attribute__((address_space(1))) *gptr;
+    u64 line = start, sum = 0;
+    const u64 t0 = clock_ticks();
+    for (u64 k = 0; k < hops; ++k) {
+        const u32 word = *(gptr)((u64)region + (line << log2_line));
+        sum += word;
+        const u32 salt = (u32)k * 0x9E3779B9u;  // hop-dependent, so the walk cannot close into a short cycle
+        line = reduce_to_line(line + stride + (u64)((word ^ salt) & mask), red);
+    }
+    const u64 t1 = clock_ticks();
+    if (threadIdx.x == 0) {
+        out->final_line = line;
+        out->word_sum = sum;
+        out->ticks = t1 - t0;
+    }
+}
+
+// Plain copy, 16 bytes per lane and step, grid-stride: a kernel of exactly known
+// HBM traffic (bytes read = bytes written = n_vec * 16).
+__global__ void __launch_bounds__(256) copy_kernel(u32x4 *dst, const u32x4 *src, u64 n_vec) {
+    const u64 stride = (u64)gridDim.x * blockDim.x;
+    for (u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x; i < n_vec; i += stride)
+        __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
+}
+
+}  // namespace rr
+
+using namespace rr;
+
+extern "C" int rr_fill(void *region, uint64_t region_bytes, uint64_t fill_seed, void *hip_stream) {
+    if (!region) return fail(RR_EINVAL, "region is NULL");
+    if ((uintptr_t)region % 16 != 0) return fail(RR_EINVAL, "region is not 16-byte aligned");
+    if (region_bytes % 16 != 0) return fail(RR_EINVAL, "region_bytes must be a multiple of 16");
+    if (region_bytes == 0) return RR_OK;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    int dev = 0, n_cu = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    HIP_TRY(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
+    const u64 n_pairs = region_bytes / 16;
+    u64 blocks = (n_pairs + 255) / 256;
+    const u64 cap = (u64)n_cu * 16;  // grid-stride beyond this
+    if (blocks > cap) blocks = cap;
+    hipLaunchKernelGGL(fill_kernel, dim3((u32)blocks), dim3(256), 0, stream, (u64x2 *)region, n_pairs,
+                       (u64)fill_seed);
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipStreamSynchronize(stream));
+    return RR_OK;
+}
+
+extern "C" int rr_seq_read(const void *region, uint64_t region_bytes, void *hip_stream, rr_result_t *out) {
+    if (!out) return fail(RR_EINVAL, "out is NULL");
+    if (!region) return fail(RR_EINVAL, "region is NULL");
+    if ((uintptr_t)region % 16 != 0) return fail(RR_EINVAL, "region is not 16-byte aligned");
+    if (region_bytes % 16 != 0) return fail(RR_EINVAL, "region_bytes must be a multiple of 16");
+    rr_result_t res;
+    memset(&res, 0, sizeof res);
+    if (region_bytes == 0) {
+        *out = res;
+        return RR_OK;
+    }
+    hipStream_t stream = (hipStream_t)hip_stream;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    DeviceState *st = nullptr;
+    int rc = get_state(stream, &st);
+    if (rc != RR_OK) return rc;
+    const u64 n_vec = region_bytes / 16;
+    u64 blocks = (n_vec + 255) / 256;
+    const u64 cap = 16ull * st->cus.size();  // two rounds of resident workgroups; each wave loops over its chunks
+    if (blocks > cap) blocks = cap;
+    rc = begin_cells(*st, stream);
+    if (rc != RR_OK) return rc;
+    HIP_TRY(hipEventRecord(st->ev0, stream));
+    hipLaunchKernelGGL(seq_read_kernel, dim3((u32)blocks), dim3(256), 0, stream, (const u32x4 *)region, n_vec,
+                       st->scratch);
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipEventRecord(st->ev1, stream));
+    rc = finish_and_wait(*st, 0u, 1u, 0u, stream);
+    if (rc != RR_OK) return rc;
+    float ms = 0.f;
+    HIP_TRY(hipEventElapsedTime(&ms, st->ev0, st->ev1));
+    res.checksum = st->head->checksum;
+    res.kernel_ms_event = ms;
+    res.kernel_ms_device = (double)(st->head->t_max - st->head->t_min) / (double)st->wall_khz;
+    res.waves_run = st->head->waves_run;
+    res.launches = 1;
+    *out = res;
+    return RR_OK;
+}
+
+extern "C" int rr_chase(const void *region, uint64_t region_bytes, uint32_t line_bytes, uint64_t start,
+                        uint64_t stride, uint32_t mask, uint64_t hops, void *hip_stream, rr_chase_result_t *out) {
+    if (!out) return fail(RR_EINVAL, "out is NULL");
+    if (!region) return fail(RR_EINVAL, "region is NULL");
+    if (line_bytes != 128 && line_bytes != 256 && line_bytes != 512)
+        return fail(RR_EINVAL, "line_bytes must be 128, 256 or 512 (got %u)", line_bytes);
+    if (region_bytes == 0 || region_bytes % line_bytes != 0)
+        return fail(RR_EINVAL, "region_bytes must be a positive multiple of line_bytes");
+    if ((uintptr_t)region % line_bytes != 0) return fail(RR_EINVAL, "region is not aligned to line_bytes");
+    const u64 n_lines = region_bytes / line_bytes;
+    if (n_lines > (1ull << 32)) return fail(RR_EINVAL, "region has more than 2^32 lines");
+    if (start >= n_lines) return fail(RR_EINVAL, "start must be below the number of lines");
+    if (hops == 0) return fail(RR_EINVAL, "hops must be at least 1");
+    hipStream_t stream = (hipStream_t)hip_stream;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    DeviceState *st = nullptr;
+    int rc = get_state(stream, &st);
+    if (rc != RR_OK) return rc;
+    // the walk's three result words go through the (otherwise idle) key-mark area of the scratch
+    ChaseOut *dev_out = (ChaseOut *)st->scratch->key_seen;
+    const u32 log2_line = line_bytes == 128 ? 7 : line_bytes == 256 ? 8 : 9;
+    HIP_TRY(hipEventRecord(st->ev0, stream));
+    hipLaunchKernelGGL(chase_kernel, dim3(1), dim3(64), 0, stream, (const char *)region, make_reducer(n_lines),
+                       log2_line, (u64)start, (u64)(stride % n_lines), mask, (u64)hops, dev_out);
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipEventRecord(st->ev1, stream));
+    ChaseOut host;
+    HIP_TRY(hipMemcpyAsync(&host, dev_out, sizeof host, hipMemcpyDeviceToHost, stream));
+    HIP_TRY(hipStreamSynchronize(stream));
+    float ms = 0.f;
+    HIP_TRY(hipEventElapsedTime(&ms, st->ev0, st->ev1));
+    out->final_line = host.final_line;
+    out->word_sum = host.word_sum;
+    out->kernel_ms_event = ms;
+    out->ns_per_hop = (double)host.ticks * 1e6 / (double)st->wall_khz / (double)hops;
+    return RR_OK;
+}
+
+extern "C" int rr_copy(void *dst, const void *src, uint64_t bytes, void *hip_stream, double *kernel_ms) {
+    if (!dst || !src) return fail(RR_EINVAL, "dst or src is NULL");
+    if ((uintptr_t)dst % 16 != 0 || (uintptr_t)src % 16 != 0 || bytes % 16 != 0)
+        return fail(RR_EINVAL, "dst, src and bytes must be multiples of 16");
+    const uintptr_t d = (uintptr_t)dst, c = (uintptr_t)src;
+    if (d < c + bytes && c < d + bytes && bytes > 0) return fail(RR_EINVAL, "dst and src overlap");
+    if (kernel_ms) *kernel_ms = 0.0;
+    if (bytes == 0) return RR_OK;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    DeviceState *st = nullptr;
+    int rc = get_state(stream, &st);
+    if (rc != RR_OK) return rc;
+    const u64 n_vec = bytes / 16;
+    u64 blocks = (n_vec + 255) / 256;
+    const u64 cap = (u64)st->cus.size() * 8;
+    if (blocks > cap) blocks = cap;
+    HIP_TRY(hipEventRecord(st->ev0, stream));
+    hipLaunchKernelGGL(copy_kernel, dim3((u32)blocks), dim3(256), 0, stream, (u32x4 *)dst, (const u32x4 *)src, n_vec);
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipEventRecord(st->ev1, stream));
+    HIP_TRY(hipStreamSynchronize(stream));
+    float ms = 0.f;
+    HIP_TRY(hipEventElapsedTime(&ms, st->ev0, st->ev1));
+    if (kernel_ms) *kernel_ms = ms;
+    return RR_OK;
+}
