@@ -157,6 +157,7 @@ class Runner:
                 key = f"windows/{scheme}/{n_windows}/{cfg.name}"
                 if key not in self.seen:
                     self.emit(key, {"experiment": "windows", "scheme": scheme, "n_windows": n_windows,
+                                    "window_of_group": w.tolist(),
                                     **self.timed_read(cfg, rl.WindowMap(n_windows, g, w)), **self.meta})
 
     def probe(self):
@@ -207,7 +208,8 @@ class Runner:
         n_groups = int(group.max()) + 1
         sizes = np.bincount(group, minlength=n_groups) * blk
         first = [u[0] for u in units]
-        self.emit(key, {"experiment": "probe", "unit_cus": blk, "n_units": m, "units_first_cu": first,
+        self.emit(key, {"experiment": "probe", "unit_cus": blk, "n_units": m, "region_gib": cfg.region_bytes / wl.GiB,
+                        "n_reads": n_reads, "iters_per_wave": cfg.iters_per_wave, "units_first_cu": first,
                         "unit_coords_first_cu": self.cus[first].tolist(), "n_pairs": m * (m - 1) // 2,
                         "pair_gbps_min": round(float(off.min()), 2), "pair_gbps_median": round(float(np.median(off)), 2),
                         "pair_gbps_max": round(float(off.max()), 2),
@@ -363,6 +365,7 @@ class Runner:
                 res = [call(cfg.read_seed + i) for i in range(self.args.reps)]
                 med = statistics.median(r.kernel_ms_event for r in res)
                 self.emit(key, {"experiment": "updates", "op": name, "region_gib": gib, "n_updates": cfg.n_reads,
+                                "iters_per_wave": cfg.iters_per_wave, "value_seed": 99,
                                 "kernel_ms_median": round(med, 4), "gbps_lines": round(cfg.bytes_read / med / 1e6, 1),
                                 "pct_of_hbm_peak": round(cfg.bytes_read / med / 1e6 / HBM_PEAK_GBPS * 100, 1),
                                 "note": "line bytes per second; an add reads and writes every line",
@@ -461,7 +464,8 @@ class Runner:
             for size in sizes:
                 key = f"{tag}/size/{size // piece}"
                 if key not in self.seen:
-                    row = {"experiment": "pieces-size", "region_mib": size / wl.MiB, "pieces_in_region": size // piece}
+                    row = {"experiment": "pieces-size", "region_mib": size / wl.MiB, "pieces_in_region": size // piece,
+                           "n_reads": W * iters, "iters_per_wave": iters}
                     row["gbps_uniform"], row["checksum_uniform"] = rate(size, W)
                     for name, (g, wog), nw in (("random_per_cu_8", wl.window_map_random_per_cu(n, 8, 8), 8),
                                                ("random_per_cu_32", wl.window_map_random_per_cu(n, 32, 32), 32),

@@ -119,6 +119,30 @@ def test_chase_validation():
         assert e.value.code == rl.RR_EINVAL and needle in str(e.value)
 
 
+def test_verify_sweep_tool(tmp_path, worked):
+    """The result checker recomputes a row's checksum from what the row says: a row holding the worked PR1 value
+    matches, the same row with one bit flipped does not, rows without a checksum are skipped."""
+    import io
+    import json
+    import verify_sweep
+    pr1 = int(worked["pr1_W256_I4096"][0])
+    base = {"experiment": "region", "region_gib": 0.25, "line_bytes": 128, "lanes_per_line": 32, "n_reads": 1 << 20,
+            "iters_per_wave": 4096}
+    rows = [{"key": "good", **base, "checksum_first_seed": pr1},
+            {"key": "bad", **base, "checksum_first_seed": pr1 ^ 2},
+            {"key": "big", **base, "n_reads": 1 << 40, "checksum_first_seed": 0},
+            {"key": "other", "experiment": "groups"}]
+    path = tmp_path / "r.jsonl"
+    path.write_text("\n".join(json.dumps(r) for r in rows) + "\n")
+    out = io.StringIO()
+    assert verify_sweep.verify(str(path), 2, 3e8, out) == (1, 1, 2)
+    text = out.getvalue()
+    assert "good: match" in text and "bad: MISMATCH" in text and "big: skipped" in text and "other: skipped" in text
+    assert verify_sweep.main([str(path), "--threads", "2"]) == 1
+    path.write_text(json.dumps(rows[0]) + "\n")
+    assert verify_sweep.main([str(path), "--threads", "2"]) == 0
+
+
 def test_region_create_validation():
     """Argument checks of the piecewise region come before any HIP call."""
     for args, needle in (((0, 4096), "multiple of piece_bytes"), ((8192, 0), "multiple of piece_bytes"),
