@@ -51,7 +51,8 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this benchmark is a single-GPU measurement; --gpus must be 1 "
-              "(no multi-GPU path is built: see DESIGN.md, 'How the path would shard').", file=sys.stderr)
+              "(no multi-GPU path is built; each GPU would run its own range of logical waves and the checksums add).",
+              file=sys.stderr)
         return 2
 
     from paper_2405_11425_amd import envinfo
