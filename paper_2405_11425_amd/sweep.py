@@ -352,7 +352,7 @@ class Runner:
         rl, wl = self.rl, self.wl
         n = len(self.cus)
         touched = False
-        for gib in sorted({min(16, self.max_gib), min(64, self.max_gib), self.max_gib}):
+        for gib in sorted({min(g, self.max_gib) for g in (1, 16, 64, 128, 192, 256)}):
             cfg = wl.ReadConfig(f"update-{gib}GiB", gib * wl.GiB, 128, 32, wl.resident_logical_waves(n), wl.ITERS_PER_WAVE)
             for op, name in ((rl.OP_WRITE, "write"), (rl.OP_ADD, "add")):
                 key = f"updates/{name}/{cfg.name}"
