@@ -150,6 +150,28 @@ def test_chase_closed_cycle_over_pages(region, dist, n):
         assert got.final_line == (hops % n) * (stride // 128)
 
 
+def test_calls_on_a_side_stream():
+    """Every entry point works on the stream it is given (explicitly, or torch's current one) and is ordered
+    after what that stream already holds."""
+    side = torch.cuda.Stream()
+    R = 1 << 24
+    with torch.cuda.stream(side):
+        buf = torch.empty(R + 256, dtype=torch.uint8, device="cuda")
+        buf.fill_(0xAB)                                   # queued on the side stream; rr_fill must come after it
+        rl.fill(buf, 5, region_bytes=R, stream=side)
+        got = rl.rand_read(buf, 128, 64 * 100, 100, 3, region_bytes=R, stream=side)
+        tick = rl.rand_read(buf, 128, 64 * 100, 100, 3, region_bytes=R, stream=side, mode=rl.MODE_TICKET)
+        wide = rl.rand_read(buf, 256, 33 * 7, 7, 9, region_bytes=R)        # stream=None -> torch's current stream
+        seq = rl.seq_read(buf, R, stream=side)
+        walk = rl.chase(buf, 128, 1, 3, 0xFFF, 500, region_bytes=R, stream=side)
+    side.synchronize()
+    assert got.checksum == tick.checksum == orc.checksum(R, 128, 64, 100, 5, 3)
+    assert wide.checksum == orc.checksum(R, 256, 33, 7, 5, 9)
+    assert seq.checksum == orc.sum_words(5, 0, R // 4)
+    assert (walk.final_line, walk.word_sum) == orc.chase(R, 128, 5, 1, 3, 0xFFF, 500)
+    assert (buf[R:].cpu() == 0xAB).all()
+
+
 # ------------------------------------------------------------------ regions mapped in pieces
 def test_piecewise_region_behaves_like_any_region():
     """A region backed by separate 128 KiB allocations: same bytes after the fill, same checksums (with and
