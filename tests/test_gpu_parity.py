@@ -172,6 +172,31 @@ def test_calls_on_a_side_stream():
     assert (buf[R:].cpu() == 0xAB).all()
 
 
+def test_concurrent_callers_are_serialised(region):
+    """Two host threads calling at once (ctypes drops the GIL): the library's lock keeps the shared scratch of the
+    device to one call at a time, so every call still returns its own exact checksum."""
+    import threading
+    R = 1 << 26
+    jobs = {0: (128, 96, 50, 11, rl.MODE_AUTO), 1: (256, 40, 77, 12, rl.MODE_TICKET)}
+    want = {k: orc.checksum(R, B, W, I, wl.FILL_SEED, seed) for k, (B, W, I, seed, _) in jobs.items()}
+    bad = []
+
+    def worker(k):
+        B, W, I, seed, mode = jobs[k]
+        stream = torch.cuda.Stream()
+        for _ in range(40):
+            got = rl.rand_read(region, B, W * I, I, seed, region_bytes=R, stream=stream, mode=mode)
+            if got.checksum != want[k]:
+                bad.append((k, got.checksum))
+
+    threads = [threading.Thread(target=worker, args=(k,)) for k in jobs]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not bad
+
+
 # ------------------------------------------------------------------ regions mapped in pieces
 def test_piecewise_region_behaves_like_any_region():
     """A region backed by separate 128 KiB allocations: same bytes after the fill, same checksums (with and
