@@ -32,9 +32,12 @@
  *     arguments are left untouched.  rr_last_error() gives a message for the
  *     calling thread's last failure.  All RR_EINVAL checks that do not need the
  *     device are made before the first HIP call.
- *   - The library keeps a few KB of device scratch per GPU (checksum cell,
+ *   - The library keeps about 320 KB of device scratch per GPU (result cells,
  *     ticket counters, timestamps, lookup tables), created on first use and
- *     released by rr_shutdown().  Calls that overlap on one GPU are not supported.
+ *     released by rr_shutdown().
+ *   - Threads: any thread may call.  The calls that launch kernels share that
+ *     scratch, so the library runs them one at a time (one lock); each waits for
+ *     its own kernels before it returns and lets the next one in.
  */
 #ifndef RANDLINE_H
 #define RANDLINE_H
