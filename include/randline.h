@@ -141,8 +141,8 @@ typedef struct {
  * 96 GiB thirds of the HBM are being read at the same time by anyone (measure
  * it with the "zones" experiment of the sweep driver); restricting each compute
  * group to a window (paper Sec. 2.4) does not change that, but letting all
- * waves work on the same zone at the same time does.  With zone_bytes set, the
- * work is cut into items (zone, pair of logical waves, chunk of iterations); an
+ * waves work on the same zone at the same time does.  With zone_bytes or
+ * zone_of_window set, the work is cut into items (zone, pair of logical waves, chunk of iterations); an
  * item bins its chunk's line indices in LDS and reads only those inside its
  * zone.  Ticketed launches hand the items out zone-major, so the whole device
  * works on one zone, then on the next, however unevenly the individual waves
@@ -150,7 +150,8 @@ typedef struct {
  * because the hardware serves the oldest workgroups of a CU first the phases
  * then overlap widely.  This is the paper's idea -- keep what is accessed
  * together inside one locality domain -- transposed from space (a window per
- * group) to time (a window per phase).  Zones must be contiguous in the region.
+ * group) to time (a window per phase).  zone_bytes describes contiguous zones
+ * of equal size, zone_of_window any assignment of up to 64 windows to zones.
  */
 
 /*
