@@ -48,6 +48,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--max-region-gib", type=int, default=256)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
+    ap.add_argument("--no-zone-curve", action="store_true", help="skip the extra zone-by-zone curve")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this benchmark is a single-GPU measurement; --gpus must be 1 "
@@ -141,6 +142,32 @@ def main():
         "fill_gbps": round(max_gib * GiB / fill_s / 1e9, 1),
         "roofline": roofline,
     }
+
+    # Not part of the metric: the same reads zone by zone (the library's remedy for the two steps of the curve),
+    # with the zone map of this allocation probed first; checksums must equal those of the plain launches.
+    if not args.no_zone_curve and max_gib >= 128:
+        from paper_2405_11425_amd import zonemap
+        t0 = time.perf_counter()
+        whole = (max_gib // 32) * 32 * GiB
+        zone_of_window = zonemap.detect_zone_map(region, whole, n_cus)
+        zcurve, same = [], True
+        for cfg in configs:
+            if cfg.region_bytes < 128 * GiB or cfg.region_bytes > whole or cfg.region_bytes % (whole // 32) != 0:
+                continue
+            zm = zone_of_window[:cfg.region_bytes // (whole // 32)]
+            ids = {z: i for i, z in enumerate(dict.fromkeys(zm))}
+            zm = [ids[z] for z in zm]
+            call = lambda seed: rl.rand_read(region, cfg.line_bytes, cfg.n_reads, cfg.iters_per_wave, seed,
+                                             region_bytes=cfg.region_bytes, zone_of_window=zm)
+            call(1000)
+            res = [call(wl.READ_SEED + i) for i in range(5)]
+            same = same and res[0].checksum == records[cfg.name][0].checksum
+            ms = statistics.median(r.kernel_ms_event for r in res)
+            zcurve.append({"region_gib": cfg.region_bytes // GiB, "zones": len(ids),
+                           "gbps": round(cfg.bytes_read / ms / 1e6, 1)})
+        out["zone_by_zone"] = {"note": "extra, not in value: uniform reads ordered zone by zone (opts.zone_of_window)",
+                               "zone_of_window_8gib": zone_of_window, "curve": zcurve,
+                               "checksums_equal_plain": bool(same), "seconds": round(time.perf_counter() - t0, 1)}
 
     if not args.no_cpu_baseline:
         # CPU-baseline leg: the oracle as it stands, on one whole step (every sweep point), first timed seed.

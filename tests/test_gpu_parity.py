@@ -150,6 +150,23 @@ def test_chase_closed_cycle_over_pages(region, dist, n):
         assert got.final_line == (hops % n) * (stride // 128)
 
 
+def test_detected_zone_map_drives_the_phased_read(region):
+    """The quick zone probe returns a usable map (one id per window, ids numbered by first appearance), and a read
+    ordered by that map returns the checksum of the plain read."""
+    from paper_2405_11425_amd import zonemap
+    n_cus = len(rl.enumerate_cus())
+    R = (region.numel() // (32 * GiB)) * 32 * GiB
+    if R == 0:
+        pytest.skip("region too small for 32 windows of whole GiB")
+    zm = zonemap.detect_zone_map(region, R, n_cus)
+    assert len(zm) == 32 and zm[0] == 0 and max(zm) < 16
+    assert all(z <= max(zm[:i]) + 1 for i, z in enumerate(zm) if i)          # numbered by first appearance
+    W, I = 4096, 512
+    plain = rl.rand_read(region, 128, W * I, I, 21, region_bytes=R)
+    phased = rl.rand_read(region, 128, W * I, I, 21, region_bytes=R, zone_of_window=zm)
+    assert plain.checksum == phased.checksum == orc.checksum(R, 128, W, I, wl.FILL_SEED, 21, n_threads=ORACLE_THREADS)
+
+
 def test_calls_on_a_side_stream():
     """Every entry point works on the stream it is given (explicitly, or torch's current one) and is ordered
     after what that stream already holds."""
