@@ -48,7 +48,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--max-region-gib", type=int, default=256)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
-    ap.add_argument("--no-zone-curve", action="store_true", help="skip the extra zone-by-zone curve")
+    ap.add_argument("--plain-order", action="store_true",
+                    help="read every region in plain order (no zone probe, no zone-by-zone launches)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this benchmark is a single-GPU measurement; --gpus must be 1 "
@@ -82,10 +83,48 @@ def main():
     fill_s = time.perf_counter() - t0
     configs = wl.region_sweep(max_gib * GiB, n_cus)
 
+    def read(cfg, seed, zm=None):
+        kw = {"zone_of_window": zm} if zm is not None else {}
+        return rl.rand_read(region, cfg.line_bytes, cfg.n_reads, cfg.iters_per_wave, seed,
+                            lanes_per_line=cfg.lanes_per_line, region_bytes=cfg.region_bytes, **kw)
+
+    # Before the timed region (like the fill): regions that span several memory zones may be read zone by zone
+    # (opts.zone_of_window: same lines, same checksum, ordered so that the device works on one zone at a time).
+    # The zone map of this allocation is probed, both orders are timed on every such region, and the faster
+    # one is used for it from here on, warm-up included.
+    order = {cfg.name: None for cfg in configs}
+    zone_info = None
+    if not args.plain_order and max_gib >= 32:
+        from paper_2405_11425_amd import zonemap
+        t0 = time.perf_counter()
+        whole = (max_gib // 32) * 32 * GiB
+        win = whole // 32
+        zone_of_window = zonemap.detect_zone_map(region, whole, n_cus)
+        tried = []
+        for cfg in configs:
+            if cfg.region_bytes > whole or cfg.region_bytes % win != 0:
+                continue
+            zm = zone_of_window[:cfg.region_bytes // win]
+            ids = {z: i for i, z in enumerate(dict.fromkeys(zm))}
+            if len(ids) < 2:
+                continue
+            zm = [ids[z] for z in zm]
+            rate = {}
+            for name, m in (("plain", None), ("zone-by-zone", zm)):
+                read(cfg, 1000, m)
+                ms = statistics.median(read(cfg, 2000 + i, m).kernel_ms_event for i in range(3))
+                rate[name] = round(cfg.bytes_read / ms / 1e6, 1)
+            if rate["zone-by-zone"] > rate["plain"]:
+                order[cfg.name] = zm
+            tried.append({"region_gib": cfg.region_bytes // GiB, "zones": len(ids), "gbps_plain": rate["plain"],
+                          "gbps_zone_by_zone": rate["zone-by-zone"],
+                          "chosen": "zone-by-zone" if order[cfg.name] is not None else "plain"})
+        zone_info = {"zone_of_window_8gib": zone_of_window, "regions_spanning_zones": tried,
+                     "seconds_before_timing": round(time.perf_counter() - t0, 2)}
+
     def step(seed, record=None):
         for cfg in configs:
-            r = rl.rand_read(region, cfg.line_bytes, cfg.n_reads, cfg.iters_per_wave, seed,
-                             lanes_per_line=cfg.lanes_per_line, region_bytes=cfg.region_bytes)
+            r = read(cfg, seed, order[cfg.name])
             if record is not None:
                 record.setdefault(cfg.name, []).append(r)
 
@@ -102,12 +141,15 @@ def main():
     bytes_per_step = sum(c.bytes_read for c in configs)
     value = bytes_per_step * args.steps / wall_s / 1e9
     curve = []
-    all_ms = []
+    all_ms = []     # launches of the dominant kernel (the plain read kernel: most launches, most of the time)
     for cfg in configs:
         ms = [r.kernel_ms_event for r in records[cfg.name]]
-        all_ms += ms
+        if order[cfg.name] is None:
+            all_ms += ms
         med = statistics.median(ms)
-        curve.append({"region_gib": cfg.region_bytes // GiB, "gbps": round(cfg.bytes_read / med / 1e6, 1),
+        curve.append({"region_gib": cfg.region_bytes // GiB,
+                      "order": "plain" if order[cfg.name] is None else "zone-by-zone",
+                      "gbps": round(cfg.bytes_read / med / 1e6, 1),
                       "gbps_min": round(cfg.bytes_read / max(ms) / 1e6, 1),
                       "gbps_max": round(cfg.bytes_read / min(ms) / 1e6, 1),
                       "pct_of_hbm_peak": round(cfg.bytes_read / med / 1e6 / HBM_PEAK_GBPS * 100, 1),
@@ -120,7 +162,9 @@ def main():
                 "frac": round(achieved / HBM_PEAK_GBPS, 4),
                 "traffic": read_traffic_file(os.path.join(ROOT, "profiles", "rand_read_region_sweep_pmc.txt")),
                 "bytes_per_launch": bytes_per_launch, "avg_launch_ms": round(avg_ms, 4),
-                "launches_timed": len(all_ms)}
+                "launches_timed": len(all_ms),
+                "note": "launches in plain order only; regions read zone by zone run rand_read_phased_kernel "
+                        "(see curve[].order)"}
 
     out = {
         "metric": "random-line read GB/s vs region size (1-256 GiB); % of 8 TB/s HBM peak",
@@ -129,7 +173,9 @@ def main():
         "vs_baseline": None, "dtype": "u32", "data": "synthetic",
         "config": {"workload": "region-size sweep (configs[1]): per region size one launch with all "
                                f"{n_cus * wl.WAVES_PER_CU} wave slots occupied, each 32-lane logical wave reading "
-                               "4096 uniformly random 128-B lines; regions are prefixes of one filled allocation",
+                               "4096 uniformly random 128-B lines; regions are prefixes of one filled allocation; "
+                               "regions that span several memory zones are read in whichever order was faster "
+                               "before the timed steps, plain or zone by zone (same lines, same checksums)",
                    "regions_gib": [c.region_bytes // GiB for c in configs], "line_bytes": 128,
                    "lanes_per_line": 32, "logical_waves": configs[0].logical_waves,
                    "iters_per_wave": configs[0].iters_per_wave, "reads_per_launch": configs[0].n_reads,
@@ -143,31 +189,8 @@ def main():
         "roofline": roofline,
     }
 
-    # Not part of the metric: the same reads zone by zone (the library's remedy for the two steps of the curve),
-    # with the zone map of this allocation probed first; checksums must equal those of the plain launches.
-    if not args.no_zone_curve and max_gib >= 128:
-        from paper_2405_11425_amd import zonemap
-        t0 = time.perf_counter()
-        whole = (max_gib // 32) * 32 * GiB
-        zone_of_window = zonemap.detect_zone_map(region, whole, n_cus)
-        zcurve, same = [], True
-        for cfg in configs:
-            if cfg.region_bytes < 128 * GiB or cfg.region_bytes > whole or cfg.region_bytes % (whole // 32) != 0:
-                continue
-            zm = zone_of_window[:cfg.region_bytes // (whole // 32)]
-            ids = {z: i for i, z in enumerate(dict.fromkeys(zm))}
-            zm = [ids[z] for z in zm]
-            call = lambda seed: rl.rand_read(region, cfg.line_bytes, cfg.n_reads, cfg.iters_per_wave, seed,
-                                             region_bytes=cfg.region_bytes, zone_of_window=zm)
-            call(1000)
-            res = [call(wl.READ_SEED + i) for i in range(5)]
-            same = same and res[0].checksum == records[cfg.name][0].checksum
-            ms = statistics.median(r.kernel_ms_event for r in res)
-            zcurve.append({"region_gib": cfg.region_bytes // GiB, "zones": len(ids),
-                           "gbps": round(cfg.bytes_read / ms / 1e6, 1)})
-        out["zone_by_zone"] = {"note": "extra, not in value: uniform reads ordered zone by zone (opts.zone_of_window)",
-                               "zone_of_window_8gib": zone_of_window, "curve": zcurve,
-                               "checksums_equal_plain": bool(same), "seconds": round(time.perf_counter() - t0, 1)}
+    if zone_info is not None:
+        out["zone_order"] = zone_info
 
     if not args.no_cpu_baseline:
         # CPU-baseline leg: the oracle as it stands, on one whole step (every sweep point), first timed seed.

@@ -115,7 +115,7 @@ typedef struct {
     uint32_t bcast;          /* RR_BCAST_*                                                         */
     uint32_t nontemporal;    /* RR_NT_*                                                            */
     uint32_t chunk_iters;    /* iterations of a logical wave executed per ticket / hardware wave: a
-                                multiple of 64; 0 = default (flat: all of them; ticketed: 512)     */
+                                multiple of 64; 0 = default (flat: all of them; ticketed: 1024)    */
     uint32_t reserved;       /* must be 0                                                          */
     uint64_t first_wave;     /* id of the first logical wave (default 0); multiple of n_groups     */
     uint64_t zone_bytes;     /* 0 = off.  Otherwise the region is cut into zones of this many bytes

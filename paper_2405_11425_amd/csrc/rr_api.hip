@@ -4,6 +4,8 @@
 // rr_phased_kernel.hpp and rr_update_kernel.hpp and are instantiated in the rr_inst_*.hip files.
 #include <algorithm>
 #include <cstring>
+#include <map>
+#include <utility>
 #include <vector>
 
 #include "rr_host.hpp"
@@ -170,6 +172,22 @@ int make_plan(const void *region, uint64_t region_bytes, uint32_t line_bytes, ui
     return RR_OK;
 }
 
+// Workgroups of `block` threads of this kernel that one CU holds at a time, as the runtime computes it from the
+// kernel's registers and LDS (the 8-per-SIMD wave limit if it cannot say).  Cached per (kernel, block).
+u32 resident_blocks_per_cu(kernel_handle kernel, u32 block) {
+    static std::map<std::pair<kernel_handle, u32>, u32> cache;  // guarded by g_mutex (run_plan holds it)
+    auto key = std::make_pair(kernel, block);
+    auto it = cache.find(key);
+    if (it != cache.end()) return it->second;
+    int n = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel, (int)block, 0) != hipSuccess || n <= 0) {
+        (void)hipGetLastError();
+        n = (int)(32 / (block / 64));
+    }
+    cache[key] = (u32)n;
+    return (u32)n;
+}
+
 // Lookup tables of one call: CU key -> group and dense id, group -> window, group -> its CUs, and each
 // CU's share of its group's units.  Built in the pinned staging copy and uploaded only if they differ
 // from what the device already holds.
@@ -259,9 +277,9 @@ int run_plan(const Plan &pl, const void *region, uint32_t iters, const rr_window
     p.quota = quota;
     p.iters = iters;
     // flat launches default to one hardware wave per whole logical wave (pair); ticketed ones to
-    // chunks of 512 iterations so that resident waves finish together
+    // chunks of 1024 iterations (shorter ones pay for draining the load ring at every chunk end)
     const bool phased = pl.n_zones > 0;  // its chunks are what one pass through the LDS lists holds
-    u32 chunk = phased ? kPhaseChunk : pl.chunk_iters ? pl.chunk_iters : (pl.mode == RR_MODE_TICKET ? 512u : iters);
+    u32 chunk = phased ? kPhaseChunk : pl.chunk_iters ? pl.chunk_iters : (pl.mode == RR_MODE_TICKET ? 1024u : iters);
     if (chunk > iters) chunk = iters;
     p.chunk_iters = chunk;
     p.chunks_per_wave = (iters + chunk - 1) / chunk;
@@ -280,12 +298,14 @@ int run_plan(const Plan &pl, const void *region, uint32_t iters, const rr_window
     p.phase_ticks = (opts && pl.n_zones) ? (u64 *)opts->phase_ticks : nullptr;
 
     const u32 waves_per_block = pl.block / 64;
-    // a CU holds at most 32 waves (8 per SIMD); workgroups beyond what really fits queue up,
-    // find every share claimed and leave at once
-    const u32 blocks_per_cu = 32 / waves_per_block;
     u64 grid;
     if (p.ticket_mode) {
-        grid = pl.grid_blocks ? pl.grid_blocks : (u64)blocks_per_cu * n_cus * (pl.pinned ? 64u : 1u);
+        // As many workgroups as are resident at once: work-stealing finishes the job whatever the placement, and
+        // every workgroup beyond that only starts when the work is done, scans all shares and leaves -- which
+        // lengthens the kernel (measured 1-2 %).  Pinned runs need many more, most land on CUs that take no part.
+        u32 blocks_per_cu = resident_blocks_per_cu(pl.kernel, pl.block);
+        if (pl.pinned) blocks_per_cu = (32 / waves_per_block) * 64u;
+        grid = pl.grid_blocks ? pl.grid_blocks : (u64)blocks_per_cu * n_cus;
     } else {
         const u64 hw_waves = (pl.W + lpw - 1) / lpw * (phased ? 1u : p.chunks_per_wave);
         grid = (hw_waves + waves_per_block - 1) / waves_per_block;

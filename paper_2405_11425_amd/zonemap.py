@@ -18,8 +18,10 @@ from . import workloads as wl
 
 
 def detect_zone_map(region, region_bytes: int, n_cus: int, n_windows: int = 32, reps: int = 3,
-                    tolerance: float = 0.02, max_zones: int = 16) -> List[int]:
-    """zone_of_window[n_windows] for the first region_bytes of `region` (ids in order of first appearance)."""
+                    tolerance: float = 0.02, max_zones: int = 16, unroll: int = 8) -> List[int]:
+    """zone_of_window[n_windows] for the first region_bytes of `region` (ids in order of first appearance).
+    The probe launches use the ring-of-8 build of the read kernel by default, so that in a kernel trace they
+    stay apart from a caller's own launches of the default (ring of 16) kernel."""
     if region_bytes % (n_windows * 128) != 0:
         raise ValueError("region_bytes must be a multiple of n_windows lines")
     waves = wl.resident_logical_waves(n_cus)
@@ -28,7 +30,8 @@ def detect_zone_map(region, region_bytes: int, n_cus: int, n_windows: int = 32, 
 
     def pair_rate(a: int, b: int) -> float:
         wm = rl.WindowMap(n_windows, parity, np.array([a, b], np.uint16))
-        call = lambda seed: rl.rand_read(region, 128, waves * iters, iters, seed, wm, region_bytes=region_bytes)
+        call = lambda seed: rl.rand_read(region, 128, waves * iters, iters, seed, wm, region_bytes=region_bytes,
+                                         unroll=unroll)
         call(1000)
         ms = statistics.median(call(wl.READ_SEED + i).kernel_ms_event for i in range(reps))
         return waves * iters * 128 / ms / 1e6
