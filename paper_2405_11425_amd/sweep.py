@@ -268,7 +268,7 @@ class Runner:
                 M[a, b] = M[b, a] = row["gbps"]
             print(f"# zones row {a + 1}/{n_w} done, {time.perf_counter() - t0:.1f} s", file=sys.stderr, flush=True)
         # related windows are the FAST pairs here, so cluster on the reciprocal
-        group, order, thr = rl.groups_from_heatmap(1.0 / M, None, self.args.min_gap / 5)
+        group, order, thr = rl.groups_from_heatmap(1.0 / M, None, 0.002)   # the two modes lie only 3-4 % apart
         zones = [[int(w) for w in np.flatnonzero(group == g)] for g in range(int(group.max()) + 1)]
         same = [M[a, b] for a in range(n_w) for b in range(a + 1, n_w) if group[a] == group[b]]
         cross = [M[a, b] for a in range(n_w) for b in range(a + 1, n_w) if group[a] != group[b]]
