@@ -4,7 +4,8 @@ measured point to a JSONL file (points already present are skipped, so a run can
     python -m paper_2405_11425_amd.sweep region  [--out results.jsonl] [--reps 5]
     python -m paper_2405_11425_amd.sweep lines | windows | probe | stream | zones | groups | latency | pages | pieces | updates | calib | all
 
-  region   throughput vs region size, uniform random 128-byte lines        (paper Sec. 2.1, Fig. 1)
+  region   throughput vs region size, uniform random 128-byte lines, in plain order and (regions spanning several
+           memory zones) zone by zone                                   (paper Sec. 2.1, Fig. 1; Sec. 2.4, Fig. 5)
   lines    32 x {4,8,16} B and 64 x 4 B lines at 128 GiB and the largest region (Sec. 2.1, text)
   windows  per-CU random windows vs XCD-aware windows, 1/2, 1/4, 1/8           (Sec. 2.1 / 2.4, Fig. 1 / 5)
   probe    all pairs over 64 sampled CUs + each alone, heatmap and inferred groups (Sec. 2.2, Fig. 2 / 3)
@@ -126,10 +127,30 @@ class Runner:
 
     # ------------------------------------------------------------------ experiments
     def region_sweep(self):
-        for cfg in self.wl.region_sweep(self.max_gib * self.wl.GiB, len(self.cus)):
+        wl = self.wl
+        configs = wl.region_sweep(self.max_gib * wl.GiB, len(self.cus))
+        for cfg in configs:
             key = f"region/{cfg.name}/{json.dumps(self.launch, sort_keys=True)}"
             if key not in self.seen:
                 self.emit(key, {"experiment": "region", "scheme": "uniform", **self.timed_read(cfg), **self.meta})
+        # the same reads ordered zone by zone, for the regions that span several memory zones (the flat curve of
+        # Fig. 5, reached here by a window per phase instead of a window per group)
+        whole = (self.max_gib // 32) * 32 * wl.GiB
+        big = [c for c in configs if whole and c.region_bytes <= whole and c.region_bytes % (whole // 32) == 0
+               and f"region-zoned/{c.name}" not in self.seen]
+        if not big:
+            return
+        from . import zonemap
+        zone_of_window = zonemap.detect_zone_map(self.region, whole, len(self.cus))
+        for cfg in big:
+            zm = zone_of_window[:cfg.region_bytes // (whole // 32)]
+            ids = {z: i for i, z in enumerate(dict.fromkeys(zm))}
+            if len(ids) < 2:
+                continue
+            zm = [ids[z] for z in zm]
+            self.emit(f"region-zoned/{cfg.name}", {"experiment": "region", "scheme": "uniform, zone by zone",
+                                                   "zones": len(ids), "zone_of_window": zm,
+                                                   **self.timed_read(cfg, zone_of_window=zm), **self.meta})
 
     def line_sweep(self):
         sizes = sorted({min(128, self.max_gib), self.max_gib})
