@@ -398,6 +398,8 @@ def test_repeatable(region):
     (5 << 22, 512, 32, 31, 513, 1 << 22),           # 16-byte lanes, 5 zones
     (1 << 26, 256, 64, 33, 700, 1 << 25),           # 64-lane lines
     (1 << 26, 512, 64, 9, 70, 1 << 26),             # a single zone
+    (1 << 26, 128, 32, 10, 2100, 1 << 26),          # a single zone and full chunks: every list filled to capacity
+    (1 << 26, 256, 64, 5, 2048, 1 << 26),           # the same with 64-lane lines
     (1 << 28, 128, 32, 256, 4096, 96 << 20),        # the small reference configuration in 3 zones
 ])
 def test_zone_phased_reads_same_checksum(region, R, B, lanes, W, I, zone):
