@@ -95,32 +95,36 @@ def main():
     order = {cfg.name: None for cfg in configs}
     zone_info = None
     if not args.plain_order and max_gib >= 32:
-        from paper_2405_11425_amd import zonemap
-        t0 = time.perf_counter()
-        whole = (max_gib // 32) * 32 * GiB
-        win = whole // 32
-        zone_of_window = zonemap.detect_zone_map(region, whole, n_cus)
-        tried = []
-        for cfg in configs:
-            if cfg.region_bytes > whole or cfg.region_bytes % win != 0:
-                continue
-            zm = zone_of_window[:cfg.region_bytes // win]
-            ids = {z: i for i, z in enumerate(dict.fromkeys(zm))}
-            if len(ids) < 2:
-                continue
-            zm = [ids[z] for z in zm]
-            rate = {}
-            for name, m in (("plain", None), ("zone-by-zone", zm)):
-                read(cfg, 1000, m)
-                ms = statistics.median(read(cfg, 2000 + i, m).kernel_ms_event for i in range(3))
-                rate[name] = round(cfg.bytes_read / ms / 1e6, 1)
-            if rate["zone-by-zone"] > rate["plain"]:
-                order[cfg.name] = zm
-            tried.append({"region_gib": cfg.region_bytes // GiB, "zones": len(ids), "gbps_plain": rate["plain"],
-                          "gbps_zone_by_zone": rate["zone-by-zone"],
-                          "chosen": "zone-by-zone" if order[cfg.name] is not None else "plain"})
-        zone_info = {"zone_of_window_8gib": zone_of_window, "regions_spanning_zones": tried,
-                     "seconds_before_timing": round(time.perf_counter() - t0, 2)}
+        try:
+            from paper_2405_11425_amd import zonemap
+            t0 = time.perf_counter()
+            whole = (max_gib // 32) * 32 * GiB
+            win = whole // 32
+            zone_of_window = zonemap.detect_zone_map(region, whole, n_cus)
+            tried = []
+            for cfg in configs:
+                if cfg.region_bytes > whole or cfg.region_bytes % win != 0:
+                    continue
+                zm = zone_of_window[:cfg.region_bytes // win]
+                ids = {z: i for i, z in enumerate(dict.fromkeys(zm))}
+                if len(ids) < 2:
+                    continue
+                zm = [ids[z] for z in zm]
+                rate = {}
+                for name, m in (("plain", None), ("zone-by-zone", zm)):
+                    read(cfg, 1000, m)
+                    ms = statistics.median(read(cfg, 2000 + i, m).kernel_ms_event for i in range(3))
+                    rate[name] = round(cfg.bytes_read / ms / 1e6, 1)
+                if rate["zone-by-zone"] > rate["plain"]:
+                    order[cfg.name] = zm
+                tried.append({"region_gib": cfg.region_bytes // GiB, "zones": len(ids), "gbps_plain": rate["plain"],
+                              "gbps_zone_by_zone": rate["zone-by-zone"],
+                              "chosen": "zone-by-zone" if order[cfg.name] is not None else "plain"})
+            zone_info = {"zone_of_window_8gib": zone_of_window, "regions_spanning_zones": tried,
+                         "seconds_before_timing": round(time.perf_counter() - t0, 2)}
+        except rl.RandlineError as e:   # the sweep itself does not depend on this: go on in plain order, and say so
+            order = {cfg.name: None for cfg in configs}
+            zone_info = {"error": str(e)}
 
     def step(seed, record=None):
         for cfg in configs:
