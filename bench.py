@@ -209,6 +209,10 @@ def main():
             t_all += time.perf_counter() - t0
             reads_all += cfg.n_reads
             match = match and c_all == records[cfg.name][0].checksum
+        # the last timed step too (not timed: the rate above is from the first pass only)
+        last_seed = wl.READ_SEED + args.steps - 1
+        match_last = all(orc.checksum(c.region_bytes, c.line_bytes, c.logical_waves, c.iters_per_wave, c.fill_seed,
+                                      last_seed, n_threads=cores) == records[c.name][-1].checksum for c in picks)
         cfg = configs[-1]
         sample_waves = cfg.logical_waves // 4           # single thread: a quarter of one point's waves
         t0 = time.perf_counter()
@@ -235,7 +239,9 @@ def main():
             "materialised_gbps": round(mat_waves * 1024 * cfg.line_bytes / t_mat / 1e9, 3),
             "materialised_sample": f"{mat_waves} logical waves x 1024 reads from a {mat_bytes // GiB} GiB host buffer, "
                                    f"{cores} threads, {t_mat:.2f} s",
-            "checksum_matches_gpu": bool(match),
+            "checksum_matches_gpu": bool(match and match_last),
+            "checksums_compared": f"all {len(picks)} region sizes, first timed step (seed {wl.READ_SEED}) and last "
+                                  f"(seed {last_seed})",
         }
     print(json.dumps(out))
     return 0
