@@ -91,6 +91,7 @@ class Runner:
         rl.fill(self.region, wl.FILL_SEED)
         self.fill_s = time.perf_counter() - t0
         self.seen = _rows(args.out)
+        self._zone_of_window = None
         self.launch = {k: v for k, v in dict(unroll=args.unroll, bcast=args.bcast, nontemporal=args.nt,
                                              block_threads=args.block).items() if v}
         self.meta = {"device": torch.cuda.get_device_name(0), "environment": env, "n_cus": len(self.cus),
@@ -126,6 +127,20 @@ class Runner:
                 "checksum_first_seed": res[0].checksum, "waves_run": res[0].waves_run, "launches": res[0].launches}
 
     # ------------------------------------------------------------------ experiments
+    def zone_map_for(self, region_bytes):
+        """(zones spanned, zone_of_window for the first region_bytes) from one probe of the whole allocation, in 32
+        windows; (1, None) when the region lies in one zone or does not end on a window boundary."""
+        wl = self.wl
+        whole = (self.max_gib // 32) * 32 * wl.GiB
+        if not whole or region_bytes > whole or region_bytes % (whole // 32) != 0:
+            return 1, None
+        if self._zone_of_window is None:
+            from . import zonemap
+            self._zone_of_window = zonemap.detect_zone_map(self.region, whole, len(self.cus))
+        zm = self._zone_of_window[:region_bytes // (whole // 32)]
+        ids = {z: i for i, z in enumerate(dict.fromkeys(zm))}
+        return len(ids), [ids[z] for z in zm]
+
     def region_sweep(self):
         wl = self.wl
         configs = wl.region_sweep(self.max_gib * wl.GiB, len(self.cus))
@@ -135,22 +150,14 @@ class Runner:
                 self.emit(key, {"experiment": "region", "scheme": "uniform", **self.timed_read(cfg), **self.meta})
         # the same reads ordered zone by zone, for the regions that span several memory zones (the flat curve of
         # Fig. 5, reached here by a window per phase instead of a window per group)
-        whole = (self.max_gib // 32) * 32 * wl.GiB
-        big = [c for c in configs if whole and c.region_bytes <= whole and c.region_bytes % (whole // 32) == 0
-               and f"region-zoned/{c.name}" not in self.seen]
-        if not big:
-            return
-        from . import zonemap
-        zone_of_window = zonemap.detect_zone_map(self.region, whole, len(self.cus))
-        for cfg in big:
-            zm = zone_of_window[:cfg.region_bytes // (whole // 32)]
-            ids = {z: i for i, z in enumerate(dict.fromkeys(zm))}
-            if len(ids) < 2:
+        for cfg in configs:
+            key = f"region-zoned/{cfg.name}"
+            if key in self.seen:
                 continue
-            zm = [ids[z] for z in zm]
-            self.emit(f"region-zoned/{cfg.name}", {"experiment": "region", "scheme": "uniform, zone by zone",
-                                                   "zones": len(ids), "zone_of_window": zm,
-                                                   **self.timed_read(cfg, zone_of_window=zm), **self.meta})
+            n_zones, zm = self.zone_map_for(cfg.region_bytes)
+            if n_zones >= 2:
+                self.emit(key, {"experiment": "region", "scheme": "uniform, zone by zone", "zones": n_zones,
+                                "zone_of_window": zm, **self.timed_read(cfg, zone_of_window=zm), **self.meta})
 
     def line_sweep(self):
         sizes = sorted({min(128, self.max_gib), self.max_gib})
@@ -158,7 +165,13 @@ class Runner:
             for cfg in self.wl.line_width_sweep(gib * self.wl.GiB):
                 key = f"lines/{cfg.name}/{json.dumps(self.launch, sort_keys=True)}"
                 if key not in self.seen:
-                    self.emit(key, {"experiment": "lines", **self.timed_read(cfg, reps=3), **self.meta})
+                    self.emit(key, {"experiment": "lines", "order": "plain", **self.timed_read(cfg, reps=3), **self.meta})
+                key = f"lines-zoned/{cfg.name}"
+                if key not in self.seen:
+                    n_zones, zm = self.zone_map_for(cfg.region_bytes)
+                    if n_zones >= 2:
+                        self.emit(key, {"experiment": "lines", "order": "zone by zone", "zones": n_zones,
+                                        **self.timed_read(cfg, reps=3, zone_of_window=zm), **self.meta})
 
     def window_sweep(self):
         wl, rl = self.wl, self.rl
