@@ -6,7 +6,8 @@ measured point to a JSONL file (points already present are skipped, so a run can
 
   region   throughput vs region size, uniform random 128-byte lines, in plain order and (regions spanning several
            memory zones) zone by zone                                   (paper Sec. 2.1, Fig. 1; Sec. 2.4, Fig. 5)
-  lines    32 x {4,8,16} B and 64 x 4 B lines at 128 GiB and the largest region (Sec. 2.1, text)
+  lines    32 x {4,8,16} B and 64 x 4 B lines at 128 GiB and the largest region, 2^30 reads per launch, in plain
+           order and zone by zone                                                  (Sec. 2.1, text)
   windows  per-CU random windows vs XCD-aware windows, 1/2, 1/4, 1/8           (Sec. 2.1 / 2.4, Fig. 1 / 5)
   probe    all pairs over 64 sampled CUs + each alone, heatmap and inferred groups (Sec. 2.2, Fig. 2 / 3)
   stream   sequential read and copy ceilings                                 (Sec. 2.1, remark on sequential reads)
@@ -158,6 +159,18 @@ class Runner:
             if n_zones >= 2:
                 self.emit(key, {"experiment": "region", "scheme": "uniform, zone by zone", "zones": n_zones,
                                 "zone_of_window": zm, **self.timed_read(cfg, zone_of_window=zm), **self.meta})
+        # and with 16 times as many logical waves per launch (2^30 reads): start, end and zone changes of a launch
+        # then weigh 16 times less
+        for cfg in configs:
+            long_cfg = wl.ReadConfig(cfg.name + "-16x", cfg.region_bytes, cfg.line_bytes, cfg.lanes_per_line,
+                                     16 * cfg.logical_waves, cfg.iters_per_wave)
+            n_zones, zm = self.zone_map_for(cfg.region_bytes)
+            for scheme, kw in (("uniform", {}), ("uniform, zone by zone", {"zone_of_window": zm})):
+                key = f"region-long/{scheme}/{cfg.name}"
+                if key in self.seen or (kw and n_zones < 2):
+                    continue
+                self.emit(key, {"experiment": "region", "scheme": scheme, "launch_size": "16x", "zones": n_zones,
+                                **self.timed_read(long_cfg, reps=3, **kw), **self.meta})
 
     def line_sweep(self):
         sizes = sorted({min(128, self.max_gib), self.max_gib})
