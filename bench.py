@@ -145,7 +145,7 @@ def main():
     bytes_per_step = sum(c.bytes_read for c in configs)
     value = bytes_per_step * args.steps / wall_s / 1e9
     curve = []
-    all_ms = []     # launches of the dominant kernel (the plain read kernel: most launches, most of the time)
+    all_ms = []     # launches of the dominant kernel (the flat read kernel: most launches, most of the time)
     for cfg in configs:
         ms = [r.kernel_ms_event for r in records[cfg.name]]
         if order[cfg.name] is None:
@@ -161,7 +161,7 @@ def main():
     bytes_per_launch = configs[0].bytes_read
     avg_ms = sum(all_ms) / len(all_ms)
     achieved = bytes_per_launch / avg_ms / 1e6
-    roofline = {"bound": "hbm", "kernel": "rand_read_kernel<32 lanes, 1 dword, ring 16, DPP broadcast, non-temporal>",
+    roofline = {"bound": "hbm", "kernel": "rand_read_flat_kernel<32 lanes, 1 dword, ring 16, DPP broadcast, non-temporal>",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBPS, 4),
                 "traffic": read_traffic_file(os.path.join(ROOT, "profiles", "rand_read_region_sweep_pmc.txt")),

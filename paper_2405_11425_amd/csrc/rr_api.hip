@@ -324,10 +324,16 @@ int run_plan(const Plan &pl, const void *region, uint32_t iters, const rr_window
     }
     st.cells_clean = false;
     const int max_launches = p.ticket_mode ? 32 : 1;
+    // the plain flat launch has a kernel of its own (fewer registers, 8 resident waves per SIMD instead of 7)
+    kernel_handle kernel = pl.kernel;
+    if (!p.ticket_mode && !phased && !wm && !p.locate) {
+        kernel_handle flat = find_flat_kernel(pl.lanes, pl.wdw, pl.unroll, pl.bcast, pl.nt);
+        if (flat) kernel = flat;
+    }
     void *args[] = {(void *)&p};
     for (int launch = 0;; ++launch) {
         HIP_TRY(hipEventRecord(st.ev0, stream));
-        HIP_TRY(hipLaunchKernel(pl.kernel, dim3((u32)grid), dim3(pl.block), args, 0, stream));
+        HIP_TRY(hipLaunchKernel(kernel, dim3((u32)grid), dim3(pl.block), args, 0, stream));
         HIP_TRY(hipEventRecord(st.ev1, stream));
         rc = finish_and_wait(st, n_cus, (u32)tickets_per_unit, p.ticket_mode, stream);
         if (rc != RR_OK) return rc;

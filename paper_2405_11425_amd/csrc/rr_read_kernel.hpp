@@ -269,6 +269,41 @@ __global__ void __launch_bounds__(256) rand_read_kernel(const ReadParams p) {
     }
 }
 
+// The flat launch without a window map, on its own: no tickets, no tables, no CU lookup.  It needs 34 scalar and
+// 36-78 vector registers where the general kernel needs 85 and 64+, so that a SIMD really holds 8 waves of it (the
+// general kernel: 7, the scalar registers being the limit) and all 8192 hardware waves of the sweep's launches are
+// resident from the start.  Ticket = launch index = unit * chunks_per_wave + chunk.
+template <int LANES, int WDW, int U, int BC, int NT>
+__global__ void __launch_bounds__(256) rand_read_flat_kernel(const ReadParams p) {
+    constexpr u32 LPW = 64 / LANES;
+    const u32 lane = threadIdx.x & 63;
+    const u32 half = (LANES == 32) ? (lane >> 5) : 0;
+    const u32 launch_index = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    const u32 cpw = p.chunks_per_wave;
+    const u32 unit = launch_index / cpw;
+    const u32 chunk = launch_index - unit * cpw;
+    const u64 j0 = (u64)unit * LPW;  // the lower logical wave of the unit
+    if (j0 >= p.quota) return;
+    const u64 t0 = clock_ticks();
+    u64 j = j0 + half;
+    const bool valid = j < p.quota;  // odd quota: the upper half shadows the lower one
+    if (!valid) j = j0;
+    const u64 w = p.first_wave + j;
+    const u64 wave_seed = mix64(p.read_seed + (w + 1) * kGamma);
+    const u32 it0 = chunk * p.chunk_iters;
+    const u32 n_it = min(p.chunk_iters, p.iters - it0);
+    const u64 part = read_logical_wave<LANES, WDW, U, BC, NT>(p.region, wave_seed, 0u, it0, n_it, p.log2_line, p.red, lane);
+    const u64 total = wave_sum(valid ? part : 0);
+    const u64 t1 = clock_ticks();
+    if (lane == 0) {
+        Cell *c = &p.scratch->cells[launch_index & (kNumCells - 1)];
+        atomicAdd(&c->sum, total);
+        atomicMin(&c->t_min, t0);
+        atomicMax(&c->t_max, t1);
+        atomicAdd(&c->waves, 1u);
+    }
+}
+
 // Each (LANES, WDW) family lives in its own translation unit and exposes a
 // finder that returns the kernel's host-side handle for (unroll, bcast,
 // nontemporal), or null if that combination is not built.
@@ -278,5 +313,7 @@ kernel_handle find_read_kernel_32_2(u32 unroll, u32 bcast, u32 nt);
 kernel_handle find_read_kernel_32_4(u32 unroll, u32 bcast, u32 nt);
 kernel_handle find_read_kernel_64_1(u32 unroll, u32 bcast, u32 nt);
 kernel_handle find_read_kernel_64_2(u32 unroll, u32 bcast, u32 nt);
+// The flat-only kernel is built for the DPP broadcast and each family's default ring depth; null otherwise.
+kernel_handle find_flat_kernel(u32 lanes, u32 wdw, u32 unroll, u32 bcast, u32 nt);
 
 }  // namespace rr
