@@ -26,6 +26,34 @@ def test_library_exports_every_declared_symbol():
     assert declared == set(rl.binding.EXPORTS)
 
 
+def test_header_is_plain_c(tmp_path):
+    """The boundary is a C ABI: the header must compile as C99 (and as C++) on its own, with no HIP or torch types, and
+    the structs the binding mirrors must have the sizes and field offsets the C compiler gives them."""
+    import subprocess
+    inc = os.path.join(os.path.dirname(os.path.abspath(__file__)), "..", "include")
+    b = rl.binding
+    mirrors = {"rr_launch_opts_t": b._Opts, "rr_result_t": b._Result, "rr_window_map_t": b._WindowMap,
+               "rr_chase_result_t": b._ChaseResult}
+    prints = []
+    for cname, mirror in mirrors.items():
+        prints.append(f'printf("%zu\\n", sizeof({cname}));')
+        prints += [f'printf("%zu\\n", offsetof({cname}, {field}));' for field, _ in mirror._fields_]
+    src = tmp_path / "abi.c"
+    src.write_text('#include "randline.h"\n#include <stddef.h>\n#include <stdio.h>\nint main(void) {\n'
+                   + "\n".join(prints) + "\nreturn RR_OK; }\n")
+    exe = tmp_path / "abi"
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", inc, "-o", str(exe), str(src)],
+                   check=True)
+    subprocess.run(["g++", "-std=c++11", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", inc, "-fsyntax-only", "-x", "c++",
+                    str(src)], check=True)
+    got = [int(x) for x in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()]
+    want = []
+    for mirror in mirrors.values():
+        want.append(C.sizeof(mirror))
+        want += [getattr(mirror, field).offset for field, _ in mirror._fields_]
+    assert got == want
+
+
 def test_strerror_and_codes():
     L = rl.lib()
     assert L.rr_strerror(0) == b"success"
