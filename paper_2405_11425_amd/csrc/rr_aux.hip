@@ -1,5 +1,6 @@
 // The streaming and latency companions of the random read: fill, sequential read, plain copy and
 // the dependent-load walk, with their entry points.
+#include <algorithm>
 #include <cstring>
 
 #include "rr_host.hpp"
@@ -27,27 +28,52 @@ __global__ void __launch_bounds__(256) fill_kernel(u64x2 *out, u64 n_pairs, u64 
 // Streaming counterpart of the random read: every 32-bit word of the region is
 // read once (the sequential reads the paper expects to be faster than random
 // lines, Sec. 2.1).  Each wave owns contiguous 8 KiB chunks (eight 16-byte loads
-// per lane in flight, consecutive lanes on consecutive addresses), chunks dealt
-// round-robin to the waves -- measured 3 % faster than a plain grid-stride loop;
-// what does not fill a chunk is read grid-stride.  Same checksum convention:
+// per lane in flight, consecutive lanes on consecutive addresses) -- measured
+// 3 % faster than a plain grid-stride loop; what does not fill a chunk is read
+// grid-stride.  Same checksum convention:
 // wrapping 64-bit sum of zero-extended words, one atomic per wave.
-__global__ void __launch_bounds__(256) seq_read_kernel(const u32x4 *src, u64 n_vec, Scratch *s) {
+__global__ void __launch_bounds__(256) seq_read_kernel(const u32x4 *src, u64 n_vec, Scratch *s, u32 block_chunks) {
     typedef const u32x4 __attribute__((address_space(1))) *gptr;
     constexpr u32 kLoads = 8;
     gptr g = (gptr)(u64)src;
     const u32 lane = threadIdx.x & 63;
     const u64 wave = ((u64)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
-    const u64 n_waves = ((u64)gridDim.x * blockDim.x) >> 6;
     const u64 n_chunks = n_vec / (64 * kLoads);
     const u64 t0 = clock_ticks();
     Acc acc{0u, 0u};
-    for (u64 c = wave; c < n_chunks; c += n_waves) {
-        const u64 base = c * (64 * kLoads) + lane;
-        u32x4 v[kLoads];
+    if (block_chunks == 0) {
+        // small regions: chunks dealt round-robin to the waves, no counters
+        const u64 n_waves = ((u64)gridDim.x * blockDim.x) >> 6;
+        for (u64 c = wave; c < n_chunks; c += n_waves) {
+            const u64 base = c * (64 * kLoads) + lane;
+            u32x4 v[kLoads];
 #pragma unroll
-        for (u32 k = 0; k < kLoads; ++k) v[k] = __builtin_nontemporal_load(g + base + k * 64);
+            for (u32 k = 0; k < kLoads; ++k) v[k] = __builtin_nontemporal_load(g + base + k * 64);
 #pragma unroll
-        for (u32 k = 0; k < kLoads; ++k) acc.add(v[k]);
+            for (u32 k = 0; k < kLoads; ++k) acc.add(v[k]);
+        }
+    } else {
+        // Large regions: blocks of block_chunks consecutive chunks are handed out in address order from one
+        // counter.  However unevenly the waves advance, the device as a whole then sweeps through the region front
+        // to back and reads one memory zone after the other; with the fixed round-robin assignment the slow waves
+        // fall so far behind that all zones are read at once.  The blocks are large
+        // because an atomic on one address takes about 12 ns.
+        const u64 n_blocks = (n_chunks + block_chunks - 1) / block_chunks;
+        for (;;) {
+            u32 t = 0;
+            if (lane == 0) t = atomicAdd(&s->tickets[0], 1u);
+            const u64 b = __builtin_amdgcn_readfirstlane(t);
+            if (b >= n_blocks) break;
+            const u64 c_end = min((b + 1) * block_chunks, n_chunks);
+            for (u64 c = b * block_chunks; c < c_end; ++c) {
+                const u64 base = c * (64 * kLoads) + lane;
+                u32x4 v[kLoads];
+#pragma unroll
+                for (u32 k = 0; k < kLoads; ++k) v[k] = __builtin_nontemporal_load(g + base + k * 64);
+#pragma unroll
+                for (u32 k = 0; k < kLoads; ++k) acc.add(v[k]);
+            }
+        }
     }
     const u64 stride = (u64)gridDim.x * blockDim.x;
     for (u64 i = n_chunks * (64 * kLoads) + (u64)blockIdx.x * blockDim.x + threadIdx.x; i < n_vec; i += stride)
@@ -139,11 +165,20 @@ extern "C" int rr_seq_read(const void *region, uint64_t region_bytes, void *hip_
     u64 blocks = (n_vec + 255) / 256;
     const u64 cap = 16ull * st->cus.size();  // two rounds of resident workgroups; each wave loops over its chunks
     if (blocks > cap) blocks = cap;
+    // Regions that may span several memory zones (more than 96 GiB) are swept front to back in blocks of 2 MiB
+    // from one counter: 6.82 / 6.91 / 6.89 TB/s over 128 / 192 / 256 GiB against 6.77 / 6.75 / 6.48 with the static
+    // assignment, which in turn is better inside one zone (7.0 against 6.7 TB/s at 64 GiB: no claims, no imbalance
+    // from the coarse blocks).
+    const u32 block_chunks = region_bytes > (96ull << 30) ? 256u : 0u;
     rc = begin_cells(*st, stream);
     if (rc != RR_OK) return rc;
+    if (block_chunks) {
+        rc = launch_reset(*st, 2u, stream);
+        if (rc != RR_OK) return rc;
+    }
     HIP_TRY(hipEventRecord(st->ev0, stream));
     hipLaunchKernelGGL(seq_read_kernel, dim3((u32)blocks), dim3(256), 0, stream, (const u32x4 *)region, n_vec,
-                       st->scratch);
+                       st->scratch, block_chunks);
     HIP_TRY(hipGetLastError());
     HIP_TRY(hipEventRecord(st->ev1, stream));
     rc = finish_and_wait(*st, 0u, 1u, 0u, stream);
