@@ -1,0 +1,152 @@
+"""Turn a result file of the experiment driver into a Markdown report.
+
+    python -m paper_2405_11425_amd.report results.jsonl > RESULTS.md
+
+One table per experiment of sweep.py: achieved GB/s (decimal, lines read x line bytes / kernel time) and
+the share of the 8 TB/s HBM3E peak per region size, line width and window scheme, the probes, the
+latency walks and the small-translation experiments.  Pure text processing; no GPU, no library.
+"""
+import collections
+import json
+import sys
+
+PEAK = 8000.0
+
+
+def pct(gbps):
+    return f"{gbps / PEAK * 100:.1f} %"
+
+
+def table(header, rows):
+    out = ["| " + " | ".join(header) + " |", "|" + "|".join("---" for _ in header) + "|"]
+    out += ["| " + " | ".join(str(c) for c in r) + " |" for r in rows]
+    return "\n".join(out) + "\n"
+
+
+def gib(x):
+    return f"{x:g} GiB"
+
+
+def report(rows):
+    by = collections.defaultdict(list)
+    for r in rows:
+        by[r["experiment"]].append(r)
+    out = ["# Results of `python -m paper_2405_11425_amd.sweep all`\n"]
+    env = next((r["environment"] for r in rows if "environment" in r), None)
+    if env:
+        out.append(f"{env.get('device')} ({env.get('arch')}), {env.get('compute_units')} CUs, {env.get('memory_gib')} GiB, "
+                   f"ROCm {env.get('rocm')}, compute partition {env.get('compute_partition')}, memory partition "
+                   f"{env.get('memory_partition')}, memory clock {env.get('mclk')}.  Throughput is lines read x line bytes / "
+                   "kernel time (HIP events), decimal GB/s; the percentage is of the 8 TB/s HBM3E peak.  Checksums of "
+                   "every row can be recomputed with `python tests/verify_sweep.py`.\n")
+
+    if by["region"]:
+        out.append("## Throughput vs region size (uniform random 128-byte lines)\n")
+        sizes = sorted({r["region_gib"] for r in by["region"]})
+        cols = [("uniform", None, "plain order"), ("uniform, zone by zone", None, "zone by zone"),
+                ("uniform", "16x", "plain, 16x longer launches"), ("uniform, zone by zone", "16x", "zone by zone, 16x longer")]
+        cell = {(r["scheme"], r.get("launch_size"), r["region_gib"]): r["gbps"] for r in by["region"]}
+        body = []
+        for s in sizes:
+            row = [gib(s)]
+            for scheme, size, _ in cols:
+                v = cell.get((scheme, size, s))
+                row.append(f"{v:.0f} ({pct(v)})" if v else "")
+            body.append(row)
+        out.append(table(["region"] + [c[2] for c in cols], body))
+
+    if by["lines"]:
+        out.append("## Line width (2^30 reads per launch)\n")
+        body = [[gib(r["region_gib"]), f"{r['lanes_per_line']} x {r['line_bytes'] // r['lanes_per_line']} B = {r['line_bytes']} B",
+                 r.get("order", "plain"), f"{r['gbps']:.0f} ({pct(r['gbps'])})"] for r in by["lines"]]
+        out.append(table(["region", "line", "order", "GB/s"], body))
+
+    if by["windows"]:
+        out.append("## Windows (each group of CUs restricted to one window of the region)\n")
+        body = [[gib(r["region_gib"]), r["scheme"], r["n_windows"], f"{r['gbps']:.0f} ({pct(r['gbps'])})"] for r in by["windows"]]
+        out.append(table(["region", "scheme", "windows", "GB/s"], body))
+
+    if by["stream"]:
+        out.append("## Streaming ceilings\n")
+        body = [[r["kind"], gib(r.get("region_gib", r.get("copied_gib"))), f"{r['gbps']:.0f} ({pct(r['gbps'])})"] for r in by["stream"]]
+        out.append(table(["kernel", "size", "GB/s"], body))
+
+    if by["updates"]:
+        out.append("## Random 128-byte line writes and atomic adds (2^26 lines per launch)\n")
+        body = [[r["op"], gib(r["region_gib"]), f"{r['gbps_lines']:.0f} ({pct(r['gbps_lines'])})"] for r in by["updates"]]
+        out.append(table(["operation", "region", "GB/s of lines"], body))
+
+    if by["zones"]:
+        out.append("## Memory zones (two 8 GiB windows read at a time, all pairs)\n")
+        for r in by["zones"]:
+            ranges = "; ".join("zone %d: %s" % (i, ", ".join(f"{a:g}-{b:g} GiB" for a, b in z))
+                               for i, z in enumerate(r["zone_ranges_gib"]))
+            out.append(f"{r['n_zones']} zones ({ranges}).  Pairs inside one zone {r['gbps_same_zone_median']:.0f} GB/s, across zones "
+                       f"{r['gbps_cross_zone_median']:.0f} GB/s (medians).  Uniform reads over {r['region_gib']} GiB: "
+                       f"{r['gbps_uniform_plain']:.0f} GB/s in plain order, {r['gbps_uniform_zone_by_zone']:.0f} GB/s zone by zone.\n")
+
+    if by["probe"]:
+        out.append("## Pair probe (which CUs share memory-path resources)\n")
+        for r in by["probe"]:
+            out.append(f"{r['n_units']} units of {r['unit_cus']} CU(s), {r['n_pairs']} pairs: pair / (single + single) between "
+                       f"{r['ratio_min']:.3f} and {r['ratio_max']:.3f} (median {r['ratio_median']:.3f}); threshold "
+                       f"{r['threshold']}; {r['n_groups']} groups of {r['group_sizes_in_cus']} CUs; one checksum for all runs: "
+                       f"{r['distinct_checksums'] == 1}.\n")
+
+    for r in by["groups"]:
+        if "gbps_by_xcd" in r:
+            out.append("## Groups alone, scaling, pairs of groups\n")
+            vals = list(r["gbps_by_xcd"].values())
+            out.append(f"Each XCD alone ({r['cus_per_xcd']} CUs): {min(vals):.0f}-{max(vals):.0f} GB/s.\n")
+        elif "gbps_inside_one_xcd" in r:
+            out.append("CUs inside one XCD: " + ", ".join(f"{k}: {v:.0f}" for k, v in r["gbps_inside_one_xcd"].items())
+                       + " GB/s; spread over all XCDs: " + ", ".join(f"{k}: {v:.0f}" for k, v in r["gbps_spread"].items()) + " GB/s.\n")
+        elif "pair_over_sum_of_singles" in r:
+            out.append(f"Pairs of XCDs on disjoint regions: {r['ratio_min']:.3f}-{r['ratio_max']:.3f} of the sum of the two alone.\n")
+
+    if by["latency"]:
+        out.append("## Dependent-load latency vs footprint\n")
+        body = [[f"{r['footprint_mib']:g} MiB", r["ns_per_hop"]] for r in by["latency"]]
+        out.append(table(["footprint", "ns per hop"], body))
+
+    if by["pages"]:
+        out.append("## Closed walk over N lines, one per stride (ns per hop)\n")
+        dists = sorted({r["distance_bytes"] for r in by["pages"]})
+        ns = sorted({r["n_lines"] for r in by["pages"]})
+        cell = {(r["distance_bytes"], r["n_lines"]): r["ns_per_hop"] for r in by["pages"]}
+        name = lambda d: "128 B" if d == 0 else (f"{d >> 30} GiB" if d >= 1 << 30 else f"{d >> 20} MiB" if d >= 1 << 20 else f"{d >> 10} KiB")
+        body = [[n] + [cell.get((d, n), "") for d in dists] for n in ns]
+        out.append(table(["lines"] + [name(d) for d in dists], body))
+
+    if by["pieces-size"]:
+        r0 = by["pieces-size"][0]
+        out.append(f"## Region mapped in {r0['n_pieces']} separate pieces of {r0['piece_kib']} KiB (one translation per piece)\n")
+        arms = ["uniform", "random_per_cu_8", "random_per_cu_32", "xcd_8", "shader_engine_32", "own_per_cu"]
+        body = [[f"{r['region_mib']:g} MiB", r["pieces_in_region"]] + [f"{r['gbps_' + a]:.0f}" if ("gbps_" + a) in r else "" for a in arms]
+                for r in by["pieces-size"]]
+        out.append(table(["region", "pieces"] + [a.replace("_", " ") for a in arms], body))
+    for r in by["pieces-reach"]:
+        out.append("One CU alone on a window of w pieces: " + ", ".join(f"{w}: {g:.0f}" for w, g in zip(r["window_pieces"], r["gbps"])) + " GB/s.\n")
+    for r in by["pieces-share"]:
+        out.append(f"k CUs of one XCD, each on its own window of {r['window_pieces']} pieces (GB/s per CU): "
+                   + ", ".join(f"{k}: {g:.1f}" for k, g in zip(r["cus_of_one_xcd"], r["gbps_per_cu_one_xcd"]))
+                   + "; k CUs of every XCD: " + ", ".join(f"{k}: {g:.1f}" for k, g in zip(r["cus_per_xcd_all_xcds"], r["gbps_per_cu_all_xcds"])) + ".\n")
+    for r in by["pieces-probe"]:
+        out.append(f"Pair probe with blocks of {r['unit_cus']} CUs, every CU on its own window of {r['window_pieces']} pieces: ratios "
+                   f"{r['ratio_min']:.3f}-{r['ratio_max']:.3f}, {r['n_groups']} groups of {r['group_sizes_in_cus']} CUs; the groups are the "
+                   f"XCDs: {r['groups_are_xcds']}.\n")
+    return "\n".join(out)
+
+
+def main(argv=None):
+    argv = sys.argv[1:] if argv is None else argv
+    if len(argv) != 1:
+        print(__doc__, file=sys.stderr)
+        return 2
+    rows = [json.loads(line) for line in open(argv[0]) if line.strip()]
+    print(report(rows))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -204,6 +204,44 @@ def test_verify_sweep_tool(tmp_path, worked):
     assert verify_sweep.main([str(path), "--threads", "2"]) == 0
 
 
+def test_report_renders_every_kind_of_row():
+    """The Markdown report of a result file: a table or sentence for each experiment, and no crash on a file that
+    holds only some of them."""
+    from paper_2405_11425_amd import report
+    env = {"device": "d", "arch": "gfx950", "compute_units": 256, "memory_gib": 288.0, "rocm": "7.2.0",
+           "compute_partition": "SPX", "memory_partition": "NPS1", "mclk": "2000Mhz"}
+    rows = [
+        {"experiment": "region", "scheme": "uniform", "region_gib": 1.0, "gbps": 6900.0, "environment": env},
+        {"experiment": "region", "scheme": "uniform, zone by zone", "region_gib": 256.0, "gbps": 6700.0},
+        {"experiment": "region", "scheme": "uniform", "launch_size": "16x", "region_gib": 256.0, "gbps": 6400.0},
+        {"experiment": "lines", "region_gib": 128.0, "line_bytes": 256, "lanes_per_line": 64, "order": "plain", "gbps": 6650.0},
+        {"experiment": "windows", "region_gib": 256.0, "scheme": "xcd", "n_windows": 8, "gbps": 6200.0},
+        {"experiment": "stream", "kind": "sequential read", "region_gib": 16, "gbps": 7000.0},
+        {"experiment": "updates", "op": "write", "region_gib": 16, "gbps_lines": 5000.0},
+        {"experiment": "zones", "n_zones": 2, "zone_ranges_gib": [[[0.0, 96.0]], [[96.0, 128.0]]], "region_gib": 128,
+         "gbps_same_zone_median": 6800.0, "gbps_cross_zone_median": 6500.0, "gbps_uniform_plain": 6550.0,
+         "gbps_uniform_zone_by_zone": 6700.0},
+        {"experiment": "probe", "n_units": 64, "unit_cus": 4, "n_pairs": 2016, "ratio_min": 0.72, "ratio_max": 1.0,
+         "ratio_median": 0.99, "threshold": 0.87, "n_groups": 32, "group_sizes_in_cus": [8], "distinct_checksums": 1},
+        {"experiment": "groups", "gbps_by_xcd": {"0": 1200.0, "1": 1190.0}, "cus_per_xcd": 32},
+        {"experiment": "latency", "footprint_mib": 1, "ns_per_hop": 155.0},
+        {"experiment": "pages", "distance_bytes": 1 << 30, "n_lines": 33, "ns_per_hop": 200.0},
+        {"experiment": "pieces-size", "region_mib": 512.0, "pieces_in_region": 4096, "n_pieces": 24576, "piece_kib": 128,
+         "gbps_uniform": 280.0, "gbps_own_per_cu": 6600.0},
+        {"experiment": "pieces-reach", "window_pieces": [16, 96], "gbps": [56.0, 10.0]},
+        {"experiment": "pieces-share", "window_pieces": 48, "cus_of_one_xcd": [4, 6], "gbps_per_cu_one_xcd": [50.0, 11.0],
+         "cus_per_xcd_all_xcds": [4], "gbps_per_cu_all_xcds": [49.0]},
+        {"experiment": "pieces-probe", "unit_cus": 4, "window_pieces": 48, "ratio_min": 0.18, "ratio_max": 1.01, "n_groups": 8,
+         "group_sizes_in_cus": [32], "groups_are_xcds": True},
+    ]
+    text = report.report(rows)
+    for needle in ("Throughput vs region size", "| 256 GiB |  | 6700 (83.8 %) | 6400 (80.0 %) |", "64 x 4 B = 256 B", "xcd | 8",
+                   "sequential read", "write | 16 GiB", "2 zones", "32 groups of [8] CUs", "1190-1200 GB/s", "| 1 MiB | 155.0 |",
+                   "| 33 | 200.0 |", "| 512 MiB | 4096 | 280 |", "96: 10", "6: 11.0", "the groups are the XCDs: True"):
+        assert needle in text, needle
+    assert "Line width" not in report.report(rows[:1])
+
+
 def test_region_create_validation():
     """Argument checks of the piecewise region come before any HIP call."""
     for args, needle in (((0, 4096), "multiple of piece_bytes"), ((8192, 0), "multiple of piece_bytes"),
