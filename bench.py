@@ -191,6 +191,9 @@ def main():
         "gbps_at_largest_region": curve[-1]["gbps"],
         "fill_gbps": round(max_gib * GiB / fill_s / 1e9, 1),
         "roofline": roofline,
+        # the paper's own figures (A100 SXM4-80GB, Sec. 2.1): context, not a target, hence vs_baseline is null
+        "paper_context_a100": {"theoretical_hbm_gbps": 1900, "random_256B_lines_gbps": 1400,
+                               "random_512B_lines_gbps": 1600, "throughput_collapses_above_gb": 64},
     }
 
     if zone_info is not None:
