@@ -96,6 +96,66 @@ def test_rand_read_rejects_bad_arguments_without_a_device(args, kw, needle):
     assert e.value.code == rl.RR_EINVAL and needle in str(e.value)
 
 
+def _expected_to_pass(ptr, nbytes, B, lanes, iters, wm, kw):
+    """The header's argument rules, restated (for calls with n_reads = 0, which return before any device work)."""
+    if ptr == 0 or B not in (128, 256, 512) or lanes not in (32, 64) or B // lanes not in (4, 8, 16):
+        return False
+    if nbytes == 0 or nbytes % B or ptr % B or nbytes // B > 1 << 32 or iters == 0:
+        return False
+    n_lines, G = nbytes // B, 1
+    if wm is not None:
+        G = wm.n_groups
+        if not 1 <= G <= 1024 or wm.n_windows == 0 or n_lines % wm.n_windows or not 1 <= wm.group_of_cu.size <= 1024:
+            return False
+        if any(g != 0xFFFF and g >= G for g in wm.group_of_cu) or any(w >= wm.n_windows for w in wm.window_of_group):
+            return False
+    if kw.get("block_threads", 0) not in (0, 64, 128, 256) or kw.get("bcast", 0) > 3 or kw.get("nontemporal", 0) > 2:
+        return False
+    if kw.get("mode", 0) > 2 or kw.get("chunk_iters", 0) % 64 or kw.get("first_wave", 0) % G:
+        return False
+    wdw = B // lanes // 4
+    if kw.get("unroll", 0) not in ((0, 2, 4, 8) if wdw == 4 else (0, 4, 8, 16)):
+        return False
+    if wm is not None and kw.get("mode", 0) == rl.MODE_FLAT and (G > 1 or (wm.group_of_cu == 0xFFFF).any()):
+        return False
+    return True
+
+
+def test_argument_rules_hold_for_generated_calls():
+    """Property test of rr_rand_read's validation: generated argument combinations are accepted or rejected as the
+    header says.  Every call has n_reads = 0, so an accepted call returns before any device work (also on a GPU machine)."""
+    from hypothesis import given, settings, strategies as st
+
+    maps = st.none() | st.builds(
+        lambda G, nw, cus, goc_bad, wog_bad: rl.WindowMap(
+            nw, np.array([(c % max(G, 1)) if not (goc_bad and c == 1) else G + 3 for c in range(cus)], np.uint16)
+            if cus else np.zeros(0, np.uint16),
+            np.array([(g % max(nw, 1)) if not (wog_bad and g == 0) else nw + 1 for g in range(G)], np.uint16)),
+        st.sampled_from([0, 1, 2, 8, 256, 1024, 1025]), st.sampled_from([0, 1, 2, 3, 8, 64]),
+        st.sampled_from([0, 1, 4, 256, 1024]), st.booleans(), st.booleans())
+    launch = st.fixed_dictionaries({}, optional={
+        "block_threads": st.sampled_from([0, 64, 96, 128, 256, 512]), "unroll": st.sampled_from([0, 2, 4, 8, 16, 32]),
+        "mode": st.sampled_from([0, 1, 2, 3]), "bcast": st.sampled_from([0, 1, 2, 3, 4]),
+        "nontemporal": st.sampled_from([0, 1, 2, 3]), "chunk_iters": st.sampled_from([0, 64, 100, 512]),
+        "first_wave": st.sampled_from([0, 1, 2, 8, 1024])})
+
+    @settings(max_examples=600, deadline=None)
+    @given(ptr=st.sampled_from([0, 1 << 21, (1 << 21) + 64, (1 << 21) + 256]),
+           nbytes=st.sampled_from([0, 1000, 4096, 12288, 1 << 20, 3 << 20, 1 << 39, (1 << 39) + (1 << 38)]),
+           B=st.sampled_from([64, 100, 128, 256, 512, 1024]), lanes=st.sampled_from([16, 32, 48, 64]),
+           iters=st.sampled_from([0, 1, 7, 4096]), wm=maps, kw=launch)
+    def check(ptr, nbytes, B, lanes, iters, wm, kw):
+        want = _expected_to_pass(ptr, nbytes, B, lanes, iters, wm, kw)
+        try:
+            got = rl.rand_read((ptr, nbytes), B, 0, iters, 7, wm, lanes_per_line=lanes, **kw)
+            assert want, ("accepted", ptr, nbytes, B, lanes, iters, wm, kw)
+            assert (got.checksum, got.waves_run, got.launches) == (0, 0, 0)
+        except rl.RandlineError as e:
+            assert e.code == rl.RR_EINVAL and not want, (str(e), ptr, nbytes, B, lanes, iters, wm, kw)
+
+    check()
+
+
 @pytest.mark.parametrize("wm,n_reads,kw,needle", [
     (rl.WindowMap(3, np.zeros(4, np.uint16), np.zeros(1, np.uint16)), 8, {}, "divide"),
     (rl.WindowMap(2, np.array([0, 2], np.uint16), np.array([0, 1], np.uint16)), 16, {}, "group_of_cu"),
