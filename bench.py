@@ -4,7 +4,8 @@
     python bench.py [--gpus 1] [--steps K] [--warmup W]
 
 One "step" is one pass of the hot path over the region-size sweep: for each region size
-(1, 2, 4, ..., 128, 192, 256 GiB prefixes of one filled allocation) one rr_rand_read call in
+(1, 2, 4, ..., 128, 192, 256 GiB prefixes of one filled allocation) one read launch (all of a
+step's launches go out in one rr_rand_read_batch call, which waits once at the end) in
 which every wave slot of the device is occupied and every 32-lane logical wave reads 4096
 uniformly random, aligned 128-byte lines (paper Sec. 2.1).  The fill is done once before the
 timed region (the region is resident in HBM when timing starts).  Prints ONE JSON line.
@@ -48,6 +49,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--max-region-gib", type=int, default=256)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
+    ap.add_argument("--one-by-one", action="store_true",
+                    help="one rr_rand_read call (and one wait) per region size instead of one rr_rand_read_batch per step")
     ap.add_argument("--plain-order", action="store_true",
                     help="read every region in plain order (no zone probe, no zone-by-zone launches)")
     args = ap.parse_args()
@@ -126,10 +129,18 @@ def main():
             order = {cfg.name: None for cfg in configs}
             zone_info = {"error": str(e)}
 
+    c0 = configs[0]   # the points differ in region size (and read order) only
+
     def step(seed, record=None):
-        for cfg in configs:
-            r = read(cfg, seed, order[cfg.name])
-            if record is not None:
+        if args.one_by_one:
+            results = [read(cfg, seed, order[cfg.name]) for cfg in configs]
+        else:       # the same calls, queued back to back with one wait at the end of the step
+            items = [(cfg.region_bytes, seed, {"zone_of_window": order[cfg.name]} if order[cfg.name] is not None else None)
+                     for cfg in configs]
+            results = rl.rand_read_batch(region, items, c0.line_bytes, c0.n_reads, c0.iters_per_wave,
+                                         lanes_per_line=c0.lanes_per_line)
+        if record is not None:
+            for cfg, r in zip(configs, results):
                 record.setdefault(cfg.name, []).append(r)
 
     for i in range(args.warmup):
@@ -179,7 +190,9 @@ def main():
                                f"{n_cus * wl.WAVES_PER_CU} wave slots occupied, each 32-lane logical wave reading "
                                "4096 uniformly random 128-B lines; regions are prefixes of one filled allocation; "
                                "regions that span several memory zones are read in whichever order was faster "
-                               "before the timed steps, plain or zone by zone (same lines, same checksums)",
+                               "before the timed steps, plain or zone by zone (same lines, same checksums); "
+                               + ("one call and one wait per launch" if args.one_by_one else
+                                  "a step's launches are queued back to back by one batched call that waits once"),
                    "regions_gib": [c.region_bytes // GiB for c in configs], "line_bytes": 128,
                    "lanes_per_line": 32, "logical_waves": configs[0].logical_waves,
                    "iters_per_wave": configs[0].iters_per_wave, "reads_per_launch": configs[0].n_reads,

@@ -190,6 +190,34 @@ int rr_rand_read(const void *region, uint64_t region_bytes, uint32_t line_bytes,
                  const rr_launch_opts_t *opts, rr_result_t *out);
 
 /*
+ * A series of measurements in one call (the paper's throughput curve, Sec. 2.1,
+ * is such a series: the same number of reads over regions of growing size).
+ * Item i is the call rr_rand_read(region, items[i].region_bytes, line_bytes,
+ * lanes_per_line, n_reads, iters_per_wave, NULL, items[i].read_seed, stream,
+ * items[i].opts, &out[i]) and returns the same checksum; the difference is
+ * that all kernels are queued on the stream back to back and the host waits
+ * once, at the end, so the device does not idle between the launches while
+ * the host fetches one result and prepares the next launch.
+ *   items     host [n_items]; opts may be NULL (defaults) and must not ask for
+ *             placement_out, cu_waves_out or phase_ticks
+ *   n_items   0 (nothing happens) to 64
+ *   out       host [n_items]; every entry is written on success
+ * There is no window map.  A ticketed item gets its one launch: should that
+ * leave tickets unclaimed (a compute unit that never received a workgroup and
+ * nobody stole from), the call fails with RR_EPLACE where rr_rand_read would
+ * launch again.  All arguments are validated before anything is launched.
+ */
+typedef struct {
+    uint64_t region_bytes;
+    uint64_t read_seed;
+    const rr_launch_opts_t *opts;
+} rr_read_item_t;
+
+int rr_rand_read_batch(const void *region, const rr_read_item_t *items, uint32_t n_items,
+                       uint32_t line_bytes, uint32_t lanes_per_line, uint64_t n_reads,
+                       uint32_t iters_per_wave, void *hip_stream, rr_result_t *out);
+
+/*
  * The paper's two-SM probe (Sec. 2.2): the same access stream (G = 1, no
  * windows, 128-byte lines of 32 lanes x 4 bytes) executed only by waves resident
  * on CUs cu_a and cu_b (dense ids, different, < CU count).  An oversubscribed

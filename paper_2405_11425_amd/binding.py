@@ -56,7 +56,11 @@ class _Opts(C.Structure):
                 ("cu_waves_out", C.POINTER(C.c_uint32))]
 
 
-EXPORTS = ["rr_enumerate_cus", "rr_fill", "rr_rand_read", "rr_probe_pair", "rr_probe_cus", "rr_seq_read", "rr_copy", "rr_chase", "rr_rand_update",
+class _ReadItem(C.Structure):
+    _fields_ = [("region_bytes", C.c_uint64), ("read_seed", C.c_uint64), ("opts", C.POINTER(_Opts))]
+
+
+EXPORTS = ["rr_enumerate_cus", "rr_fill", "rr_rand_read", "rr_rand_read_batch", "rr_probe_pair", "rr_probe_cus", "rr_seq_read", "rr_copy", "rr_chase", "rr_rand_update",
            "rr_region_granularity", "rr_region_create", "rr_region_destroy",
            "rr_groups_from_heatmap", "rr_shutdown", "rr_strerror", "rr_last_error"]
 
@@ -89,6 +93,8 @@ def lib():
         L.rr_rand_read.restype = C.c_int
         L.rr_rand_read.argtypes = [vp, u64, u32, u32, u64, u32, C.POINTER(_WindowMap), u64, vp,
                                    C.POINTER(_Opts), C.POINTER(_Result)]
+        L.rr_rand_read_batch.restype = C.c_int
+        L.rr_rand_read_batch.argtypes = [vp, C.POINTER(_ReadItem), u32, u32, u32, u64, u32, vp, C.POINTER(_Result)]
         L.rr_probe_pair.restype = C.c_int
         L.rr_probe_pair.argtypes = [vp, u64, u32, u32, u64, u32, u64, vp, C.POINTER(_Opts), C.POINTER(_Result)]
         L.rr_probe_cus.restype = C.c_int
@@ -236,6 +242,30 @@ def rand_read(region, line_bytes: int, n_reads: int, iters_per_wave: int, read_s
                               C.byref(o), C.byref(res)))
     return ReadResult(int(res.checksum), res.kernel_ms_event, res.kernel_ms_device, int(res.waves_run),
                       int(res.launches), placement[:W] if placement is not None else None, cu_waves)
+
+
+def rand_read_batch(region, items: Sequence, line_bytes: int, n_reads: int, iters_per_wave: int,
+                    lanes_per_line: int = 32, stream=None):
+    """Several rand_read calls queued back to back with one wait at the end (see rr_rand_read_batch).
+
+    items: one (region_bytes, read_seed) or (region_bytes, read_seed, launch options as a dict) per call.
+    Returns a list of ReadResult, one per item."""
+    ptr, _ = _region(region, 0)
+    n = len(items)
+    arr = (_ReadItem * max(n, 1))()
+    keep = []
+    for i, it in enumerate(items):
+        nbytes, seed = int(it[0]), int(it[1])
+        launch = dict(it[2]) if len(it) > 2 and it[2] else None
+        arr[i].region_bytes, arr[i].read_seed = nbytes, seed
+        if launch is not None:
+            o, _, _ = _opts(0, 1024, **launch)
+            keep.append(o)
+            arr[i].opts = C.pointer(o)
+    res = (_Result * max(n, 1))()
+    _check(lib().rr_rand_read_batch(ptr, arr, n, line_bytes, lanes_per_line, n_reads, iters_per_wave, _stream(stream), res))
+    return [ReadResult(int(r.checksum), r.kernel_ms_event, r.kernel_ms_device, int(r.waves_run), int(r.launches))
+            for r in res[:n]]
 
 
 def probe_cus(region, cus: Sequence[int], n_reads: int, iters_per_wave: int, read_seed: int,

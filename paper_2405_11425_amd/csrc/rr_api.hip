@@ -231,6 +231,81 @@ int prepare_tables(DeviceState &st, const Plan &pl, const rr_window_map_t *wm, u
     return RR_OK;
 }
 
+// One launch of a read kernel, ready to go: parameters, kernel, grid.
+struct Launch {
+    ReadParams p;
+    kernel_handle kernel = nullptr;
+    u32 grid = 0;
+    u32 tickets_per_unit = 0;
+    u32 reset_bits = 0;  // what reset_kernel has to clear first, the result cells aside
+};
+
+int make_launch(const Plan &pl, DeviceState &st, const void *region, uint32_t iters, bool has_map, uint64_t read_seed,
+                const rr_launch_opts_t *opts, u16 *placement, Launch &ln) {
+    const u32 n_cus = (u32)st.cus.size();
+    const u32 lpw = 64 / pl.lanes;
+    const u64 L_win = pl.n_lines / pl.n_windows;
+    const u64 quota = pl.W / pl.G;
+    const u64 units = (quota + lpw - 1) / lpw;  // per group
+    ReadParams &p = ln.p;
+    memset(&p, 0, sizeof p);
+    p.region = (const char *)region;
+    p.read_seed = read_seed;
+    p.first_wave = pl.first_wave;
+    p.quota = quota;
+    p.iters = iters;
+    // flat launches default to one hardware wave per whole logical wave (pair); ticketed ones to
+    // chunks of 1024 iterations (shorter ones pay for draining the load ring at every chunk end)
+    const bool phased = pl.n_zones > 0;  // its chunks are what one pass through the LDS lists holds
+    u32 chunk = phased ? kPhaseChunk : pl.chunk_iters ? pl.chunk_iters : (pl.mode == RR_MODE_TICKET ? 1024u : iters);
+    if (chunk > iters) chunk = iters;
+    p.chunk_iters = chunk;
+    p.chunks_per_wave = (iters + chunk - 1) / chunk;
+    p.n_groups = pl.G;
+    p.n_zones = pl.n_zones;
+    p.zone_shift = pl.zone_shift;
+    memcpy(p.zone_mask, pl.zone_mask, sizeof p.zone_mask);
+    p.ticket_mode = pl.mode == RR_MODE_TICKET ? 1u : 0u;
+    p.log2_line = pl.log2_line;
+    p.red = make_reducer(L_win);
+    p.scratch = st.scratch;
+    p.tables = st.tables;
+    p.placement = placement;
+    const bool want_cu_waves = opts && opts->cu_waves_out;
+    p.locate = (placement || want_cu_waves) ? 1u : 0u;
+    p.phase_ticks = (opts && pl.n_zones) ? (u64 *)opts->phase_ticks : nullptr;
+
+    const u32 waves_per_block = pl.block / 64;
+    u64 grid;
+    if (p.ticket_mode) {
+        // As many workgroups as are resident at once: work-stealing finishes the job whatever the placement, and
+        // every workgroup beyond that only starts when the work is done, scans all shares and leaves -- which
+        // lengthens the kernel (measured 1-2 %).  Pinned runs need many more, most land on CUs that take no part.
+        u32 blocks_per_cu = resident_blocks_per_cu(pl.kernel, pl.block);
+        if (pl.pinned) blocks_per_cu = (32 / waves_per_block) * 64u;
+        grid = pl.grid_blocks ? pl.grid_blocks : (u64)blocks_per_cu * n_cus;
+    } else {
+        const u64 hw_waves = (pl.W + lpw - 1) / lpw * (phased ? 1u : p.chunks_per_wave);
+        grid = (hw_waves + waves_per_block - 1) / waves_per_block;
+    }
+    if (grid == 0 || grid > 0x7FFFFFFFull) return fail(RR_EINVAL, "launch of %llu workgroups is out of range", grid);
+    ln.grid = (u32)grid;
+
+    const u64 tickets_per_unit = (u64)p.chunks_per_wave * (phased ? pl.n_zones : 1u);
+    if (units * tickets_per_unit >= (1ull << 31))
+        return fail(RR_EINVAL, "too many tickets per group (%llu)", units * tickets_per_unit);
+    ln.tickets_per_unit = (u32)tickets_per_unit;
+    // counters are needed by ticketed launches only
+    ln.reset_bits = (p.ticket_mode ? 2u : 0u) | ((p.ticket_mode || p.locate) ? 4u : 0u);
+    // the plain flat launch has a kernel of its own (fewer registers, 8 resident waves per SIMD instead of 7)
+    ln.kernel = pl.kernel;
+    if (!p.ticket_mode && !phased && !has_map && !p.locate) {
+        kernel_handle flat = find_flat_kernel(pl.lanes, pl.wdw, pl.unroll, pl.bcast, pl.nt);
+        if (flat) ln.kernel = flat;
+    }
+    return RR_OK;
+}
+
 int run_plan(const Plan &pl, const void *region, uint32_t iters, const rr_window_map_t *wm,
              uint64_t read_seed, hipStream_t stream, const rr_launch_opts_t *opts, rr_result_t *out) {
     rr_result_t res;
@@ -269,73 +344,25 @@ int run_plan(const Plan &pl, const void *region, uint32_t iters, const rr_window
     }
     if (want_placement) HIP_TRY(hipMemsetAsync(st.placement, 0xFF, pl.W * sizeof(u16), stream));
 
-    ReadParams p;
-    memset(&p, 0, sizeof p);
-    p.region = (const char *)region;
-    p.read_seed = read_seed;
-    p.first_wave = pl.first_wave;
-    p.quota = quota;
-    p.iters = iters;
-    // flat launches default to one hardware wave per whole logical wave (pair); ticketed ones to
-    // chunks of 1024 iterations (shorter ones pay for draining the load ring at every chunk end)
-    const bool phased = pl.n_zones > 0;  // its chunks are what one pass through the LDS lists holds
-    u32 chunk = phased ? kPhaseChunk : pl.chunk_iters ? pl.chunk_iters : (pl.mode == RR_MODE_TICKET ? 1024u : iters);
-    if (chunk > iters) chunk = iters;
-    p.chunk_iters = chunk;
-    p.chunks_per_wave = (iters + chunk - 1) / chunk;
-    p.n_groups = pl.G;
-    p.n_zones = pl.n_zones;
-    p.zone_shift = pl.zone_shift;
-    memcpy(p.zone_mask, pl.zone_mask, sizeof p.zone_mask);
-    p.ticket_mode = pl.mode == RR_MODE_TICKET ? 1u : 0u;
-    p.log2_line = pl.log2_line;
-    p.red = make_reducer(L_win);
-    p.scratch = st.scratch;
-    p.tables = st.tables;
-    p.placement = want_placement ? st.placement : nullptr;
+    Launch ln;
+    rc = make_launch(pl, st, region, iters, wm != nullptr, read_seed, opts, want_placement ? st.placement : nullptr, ln);
+    if (rc != RR_OK) return rc;
+    const ReadParams &p = ln.p;
     const bool want_cu_waves = opts && opts->cu_waves_out;
-    p.locate = (want_placement || want_cu_waves) ? 1u : 0u;
-    p.phase_ticks = (opts && pl.n_zones) ? (u64 *)opts->phase_ticks : nullptr;
-
-    const u32 waves_per_block = pl.block / 64;
-    u64 grid;
-    if (p.ticket_mode) {
-        // As many workgroups as are resident at once: work-stealing finishes the job whatever the placement, and
-        // every workgroup beyond that only starts when the work is done, scans all shares and leaves -- which
-        // lengthens the kernel (measured 1-2 %).  Pinned runs need many more, most land on CUs that take no part.
-        u32 blocks_per_cu = resident_blocks_per_cu(pl.kernel, pl.block);
-        if (pl.pinned) blocks_per_cu = (32 / waves_per_block) * 64u;
-        grid = pl.grid_blocks ? pl.grid_blocks : (u64)blocks_per_cu * n_cus;
-    } else {
-        const u64 hw_waves = (pl.W + lpw - 1) / lpw * (phased ? 1u : p.chunks_per_wave);
-        grid = (hw_waves + waves_per_block - 1) / waves_per_block;
-    }
-    if (grid == 0 || grid > 0x7FFFFFFFull) return fail(RR_EINVAL, "launch of %llu workgroups is out of range", grid);
-
-    const u64 tickets_per_unit = (u64)p.chunks_per_wave * (phased ? pl.n_zones : 1u);
-    if (units * tickets_per_unit >= (1ull << 31))
-        return fail(RR_EINVAL, "too many tickets per group (%llu)", units * tickets_per_unit);
-    // the finish kernel leaves the result cells cleared; counters are needed by ticketed launches only
-    const u32 what = (st.cells_clean ? 0u : 1u) | (p.ticket_mode ? 2u : 0u) |
-                     ((p.ticket_mode || p.locate) ? 4u : 0u);
+    // the finish kernel leaves the result cells cleared
+    const u32 what = (st.cells_clean ? 0u : 1u) | ln.reset_bits;
     if (what) {
         rc = launch_reset(st, what, stream);
         if (rc != RR_OK) return rc;
     }
     st.cells_clean = false;
     const int max_launches = p.ticket_mode ? 32 : 1;
-    // the plain flat launch has a kernel of its own (fewer registers, 8 resident waves per SIMD instead of 7)
-    kernel_handle kernel = pl.kernel;
-    if (!p.ticket_mode && !phased && !wm && !p.locate) {
-        kernel_handle flat = find_flat_kernel(pl.lanes, pl.wdw, pl.unroll, pl.bcast, pl.nt);
-        if (flat) kernel = flat;
-    }
-    void *args[] = {(void *)&p};
+    void *args[] = {(void *)&ln.p};
     for (int launch = 0;; ++launch) {
         HIP_TRY(hipEventRecord(st.ev0, stream));
-        HIP_TRY(hipLaunchKernel(kernel, dim3((u32)grid), dim3(pl.block), args, 0, stream));
+        HIP_TRY(hipLaunchKernel(ln.kernel, dim3(ln.grid), dim3(pl.block), args, 0, stream));
         HIP_TRY(hipEventRecord(st.ev1, stream));
-        rc = finish_and_wait(st, n_cus, (u32)tickets_per_unit, p.ticket_mode, stream);
+        rc = finish_and_wait(st, n_cus, ln.tickets_per_unit, p.ticket_mode, stream);
         if (rc != RR_OK) return rc;
         st.tables_valid = true;
         if (flat_no_map) st.flat_tables_ready = true;
@@ -377,6 +404,94 @@ extern "C" int rr_rand_read(const void *region, uint64_t region_bytes, uint32_t 
     int rc = make_plan(region, region_bytes, line_bytes, lanes_per_line, n_reads, iters_per_wave, wm, opts, out, pl);
     if (rc != RR_OK) return rc;
     return run_plan(pl, region, iters_per_wave, wm, read_seed, (hipStream_t)hip_stream, opts, out);
+}
+
+extern "C" int rr_rand_read_batch(const void *region, const rr_read_item_t *items, uint32_t n_items,
+                                  uint32_t line_bytes, uint32_t lanes_per_line, uint64_t n_reads,
+                                  uint32_t iters_per_wave, void *hip_stream, rr_result_t *out) {
+    if (n_items == 0) return RR_OK;
+    if (!items) return fail(RR_EINVAL, "items is NULL");
+    if (!out) return fail(RR_EINVAL, "out is NULL");
+    if (n_items > kMaxBatch) return fail(RR_EINVAL, "a batch holds at most %u calls (got %u)", kMaxBatch, n_items);
+    std::vector<Plan> plans(n_items);
+    for (u32 i = 0; i < n_items; ++i) {
+        const rr_launch_opts_t *o = items[i].opts;
+        if (o && (o->placement_out || o->cu_waves_out || o->phase_ticks))
+            return fail(RR_EINVAL, "item %u: per-wave outputs are not available in a batch", i);
+        int rc = make_plan(region, items[i].region_bytes, line_bytes, lanes_per_line, n_reads, iters_per_wave, nullptr,
+                           o, out, plans[i]);
+        if (rc != RR_OK) return rc;
+    }
+    memset(out, 0, n_items * sizeof(rr_result_t));
+    if (plans[0].W == 0) return RR_OK;  // nothing to read, in any item
+
+    hipStream_t stream = (hipStream_t)hip_stream;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    DeviceState *stp = nullptr;
+    int rc = get_state(stream, &stp);
+    if (rc != RR_OK) return rc;
+    DeviceState &st = *stp;
+    const u32 n_cus = (u32)st.cus.size();
+    while (st.batch_ev.size() < 2 * (size_t)n_items) {
+        hipEvent_t e = nullptr;
+        HIP_TRY(hipEventCreate(&e));
+        st.batch_ev.push_back(e);
+    }
+    // Without a window map the tables depend on the number of logical waves only, which the items share:
+    // one upload (if any) before the first launch serves them all.
+    const u32 lpw = 64 / plans[0].lanes;
+    const u64 units = (plans[0].W + lpw - 1) / lpw;
+    rc = prepare_tables(st, plans[0], nullptr, units, plans[0].n_lines, stream);
+    if (rc != RR_OK) return rc;
+    std::vector<Launch> launches(n_items);
+    for (u32 i = 0; i < n_items; ++i) {
+        rc = make_launch(plans[i], st, region, iters_per_wave, false, items[i].read_seed, items[i].opts, nullptr,
+                         launches[i]);
+        if (rc != RR_OK) return rc;
+    }
+    // queue everything, wait once
+    auto queue_all = [&]() -> int {
+        for (u32 i = 0; i < n_items; ++i) {
+            Launch &ln = launches[i];
+            const u32 what = (st.cells_clean ? 0u : 1u) | ln.reset_bits;
+            if (what) {
+                int r = launch_reset(st, what, stream);
+                if (r != RR_OK) return r;
+            }
+            st.cells_clean = false;
+            void *args[] = {(void *)&ln.p};
+            HIP_TRY(hipEventRecord(st.batch_ev[2 * i], stream));
+            HIP_TRY(hipLaunchKernel(ln.kernel, dim3(ln.grid), dim3(plans[i].block), args, 0, stream));
+            HIP_TRY(hipEventRecord(st.batch_ev[2 * i + 1], stream));
+            int r = launch_finish(st, i, n_cus, ln.tickets_per_unit, ln.p.ticket_mode, stream);
+            if (r != RR_OK) return r;
+            st.cells_clean = true;  // in stream order; what follows is on the same stream
+        }
+        HIP_TRY(hipStreamSynchronize(stream));
+        return RR_OK;
+    };
+    rc = queue_all();
+    if (rc != RR_OK) {
+        (void)hipStreamSynchronize(stream);
+        st.cells_clean = false;
+        return rc;
+    }
+    st.tables_valid = true;
+    st.flat_tables_ready = true;
+    for (u32 i = 0; i < n_items; ++i) {
+        const ResultHead &h = st.head[i];
+        float ms = 0.f;
+        HIP_TRY(hipEventElapsedTime(&ms, st.batch_ev[2 * i], st.batch_ev[2 * i + 1]));
+        out[i].launches = 1;
+        out[i].kernel_ms_event = ms;
+        out[i].checksum = h.checksum;
+        out[i].waves_run = h.waves_run;
+        if (h.waves_run && h.t_max >= h.t_min) out[i].kernel_ms_device = (double)(h.t_max - h.t_min) / (double)st.wall_khz;
+        if (launches[i].p.ticket_mode && h.unfinished)
+            return fail(RR_EPLACE, "item %u: %u compute units' shares still have unclaimed tickets after its one launch",
+                        i, h.unfinished);
+    }
+    return RR_OK;
 }
 
 extern "C" int rr_probe_cus(const void *region, uint64_t region_bytes, const uint32_t *cus, uint32_t n_target,

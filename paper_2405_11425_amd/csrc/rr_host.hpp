@@ -31,17 +31,19 @@ struct DeviceState {
     bool cells_clean = false;       // result cells are in their cleared state
     u16 *placement = nullptr;
     size_t placement_cap = 0;
-    ResultHead *head = nullptr;      // pinned host memory, mapped ...
-    ResultHead *head_dev = nullptr;  // ... and its address as the device sees it
+    ResultHead *head = nullptr;      // [kMaxBatch] pinned host memory, mapped ...
+    ResultHead *head_dev = nullptr;  // ... and its address as the device sees it; single calls use entry 0
     u32 *cu_waves_host = nullptr;    // pinned staging for the per-CU wave counts
     bool flat_tables_ready = false;  // the device tables are those of a call without a window map
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
+    std::vector<hipEvent_t> batch_ev;     // two per launch of a batch, created when first needed
     int wall_khz = 0;
     std::vector<rr_cu_t> cus;             // dense id -> coordinates
     std::vector<u16> dense_of_key_host;   // [kNumKeys], kExcluded if no such CU
 };
 
 constexpr int kMaxDevices = 16;
+constexpr u32 kMaxBatch = 64;  // launches one batched call may queue before it waits
 
 // One lock for everything below: device states, the piecewise regions, and every launch that uses the
 // per-device scratch (calls on one device are serialised).
@@ -65,7 +67,9 @@ inline Reducer make_reducer(u64 L) {
 int launch_reset(DeviceState &st, u32 what, hipStream_t stream);
 // Make sure the result cells are cleared before a kernel that adds into them (marks them used).
 int begin_cells(DeviceState &st, hipStream_t stream);
-// finish_kernel (cells -> result head in mapped host memory, cells cleared), then wait for the stream.
+// finish_kernel on `stream`: cells -> result head `slot` in mapped host memory, cells left cleared.
+int launch_finish(DeviceState &st, u32 slot, u32 n_cus, u32 tickets_per_unit, u32 ticket_mode, hipStream_t stream);
+// launch_finish into slot 0, then wait for the stream.
 int finish_and_wait(DeviceState &st, u32 n_cus, u32 tickets_per_unit, u32 ticket_mode, hipStream_t stream);
 
 // Piecewise regions still alive (rr_region.hip); for rr_shutdown, g_mutex held.

@@ -152,7 +152,7 @@ int get_state(hipStream_t stream, DeviceState **out) {
         if (!st.tables_host) HIP_TRY(hipHostMalloc((void **)&st.tables_host, sizeof(Tables), hipHostMallocDefault));
         if (!st.tables_last) st.tables_last = new Tables;
         if (!st.head) {
-            HIP_TRY(hipHostMalloc((void **)&st.head, sizeof(ResultHead), hipHostMallocMapped));
+            HIP_TRY(hipHostMalloc((void **)&st.head, kMaxBatch * sizeof(ResultHead), hipHostMallocMapped));
             HIP_TRY(hipHostGetDevicePointer((void **)&st.head_dev, st.head, 0));
         }
         if (!st.cu_waves_host) HIP_TRY(hipHostMalloc((void **)&st.cu_waves_host, kMaxCus * sizeof(u32), hipHostMallocDefault));
@@ -183,10 +183,17 @@ int begin_cells(DeviceState &st, hipStream_t stream) {
     return RR_OK;
 }
 
-int finish_and_wait(DeviceState &st, u32 n_cus, u32 tickets_per_unit, u32 ticket_mode, hipStream_t stream) {
-    hipLaunchKernelGGL(finish_kernel, dim3(1), dim3(kNumCells), 0, stream, st.scratch, st.head_dev, st.tables, n_cus,
-                       tickets_per_unit, ticket_mode);
+int launch_finish(DeviceState &st, u32 slot, u32 n_cus, u32 tickets_per_unit, u32 ticket_mode, hipStream_t stream) {
+    if (slot >= kMaxBatch) return fail(RR_EINVAL, "result slot %u out of range", slot);
+    hipLaunchKernelGGL(finish_kernel, dim3(1), dim3(kNumCells), 0, stream, st.scratch, st.head_dev + slot, st.tables,
+                       n_cus, tickets_per_unit, ticket_mode);
     HIP_TRY(hipGetLastError());
+    return RR_OK;
+}
+
+int finish_and_wait(DeviceState &st, u32 n_cus, u32 tickets_per_unit, u32 ticket_mode, hipStream_t stream) {
+    int rc = launch_finish(st, 0, n_cus, tickets_per_unit, ticket_mode, stream);
+    if (rc != RR_OK) return rc;
     HIP_TRY(hipStreamSynchronize(stream));
     st.cells_clean = true;
     return RR_OK;
@@ -241,6 +248,7 @@ extern "C" int rr_shutdown(void) {
         if (st.cu_waves_host) (void)hipHostFree(st.cu_waves_host);
         if (st.ev0) (void)hipEventDestroy(st.ev0);
         if (st.ev1) (void)hipEventDestroy(st.ev1);
+        for (hipEvent_t e : st.batch_ev) (void)hipEventDestroy(e);
         st = DeviceState();
     }
     release_all_regions();

@@ -586,6 +586,59 @@ def test_region_sweep_full_size(region, cu_table):
         assert got.waves_run == cfg.logical_waves // 2
 
 
+def test_batch_equals_single_calls(region):
+    """A batch of small calls -- flat, zone by zone with tickets, zone by zone flat, odd sizes, other
+    launch options -- returns what the same calls return one by one, and what the oracle says."""
+    W, I, B = 300, 517, 128
+    zmap = [0] * 4 + [1] * 4 + [2] * 8
+    items = [(1 << 30, 11), (3 << 26, 12), (1 << 30, 13, dict(zone_of_window=zmap)),
+             (1 << 30, 14, dict(zone_bytes=1 << 28, mode=rl.MODE_FLAT)), (5 * 128 * 1000, 15),
+             (1 << 27, 16, dict(mode=rl.MODE_TICKET, chunk_iters=128)), (1 << 30, 11, dict(unroll=4, block_threads=64)),
+             (1 << 31, 17, dict(first_wave=64))]
+    got = rl.rand_read_batch(region, items, B, W * I, I)
+    assert len(got) == len(items)
+    for it, g in zip(items, got):
+        kw = dict(it[2]) if len(it) > 2 else {}
+        one = rl.rand_read(region, B, W * I, I, it[1], region_bytes=it[0], **kw)
+        assert g.checksum == one.checksum, it
+        assert g.waves_run == one.waves_run and g.launches == 1
+        assert g.kernel_ms_event > 0
+        if "first_wave" not in kw:
+            assert g.checksum == oracle(it[0], B, W, I, read_seed=it[1]), it
+    # again, in another order and with other line shapes: nothing is left over from the first batch
+    for B2, lanes in ((256, 64), (512, 32)):
+        items2 = [(1 << 30, 21, dict(zone_bytes=1 << 29)), (1 << 29, 22), (1 << 30, 23)]
+        got2 = rl.rand_read_batch(region, items2, B2, W * I, I, lanes_per_line=lanes)
+        for it, g in zip(items2, got2):
+            assert g.checksum == oracle(it[0], B2, W, I, read_seed=it[1]), (B2, it)
+    assert rl.rand_read_batch(region, [], 128, W * I, I) == []
+    assert [r.checksum for r in rl.rand_read_batch(region, [(1 << 20, 1)] * 3, 128, 0, 7)] == [0, 0, 0]
+
+
+def test_batch_full_size(region, cu_table):
+    """The bench's step: the whole region-size sweep as one batch, the largest points zone by zone."""
+    cfgs = wl.region_sweep(region.numel(), len(cu_table))
+    c0 = cfgs[0]
+    items = [(c.region_bytes, c.read_seed) if c.region_bytes <= 96 * GiB else
+             (c.region_bytes, c.read_seed, dict(zone_bytes=96 * GiB)) for c in cfgs]
+    for rep in range(2):
+        got = rl.rand_read_batch(region, items, c0.line_bytes, c0.n_reads, c0.iters_per_wave)
+        for c, g in zip(cfgs, got):
+            assert g.checksum == oracle(c.region_bytes, c.line_bytes, c.logical_waves, c.iters_per_wave), (rep, c.name)
+            assert 0.5 < g.kernel_ms_event < 5.0
+
+
+def test_batch_rejects_what_it_cannot_do(region):
+    with pytest.raises(rl.RandlineError, match="at most 64"):
+        rl.rand_read_batch(region, [(1 << 20, 1)] * 65, 128, 64, 1)
+    with pytest.raises(rl.RandlineError):
+        rl.rand_read_batch(region, [(1 << 20, 1), (1 << 20 | 64, 2)], 128, 64, 1)   # second item's size is no multiple of a line
+    ticks = torch.zeros(64, dtype=torch.int64, device="cuda")
+    with pytest.raises(rl.RandlineError, match="not available in a batch"):
+        rl.rand_read_batch(region, [(3 << 24, 1, dict(zone_bytes=1 << 24, phase_ticks=ticks, mode=rl.MODE_FLAT))], 128, 64, 1)
+    assert rl.rand_read(region, 128, 640, 10, 5, region_bytes=1 << 20).checksum == oracle(1 << 20, 128, 64, 10, read_seed=5)
+
+
 def test_line_width_sweep_full_size(region):
     """2^30 reads per line shape at the largest region: the whole run must equal the sum of its
     16 wave sub-ranges (GPU), and sampled sub-ranges must equal the oracle."""

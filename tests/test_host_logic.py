@@ -33,7 +33,7 @@ def test_header_is_plain_c(tmp_path):
     inc = os.path.join(os.path.dirname(os.path.abspath(__file__)), "..", "include")
     b = rl.binding
     mirrors = {"rr_launch_opts_t": b._Opts, "rr_result_t": b._Result, "rr_window_map_t": b._WindowMap,
-               "rr_chase_result_t": b._ChaseResult}
+               "rr_chase_result_t": b._ChaseResult, "rr_read_item_t": b._ReadItem}
     prints = []
     for cname, mirror in mirrors.items():
         prints.append(f'printf("%zu\\n", sizeof({cname}));')
@@ -323,6 +323,37 @@ def test_out_left_untouched_on_failure():
     rc = rl.lib().rr_rand_read(1 << 21, 1000, 128, 32, 8, 8, None, 7, None, None, C.byref(res))
     assert rc == rl.RR_EINVAL and (res.checksum, res.waves_run, res.launches) == (123, 4, 5)
     assert rl.lib().rr_rand_read(1 << 21, 4096, 128, 32, 8, 8, None, 7, None, None, None) == rl.RR_EINVAL
+
+
+def test_batch_validation_comes_before_any_launch():
+    """Every item is checked, and out stays as it was, before the device is touched."""
+    fake = 1 << 21                                    # never dereferenced: all of these fail or do nothing on the host
+    with pytest.raises(rl.RandlineError, match="at most 64"):
+        rl.rand_read_batch(fake, [(4096, 1)] * 65, 128, 8, 8)
+    with pytest.raises(rl.RandlineError, match="line_bytes"):
+        rl.rand_read_batch(fake, [(4096, 1)], 100, 8, 8)
+    with pytest.raises(rl.RandlineError, match="multiple"):
+        rl.rand_read_batch(fake, [(4096, 1), (4096, 2), (1000, 3)], 128, 8, 8)
+    with pytest.raises(rl.RandlineError, match="not available in a batch"):
+        o = rl.binding._Opts()
+        o.cu_waves_out = (C.c_uint32 * 4)()
+        item = (rl.binding._ReadItem * 1)()
+        item[0].region_bytes, item[0].read_seed, item[0].opts = 4096, 1, C.pointer(o)
+        res = (rl.binding._Result * 1)()
+        rl.binding._check(rl.lib().rr_rand_read_batch(fake, item, 1, 128, 32, 8, 8, None, res))
+    res = (rl.binding._Result * 2)()
+    res[1].checksum = 99
+    items = (rl.binding._ReadItem * 2)()
+    items[0].region_bytes, items[1].region_bytes = 4096, 1000
+    assert rl.lib().rr_rand_read_batch(fake, items, 2, 128, 32, 8, 8, None, res) == rl.RR_EINVAL and res[1].checksum == 99
+    assert rl.lib().rr_rand_read_batch(fake, None, 2, 128, 32, 8, 8, None, res) == rl.RR_EINVAL
+    assert rl.lib().rr_rand_read_batch(fake, items, 1, 128, 32, 8, 8, None, None) == rl.RR_EINVAL
+    assert rl.lib().rr_rand_read_batch(fake, None, 0, 128, 32, 8, 8, None, None) == rl.RR_OK     # an empty batch
+    # nothing to read: every result is written (zeros) without a launch
+    res[0].checksum = res[1].checksum = 5
+    items[1].region_bytes = 4096
+    assert rl.lib().rr_rand_read_batch(fake, items, 2, 128, 32, 0, 8, None, res) == rl.RR_OK
+    assert (res[0].checksum, res[1].checksum, res[1].launches) == (0, 0, 0)
 
 
 # ------------------------------------------------------------------ heatmap clustering: library vs oracle
