@@ -34,7 +34,8 @@
  *     device are made before the first HIP call.
  *   - The library keeps about 320 KB of device scratch per GPU (result cells,
  *     ticket counters, timestamps, lookup tables), created on first use and
- *     released by rr_shutdown().
+ *     released by rr_shutdown(); the first rr_rand_read_batch call adds 17 MiB
+ *     (one set of cells and counters for each of the 64 launches a batch can hold).
  *   - Threads: any thread may call.  The calls that launch kernels share that
  *     scratch, so the library runs them one at a time (one lock); each waits for
  *     its own kernels before it returns and lets the next one in.
@@ -195,9 +196,10 @@ int rr_rand_read(const void *region, uint64_t region_bytes, uint32_t line_bytes,
  * Item i is the call rr_rand_read(region, items[i].region_bytes, line_bytes,
  * lanes_per_line, n_reads, iters_per_wave, NULL, items[i].read_seed, stream,
  * items[i].opts, &out[i]) and returns the same checksum; the difference is
- * that all kernels are queued on the stream back to back and the host waits
- * once, at the end, so the device does not idle between the launches while
- * the host fetches one result and prepares the next launch.
+ * that all read kernels are queued on the stream back to back (each with result
+ * cells and ticket counters of its own, so that nothing has to run between
+ * two of them) and the host waits once, at the end: the device does not idle
+ * while the host fetches one result and prepares the next launch.
  *   items     host [n_items]; opts may be NULL (defaults) and must not ask for
  *             placement_out, cu_waves_out or phase_ticks
  *   n_items   0 (nothing happens) to 64

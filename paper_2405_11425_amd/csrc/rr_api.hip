@@ -422,8 +422,12 @@ extern "C" int rr_rand_read_batch(const void *region, const rr_read_item_t *item
                            o, out, plans[i]);
         if (rc != RR_OK) return rc;
     }
-    memset(out, 0, n_items * sizeof(rr_result_t));
-    if (plans[0].W == 0) return RR_OK;  // nothing to read, in any item
+    std::vector<rr_result_t> results(n_items);  // out is written on success only
+    memset(results.data(), 0, n_items * sizeof(rr_result_t));
+    if (plans[0].W == 0) {  // nothing to read, in any item
+        memcpy(out, results.data(), n_items * sizeof(rr_result_t));
+        return RR_OK;
+    }
 
     hipStream_t stream = (hipStream_t)hip_stream;
     std::lock_guard<std::mutex> lock(g_mutex);
@@ -431,7 +435,6 @@ extern "C" int rr_rand_read_batch(const void *region, const rr_read_item_t *item
     int rc = get_state(stream, &stp);
     if (rc != RR_OK) return rc;
     DeviceState &st = *stp;
-    const u32 n_cus = (u32)st.cus.size();
     while (st.batch_ev.size() < 2 * (size_t)n_items) {
         hipEvent_t e = nullptr;
         HIP_TRY(hipEventCreate(&e));
@@ -449,31 +452,31 @@ extern "C" int rr_rand_read_batch(const void *region, const rr_read_item_t *item
                          launches[i]);
         if (rc != RR_OK) return rc;
     }
-    // queue everything, wait once
+    // Every launch has a scratch slot of its own, so the stream holds one reset (if anything needs one), the
+    // read kernels back to back, and one finish for all of them; then the host waits once.
+    std::vector<u32> tickets_per_unit(n_items), ticket_mode(n_items), reset_bits(n_items);
+    for (u32 i = 0; i < n_items; ++i) {
+        tickets_per_unit[i] = launches[i].tickets_per_unit;
+        ticket_mode[i] = launches[i].p.ticket_mode;
+        reset_bits[i] = launches[i].reset_bits;
+    }
+    BatchSlots slots;
+    rc = prepare_batch(st, n_items, tickets_per_unit.data(), ticket_mode.data(), reset_bits.data(), stream, slots);
+    if (rc != RR_OK) return rc;
     auto queue_all = [&]() -> int {
         for (u32 i = 0; i < n_items; ++i) {
             Launch &ln = launches[i];
-            const u32 what = (st.cells_clean ? 0u : 1u) | ln.reset_bits;
-            if (what) {
-                int r = launch_reset(st, what, stream);
-                if (r != RR_OK) return r;
-            }
-            st.cells_clean = false;
+            ln.p.scratch = st.batch_scratch + i;
             void *args[] = {(void *)&ln.p};
             HIP_TRY(hipEventRecord(st.batch_ev[2 * i], stream));
             HIP_TRY(hipLaunchKernel(ln.kernel, dim3(ln.grid), dim3(plans[i].block), args, 0, stream));
             HIP_TRY(hipEventRecord(st.batch_ev[2 * i + 1], stream));
-            int r = launch_finish(st, i, n_cus, ln.tickets_per_unit, ln.p.ticket_mode, stream);
-            if (r != RR_OK) return r;
-            st.cells_clean = true;  // in stream order; what follows is on the same stream
         }
-        HIP_TRY(hipStreamSynchronize(stream));
-        return RR_OK;
+        return finish_batch(st, n_items, slots, stream);
     };
     rc = queue_all();
     if (rc != RR_OK) {
-        (void)hipStreamSynchronize(stream);
-        st.cells_clean = false;
+        (void)hipStreamSynchronize(stream);  // the slots stay marked dirty
         return rc;
     }
     st.tables_valid = true;
@@ -482,15 +485,17 @@ extern "C" int rr_rand_read_batch(const void *region, const rr_read_item_t *item
         const ResultHead &h = st.head[i];
         float ms = 0.f;
         HIP_TRY(hipEventElapsedTime(&ms, st.batch_ev[2 * i], st.batch_ev[2 * i + 1]));
-        out[i].launches = 1;
-        out[i].kernel_ms_event = ms;
-        out[i].checksum = h.checksum;
-        out[i].waves_run = h.waves_run;
-        if (h.waves_run && h.t_max >= h.t_min) out[i].kernel_ms_device = (double)(h.t_max - h.t_min) / (double)st.wall_khz;
+        rr_result_t &r = results[i];
+        r.launches = 1;
+        r.kernel_ms_event = ms;
+        r.checksum = h.checksum;
+        r.waves_run = h.waves_run;
+        if (h.waves_run && h.t_max >= h.t_min) r.kernel_ms_device = (double)(h.t_max - h.t_min) / (double)st.wall_khz;
         if (launches[i].p.ticket_mode && h.unfinished)
             return fail(RR_EPLACE, "item %u: %u compute units' shares still have unclaimed tickets after its one launch",
                         i, h.unfinished);
     }
+    memcpy(out, results.data(), n_items * sizeof(rr_result_t));
     return RR_OK;
 }
 

@@ -24,6 +24,8 @@ int fail(int code, const char *fmt, ...);
 struct DeviceState {
     bool ready = false;
     Scratch *scratch = nullptr;
+    Scratch *batch_scratch = nullptr;  // [kMaxBatch], allocated by the first batched call
+    bool batch_dirty = false;          // a batch did not reach its finish: clear every slot's cells before the next
     Tables *tables = nullptr;       // device
     Tables *tables_host = nullptr;  // pinned staging copy
     Tables *tables_last = nullptr;  // what the device copy holds (plain host memory), to skip equal uploads
@@ -44,6 +46,13 @@ struct DeviceState {
 
 constexpr int kMaxDevices = 16;
 constexpr u32 kMaxBatch = 64;  // launches one batched call may queue before it waits
+
+// What the launches of a batch differ in, as far as their reset and finish are concerned (a kernel argument).
+struct BatchSlots {
+    u32 tickets_per_unit[kMaxBatch];
+    unsigned char ticket_mode[kMaxBatch];
+    unsigned char what[kMaxBatch];  // reset_kernel's bits
+};
 
 // One lock for everything below: device states, the piecewise regions, and every launch that uses the
 // per-device scratch (calls on one device are serialised).
@@ -67,10 +76,16 @@ inline Reducer make_reducer(u64 L) {
 int launch_reset(DeviceState &st, u32 what, hipStream_t stream);
 // Make sure the result cells are cleared before a kernel that adds into them (marks them used).
 int begin_cells(DeviceState &st, hipStream_t stream);
-// finish_kernel on `stream`: cells -> result head `slot` in mapped host memory, cells left cleared.
-int launch_finish(DeviceState &st, u32 slot, u32 n_cus, u32 tickets_per_unit, u32 ticket_mode, hipStream_t stream);
-// launch_finish into slot 0, then wait for the stream.
+// finish_kernel (cells -> result head 0 in mapped host memory, cells left cleared), then wait for the stream.
 int finish_and_wait(DeviceState &st, u32 n_cus, u32 tickets_per_unit, u32 ticket_mode, hipStream_t stream);
+
+// A batch of n launches (n <= kMaxBatch): launch i works on st.batch_scratch[i] and reports into st.head[i].
+// prepare_batch allocates the slots when first needed and clears in them what the launches need cleared
+// (reset_bits[i]: bit 1 ticket counters, bit 2 per-CU wave counts; result cells as far as they are not clear
+// already); finish_batch folds every slot into its result head and waits for the stream.
+int prepare_batch(DeviceState &st, u32 n, const u32 *tickets_per_unit, const u32 *ticket_mode, const u32 *reset_bits,
+                  hipStream_t stream, BatchSlots &b);
+int finish_batch(DeviceState &st, u32 n, const BatchSlots &b, hipStream_t stream);
 
 // Piecewise regions still alive (rr_region.hip); for rr_shutdown, g_mutex held.
 void release_all_regions();

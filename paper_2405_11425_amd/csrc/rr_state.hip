@@ -19,7 +19,7 @@ __global__ void __launch_bounds__(64) enumerate_kernel(Scratch *s, u32 naps) {
 }
 
 // what: bit 0 result cells; bit 1 ticket counters; bit 2 per-CU wave counts; bit 3 key marks
-__global__ void __launch_bounds__(256) reset_kernel(Scratch *s, u32 what) {
+__device__ __forceinline__ void reset_scratch(Scratch *s, u32 what) {
     const u32 t = threadIdx.x;
     if (what & 1u) {
         for (u32 i = t; i < kNumCells; i += blockDim.x) {
@@ -37,12 +37,19 @@ __global__ void __launch_bounds__(256) reset_kernel(Scratch *s, u32 what) {
         for (u32 i = t; i < kNumKeys; i += blockDim.x) s->key_seen[i] = 0;
 }
 
+__global__ void __launch_bounds__(256) reset_kernel(Scratch *s, u32 what) { reset_scratch(s, what); }
+
+// One workgroup per slot of a batch: slot b has its own scratch, slots[b].
+__global__ void __launch_bounds__(256) reset_batch_kernel(Scratch *slots, BatchSlots b) {
+    reset_scratch(&slots[blockIdx.x], b.what[blockIdx.x]);
+}
+
 // After a read launch (one block of kNumCells threads, one result cell each):
 // fold the cells into the result head (pinned host memory mapped into the
 // device, so no copy follows), leave them cleared for the next launch, and count
 // the compute units whose share of tickets has not been fully claimed.
-__global__ void __launch_bounds__(kNumCells) finish_kernel(Scratch *s, ResultHead *head, const Tables *tb,
-                                                           u32 n_cus, u32 cpw, u32 ticket_mode) {
+__device__ __forceinline__ void fold_cells(Scratch *s, ResultHead *head, const Tables *tb, u32 n_cus, u32 cpw,
+                                           u32 ticket_mode) {
     __shared__ u64 sh_sum[kNumCells], sh_min[kNumCells], sh_max[kNumCells];
     __shared__ u32 sh_waves[kNumCells], sh_open[kNumCells];
     const u32 t = threadIdx.x;
@@ -76,6 +83,18 @@ __global__ void __launch_bounds__(kNumCells) finish_kernel(Scratch *s, ResultHea
         head->waves_run = sh_waves[0];
         head->unfinished = sh_open[0];
     }
+}
+
+__global__ void __launch_bounds__(kNumCells) finish_kernel(Scratch *s, ResultHead *head, const Tables *tb,
+                                                           u32 n_cus, u32 cpw, u32 ticket_mode) {
+    fold_cells(s, head, tb, n_cus, cpw, ticket_mode);
+}
+
+// The same for every slot of a batch at once: workgroup b folds slots[b] into heads[b].
+__global__ void __launch_bounds__(kNumCells) finish_batch_kernel(Scratch *slots, ResultHead *heads, const Tables *tb,
+                                                                 u32 n_cus, BatchSlots b) {
+    const u32 i = blockIdx.x;
+    fold_cells(&slots[i], &heads[i], tb, n_cus, b.tickets_per_unit[i], b.ticket_mode[i]);
 }
 static_assert(kMaxCus <= kNumCells, "finish_kernel checks one compute unit per thread");
 
@@ -183,17 +202,50 @@ int begin_cells(DeviceState &st, hipStream_t stream) {
     return RR_OK;
 }
 
-int launch_finish(DeviceState &st, u32 slot, u32 n_cus, u32 tickets_per_unit, u32 ticket_mode, hipStream_t stream) {
-    if (slot >= kMaxBatch) return fail(RR_EINVAL, "result slot %u out of range", slot);
-    hipLaunchKernelGGL(finish_kernel, dim3(1), dim3(kNumCells), 0, stream, st.scratch, st.head_dev + slot, st.tables,
-                       n_cus, tickets_per_unit, ticket_mode);
+// Scratch for the launches of a batch, one per slot, so that nothing has to run between two read kernels;
+// allocated when the first batch arrives, cleared once, and left with clear cells by every finish.
+int prepare_batch(DeviceState &st, u32 n, const u32 *tickets_per_unit, const u32 *ticket_mode, const u32 *reset_bits,
+                  hipStream_t stream, BatchSlots &b) {
+    if (n == 0 || n > kMaxBatch) return fail(RR_EINVAL, "batch of %u launches is out of range", n);
+    bool fresh = false;
+    if (!st.batch_scratch) {
+        HIP_TRY(hipMalloc((void **)&st.batch_scratch, kMaxBatch * sizeof(Scratch)));
+        fresh = true;
+    }
+    memset(&b, 0, sizeof b);
+    bool any = false;
+    for (u32 i = 0; i < n; ++i) {
+        b.tickets_per_unit[i] = tickets_per_unit[i];
+        b.ticket_mode[i] = (unsigned char)ticket_mode[i];
+        b.what[i] = (unsigned char)(reset_bits[i] | ((fresh || st.batch_dirty) ? 1u : 0u));
+        any = any || b.what[i];
+    }
+    if (fresh || st.batch_dirty) {  // every slot, not only the ones of this batch
+        BatchSlots all = b;
+        for (u32 i = n; i < kMaxBatch; ++i) all.what[i] = 1u;
+        hipLaunchKernelGGL(reset_batch_kernel, dim3(kMaxBatch), dim3(256), 0, stream, st.batch_scratch, all);
+        HIP_TRY(hipGetLastError());
+    } else if (any) {
+        hipLaunchKernelGGL(reset_batch_kernel, dim3(n), dim3(256), 0, stream, st.batch_scratch, b);
+        HIP_TRY(hipGetLastError());
+    }
+    st.batch_dirty = true;  // until finish_batch has run and the stream has been waited for
+    return RR_OK;
+}
+
+int finish_batch(DeviceState &st, u32 n, const BatchSlots &b, hipStream_t stream) {
+    hipLaunchKernelGGL(finish_batch_kernel, dim3(n), dim3(kNumCells), 0, stream, st.batch_scratch, st.head_dev, st.tables,
+                       (u32)st.cus.size(), b);
     HIP_TRY(hipGetLastError());
+    HIP_TRY(hipStreamSynchronize(stream));
+    st.batch_dirty = false;
     return RR_OK;
 }
 
 int finish_and_wait(DeviceState &st, u32 n_cus, u32 tickets_per_unit, u32 ticket_mode, hipStream_t stream) {
-    int rc = launch_finish(st, 0, n_cus, tickets_per_unit, ticket_mode, stream);
-    if (rc != RR_OK) return rc;
+    hipLaunchKernelGGL(finish_kernel, dim3(1), dim3(kNumCells), 0, stream, st.scratch, st.head_dev, st.tables, n_cus,
+                       tickets_per_unit, ticket_mode);
+    HIP_TRY(hipGetLastError());
     HIP_TRY(hipStreamSynchronize(stream));
     st.cells_clean = true;
     return RR_OK;
@@ -240,6 +292,7 @@ extern "C" int rr_shutdown(void) {
         if (hipSetDevice(d) != hipSuccess) continue;
         (void)hipDeviceSynchronize();
         if (st.scratch) (void)hipFree(st.scratch);
+        if (st.batch_scratch) (void)hipFree(st.batch_scratch);
         if (st.tables) (void)hipFree(st.tables);
         if (st.tables_host) (void)hipHostFree(st.tables_host);
         delete st.tables_last;
