@@ -2,11 +2,19 @@
 
 The full pair matrix is the "zones" experiment of the sweep driver; this is the short form for
 callers that only want the map.  Two windows are read at the same time (even CUs one, odd CUs the
-other); a pair inside one zone runs several per cent faster than a pair across zones.  Windows are
-assigned greedily: the first unassigned window opens a zone and takes with it every window whose
-pair rate with it is within `tolerance` of the best one seen for that reference.  A second pass then
-pairs every window with one representative per zone and moves it to the zone it runs fastest with,
-which absorbs windows that a noisy measurement had left on their own.
+other); a pair inside one zone runs several per cent faster than a pair across zones (measured:
+4 % apart, single launches scatter by 0.5 % inside a zone and 0.8 % across, and on a busy box a good
+part of the launches is slower by up to 10 %: a pair's rate is therefore that of its second fastest
+launch of six, not the median).
+
+The decision is made against a fixed cut, not against the best rate seen.  A window paired with
+itself gives the rate of a pair that certainly shares a zone; the first row (window 0 with every
+other one) shows whether there is a slower cluster, and the cut goes halfway between the two (or,
+with no slower cluster, `min_gap` below the same-zone rate).  A rate close to the cut is measured
+again with three times the launches.  Windows are then assigned greedily (the first unassigned
+window opens a zone and takes every window that runs with it), zones whose first windows run
+together are merged, and every window gets a second opinion against the first window of its zone:
+one that fails it, or sits alone, moves to a zone whose first window it does run with.
 """
 import statistics
 from typing import List
@@ -17,8 +25,8 @@ from . import binding as rl
 from . import workloads as wl
 
 
-def detect_zone_map(region, region_bytes: int, n_cus: int, n_windows: int = 32, reps: int = 3,
-                    tolerance: float = 0.02, max_zones: int = 16, unroll: int = 8) -> List[int]:
+def detect_zone_map(region, region_bytes: int, n_cus: int, n_windows: int = 32, reps: int = 6,
+                    min_gap: float = 0.02, max_zones: int = 16, unroll: int = 8) -> List[int]:
     """zone_of_window[n_windows] for the first region_bytes of `region` (ids in order of first appearance).
     The probe launches use the ring-of-8 build of the read kernel by default, so that in a kernel trace they
     stay apart from a caller's own launches of the default (ring of 16) kernel."""
@@ -32,33 +40,60 @@ def detect_zone_map(region, region_bytes: int, n_cus: int, n_windows: int = 32, 
         wm = rl.WindowMap(n_windows, parity, np.array([a, b], np.uint16))
         call = lambda seed: rl.rand_read(region, 128, waves * iters, iters, seed, wm, region_bytes=region_bytes,
                                          unroll=unroll)
-        call(1000)
-        ms = statistics.median(call(wl.READ_SEED + i).kernel_ms_event for i in range(n))
-        return waves * iters * 128 / ms / 1e6
+        call(1000)                                     # the first launch with a new map is several per cent slower
+        ms = sorted(call(wl.READ_SEED + i).kernel_ms_event for i in range(n))
+        # What disturbs a launch makes it slower (on a busy box by up to 10 %, and often); launches faster than
+        # the rest by more than 1 % have not been seen.  The second fastest stands for the pair.
+        return waves * iters * 128 / ms[min(1, n - 1)] / 1e6
+
+    # the rate of a pair that certainly shares a zone: a window with itself
+    picks = sorted({0, n_windows // 3, 2 * n_windows // 3, n_windows - 1})
+    same = statistics.median(pair_rate(w, w) for w in picks)
+    # first row: window 0 with every other one; the rates fall into one or two clusters
+    row = {b: pair_rate(0, b) for b in range(1, n_windows)}
+    low = [r for r in row.values() if r < same * (1.0 - min_gap)]
+    if len(low) >= 2 and statistics.median(low) < same * (1.0 - 1.4 * min_gap):
+        cut = 0.5 * (same + statistics.median(low))    # two clusters: halfway between them
+        band = 0.25 * (same - cut)
+    else:                                              # nothing clearly slower so far
+        cut = same * (1.0 - min_gap)
+        band = 0.5 * min_gap * same
+
+    def together(a: int, b: int, first=None) -> bool:
+        r = pair_rate(a, b) if first is None else first
+        if abs(r - cut) < band:                        # too close to call: measure again, longer
+            r = pair_rate(a, b, 3 * reps)
+        return r >= cut
 
     zone = [-1] * n_windows
     n_zones = 0
     while -1 in zone:
-        if n_zones == max_zones:                      # no clear structure: give up, everything in one zone
+        if n_zones == max_zones:
             return [0] * n_windows
         ref = zone.index(-1)
         zone[ref] = n_zones
-        rates = {b: pair_rate(ref, b) for b in range(n_windows) if zone[b] == -1}
-        if rates:
-            best = max(max(rates.values()), pair_rate(ref, ref))
-            for b, r in rates.items():
-                if abs(r / best - (1.0 - tolerance)) < 0.5 * tolerance:     # too close to call: measure again, longer
-                    r = pair_rate(ref, b, 3 * reps)
-                if r >= (1.0 - tolerance) * best:
-                    zone[b] = n_zones
+        for b in range(n_windows):
+            if zone[b] == -1 and together(ref, b, row.get(b) if ref == 0 else None):
+                zone[b] = n_zones
         n_zones += 1
-    if n_zones > 1:
-        sizes = [zone.count(z) for z in range(n_zones)]
-        keep = [z for z in range(n_zones) if sizes[z] > 1] or list(range(n_zones))
-        reps_of = {z: zone.index(z) for z in keep}
-        for w in range(n_windows):
-            rates = {z: pair_rate(reps_of[z], w) for z in keep}
-            zone[w] = max(rates, key=rates.get)
-        order = {z: i for i, z in enumerate(dict.fromkeys(zone))}      # renumber by first appearance
-        zone = [order[z] for z in zone]
-    return zone
+    # zones whose first windows run together are one zone
+    firsts = [zone.index(z) for z in range(n_zones)]
+    merged = list(range(n_zones))
+    for a in range(n_zones):
+        for b in range(a + 1, n_zones):
+            if merged[b] == b and merged[a] == a and pair_rate(firsts[a], firsts[b], 3 * reps) >= cut:
+                merged[b] = a
+    zone = [merged[z] for z in zone]
+    # second opinion on every window: it must run together with the first window of its zone; one that does not, or
+    # that is alone, moves to a zone whose first window it does run with (if there is one)
+    for w in range(n_windows):
+        first = zone.index(zone[w])
+        alone = zone.count(zone[w]) == 1
+        if (first == w and not alone) or (first != w and together(first, w)):
+            continue
+        for z in sorted(set(zone) - {zone[w]}):
+            if zone.index(z) != w and pair_rate(zone.index(z), w, 3 * reps) >= cut:
+                zone[w] = z
+                break
+    order = {z: i for i, z in enumerate(dict.fromkeys(zone))}
+    return [order[z] for z in zone]

@@ -216,27 +216,36 @@ def test_chase_validation():
 ])
 def test_zone_probe_recovers_a_planted_map(monkeypatch, planted):
     """The zone probe's logic against a stand-in for the library: pairs of windows in one planted zone run 4 % faster
-    than pairs across zones, with 0.5 % noise and a few outliers; the probe must return the planted partition."""
+    than pairs across zones.  Two kinds of noise, both worse than measured on the GPU: launches that scatter by 0.8 %,
+    one in 50 of them 5 % slow and one in 100 2 % fast; and a busy box, where launches scatter by 0.6 % and every
+    third one is slower by 1-8 %.  The probe must return the planted partition for every noise stream."""
     from paper_2405_11425_amd import zonemap
-    rng = np.random.default_rng(11)
-    calls = {"n": 0}
+    for stream in range(24):
+        rng = np.random.default_rng(1000 + stream)
+        busy = stream % 2 == 1
 
-    def fake_read(region, line_bytes, n_reads, iters, seed, wm, region_bytes=None, **kw):
-        a, b = (int(x) for x in wm.window_of_group)
-        rate = 6800.0 if planted[a] == planted[b] else 6540.0
-        rate *= 1.0 + rng.normal(0.0, 0.005)
-        calls["n"] += 1
-        if calls["n"] % 97 == 0:
-            rate *= 0.93                                   # an occasional slow launch
-        return rl.ReadResult(0, n_reads * line_bytes / rate / 1e6, 0.0, 0, 1)
+        def fake_read(region, line_bytes, n_reads, iters, seed, wm, region_bytes=None, **kw):
+            a, b = (int(x) for x in wm.window_of_group)
+            rate = 6800.0 if planted[a] == planted[b] else 6540.0
+            if busy:
+                rate *= 1.0 + rng.normal(0.0, 0.006)
+                if rng.integers(3) == 0:
+                    rate *= 1.0 - rng.uniform(0.01, 0.08)
+            else:
+                rate *= 1.0 + rng.normal(0.0, 0.008)
+                if rng.integers(50) == 0:
+                    rate *= 0.95
+                if rng.integers(100) == 0:
+                    rate *= 1.02
+            return rl.ReadResult(0, n_reads * line_bytes / rate / 1e6, 0.0, 0, 1)
 
-    monkeypatch.setattr(zonemap.rl, "rand_read", fake_read)
-    got = zonemap.detect_zone_map(None, 256 << 30, 256)
-    relabel = {}
-    for g, p in zip(got, planted):
-        assert relabel.setdefault(g, p) == p               # every found zone lies inside one planted zone ...
-    assert len(relabel) == len(set(planted))               # ... and there are exactly as many
-    assert got[0] == 0 and all(z <= max(got[:i]) + 1 for i, z in enumerate(got) if i)
+        monkeypatch.setattr(zonemap.rl, "rand_read", fake_read)
+        got = zonemap.detect_zone_map(None, 256 << 30, 256)
+        relabel = {}
+        for g, p in zip(got, planted):
+            assert relabel.setdefault(g, p) == p, (stream, got)   # every found zone lies inside one planted zone ...
+        assert len(relabel) == len(set(planted)), (stream, got)   # ... and there are exactly as many
+        assert got[0] == 0 and all(z <= max(got[:i]) + 1 for i, z in enumerate(got) if i)
     with pytest.raises(ValueError):
         zonemap.detect_zone_map(None, (256 << 30) + 128, 256)
 
