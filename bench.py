@@ -126,9 +126,9 @@ def main():
                               "chosen": "zone-by-zone" if order[cfg.name] is not None else "plain"})
             zone_info = {"zone_of_window_8gib": zone_of_window, "regions_spanning_zones": tried,
                          "seconds_before_timing": round(time.perf_counter() - t0, 2)}
-        except rl.RandlineError as e:   # the sweep itself does not depend on this: go on in plain order, and say so
+        except Exception as e:   # the sweep itself does not depend on this: go on in plain order, and say so
             order = {cfg.name: None for cfg in configs}
-            zone_info = {"error": str(e)}
+            zone_info = {"error": f"{type(e).__name__}: {e}"}
 
     c0 = configs[0]   # the points differ in region size (and read order) only
 
