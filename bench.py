@@ -132,14 +132,17 @@ def main():
 
     c0 = configs[0]   # the points differ in region size (and read order) only
 
+    # the same calls as one by one, queued back to back with one wait at the end of the step; the arguments are
+    # marshalled once, a step only sets its seed
+    batch = rl.ReadBatch(region, [(cfg.region_bytes, 0, {"zone_of_window": order[cfg.name]} if order[cfg.name] is not None
+                                   else None) for cfg in configs],
+                         c0.line_bytes, c0.n_reads, c0.iters_per_wave, lanes_per_line=c0.lanes_per_line)
+
     def step(seed, record=None):
         if args.one_by_one:
             results = [read(cfg, seed, order[cfg.name]) for cfg in configs]
-        else:       # the same calls, queued back to back with one wait at the end of the step
-            items = [(cfg.region_bytes, seed, {"zone_of_window": order[cfg.name]} if order[cfg.name] is not None else None)
-                     for cfg in configs]
-            results = rl.rand_read_batch(region, items, c0.line_bytes, c0.n_reads, c0.iters_per_wave,
-                                         lanes_per_line=c0.lanes_per_line)
+        else:
+            results = batch.run(read_seed=seed)
         if record is not None:
             for cfg, r in zip(configs, results):
                 record.setdefault(cfg.name, []).append(r)

@@ -244,28 +244,45 @@ def rand_read(region, line_bytes: int, n_reads: int, iters_per_wave: int, read_s
                       int(res.launches), placement[:W] if placement is not None else None, cu_waves)
 
 
+class ReadBatch:
+    """The arguments of one rr_rand_read_batch call, marshalled once and reusable: a caller that repeats a series
+    of reads with new seeds (a benchmark step) pays for building the C structures only the first time.
+
+    items: one (region_bytes, read_seed) or (region_bytes, read_seed, launch options as a dict) per call."""
+
+    def __init__(self, region, items: Sequence, line_bytes: int, n_reads: int, iters_per_wave: int,
+                 lanes_per_line: int = 32):
+        self._ptr, _ = _region(region, 0)
+        self._n = len(items)
+        self._arr = (_ReadItem * max(self._n, 1))()
+        self._keep = []
+        for i, it in enumerate(items):
+            self._arr[i].region_bytes, self._arr[i].read_seed = int(it[0]), int(it[1])
+            launch = dict(it[2]) if len(it) > 2 and it[2] else None
+            if launch is not None:
+                o, _, _ = _opts(0, 1024, **launch)
+                self._keep.append(o)
+                self._arr[i].opts = C.pointer(o)
+        self._res = (_Result * max(self._n, 1))()
+        self._shape = (line_bytes, lanes_per_line, n_reads, iters_per_wave)
+        self._call = lib().rr_rand_read_batch
+
+    def run(self, read_seed: Optional[int] = None, stream=None):
+        """Queue the calls and wait once; with read_seed, every item uses that seed.  A list of ReadResult."""
+        if read_seed is not None:
+            for i in range(self._n):
+                self._arr[i].read_seed = read_seed
+        line_bytes, lanes, n_reads, iters = self._shape
+        _check(self._call(self._ptr, self._arr, self._n, line_bytes, lanes, n_reads, iters, _stream(stream), self._res))
+        return [ReadResult(int(r.checksum), r.kernel_ms_event, r.kernel_ms_device, int(r.waves_run), int(r.launches))
+                for r in self._res[:self._n]]
+
+
 def rand_read_batch(region, items: Sequence, line_bytes: int, n_reads: int, iters_per_wave: int,
                     lanes_per_line: int = 32, stream=None):
     """Several rand_read calls queued back to back with one wait at the end (see rr_rand_read_batch).
-
-    items: one (region_bytes, read_seed) or (region_bytes, read_seed, launch options as a dict) per call.
-    Returns a list of ReadResult, one per item."""
-    ptr, _ = _region(region, 0)
-    n = len(items)
-    arr = (_ReadItem * max(n, 1))()
-    keep = []
-    for i, it in enumerate(items):
-        nbytes, seed = int(it[0]), int(it[1])
-        launch = dict(it[2]) if len(it) > 2 and it[2] else None
-        arr[i].region_bytes, arr[i].read_seed = nbytes, seed
-        if launch is not None:
-            o, _, _ = _opts(0, 1024, **launch)
-            keep.append(o)
-            arr[i].opts = C.pointer(o)
-    res = (_Result * max(n, 1))()
-    _check(lib().rr_rand_read_batch(ptr, arr, n, line_bytes, lanes_per_line, n_reads, iters_per_wave, _stream(stream), res))
-    return [ReadResult(int(r.checksum), r.kernel_ms_event, r.kernel_ms_device, int(r.waves_run), int(r.launches))
-            for r in res[:n]]
+    Returns a list of ReadResult, one per item of ReadBatch's `items`."""
+    return ReadBatch(region, items, line_bytes, n_reads, iters_per_wave, lanes_per_line).run(stream=stream)
 
 
 def probe_cus(region, cus: Sequence[int], n_reads: int, iters_per_wave: int, read_seed: int,

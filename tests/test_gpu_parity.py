@@ -611,6 +611,11 @@ def test_batch_equals_single_calls(region):
         got2 = rl.rand_read_batch(region, items2, B2, W * I, I, lanes_per_line=lanes)
         for it, g in zip(items2, got2):
             assert g.checksum == oracle(it[0], B2, W, I, read_seed=it[1]), (B2, it)
+    # a prepared batch, run again with other seeds
+    prepared = rl.ReadBatch(region, [(1 << 30, 0), (1 << 29, 0, dict(zone_bytes=1 << 27))], 128, W * I, I)
+    for seed in (5, 6, 5):
+        for it_bytes, g in zip((1 << 30, 1 << 29), prepared.run(read_seed=seed)):
+            assert g.checksum == oracle(it_bytes, 128, W, I, read_seed=seed), seed
     assert rl.rand_read_batch(region, [], 128, W * I, I) == []
     assert [r.checksum for r in rl.rand_read_batch(region, [(1 << 20, 1)] * 3, 128, 0, 7)] == [0, 0, 0]
 
