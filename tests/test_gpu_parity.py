@@ -181,8 +181,10 @@ def test_calls_on_a_side_stream():
         wide = rl.rand_read(buf, 256, 33 * 7, 7, 9, region_bytes=R)        # stream=None -> torch's current stream
         seq = rl.seq_read(buf, R, stream=side)
         walk = rl.chase(buf, 128, 1, 3, 0xFFF, 500, region_bytes=R, stream=side)
+        both = rl.rand_read_batch(buf, [(R, 3), (R, 3, dict(mode=rl.MODE_TICKET))], 128, 64 * 100, 100, stream=side)
     side.synchronize()
     assert got.checksum == tick.checksum == orc.checksum(R, 128, 64, 100, 5, 3)
+    assert [r.checksum for r in both] == [got.checksum] * 2
     assert wide.checksum == orc.checksum(R, 256, 33, 7, 5, 9)
     assert seq.checksum == orc.sum_words(5, 0, R // 4)
     assert (walk.final_line, walk.word_sum) == orc.chase(R, 128, 5, 1, 3, 0xFFF, 500)
@@ -194,7 +196,7 @@ def test_concurrent_callers_are_serialised(region):
     device to one call at a time, so every call still returns its own exact checksum."""
     import threading
     R = 1 << 26
-    jobs = {0: (128, 96, 50, 11, rl.MODE_AUTO), 1: (256, 40, 77, 12, rl.MODE_TICKET)}
+    jobs = {0: (128, 96, 50, 11, rl.MODE_AUTO), 1: (256, 40, 77, 12, rl.MODE_TICKET), 2: (128, 64, 31, 13, "batch")}
     want = {k: orc.checksum(R, B, W, I, wl.FILL_SEED, seed) for k, (B, W, I, seed, _) in jobs.items()}
     bad = []
 
@@ -202,6 +204,12 @@ def test_concurrent_callers_are_serialised(region):
         B, W, I, seed, mode = jobs[k]
         stream = torch.cuda.Stream()
         for _ in range(40):
+            if mode == "batch":     # three launches per call, one of them ticketed, on scratch slots of their own
+                got = rl.rand_read_batch(region, [(R, seed), (R, seed, dict(mode=rl.MODE_TICKET)), (R, seed)], B, W * I, I,
+                                         stream=stream)
+                if [g.checksum for g in got] != [want[k]] * 3:
+                    bad.append((k, [g.checksum for g in got]))
+                continue
             got = rl.rand_read(region, B, W * I, I, seed, region_bytes=R, stream=stream, mode=mode)
             if got.checksum != want[k]:
                 bad.append((k, got.checksum))
