@@ -103,7 +103,8 @@ def main():
             t0 = time.perf_counter()
             whole = (max_gib // 32) * 32 * GiB
             win = whole // 32
-            zone_of_window = zonemap.detect_zone_map(region, whole, n_cus)
+            probe = {}
+            zone_of_window = zonemap.detect_zone_map(region, whole, n_cus, details=probe)
             tried = []
             for cfg in configs:
                 if cfg.region_bytes > whole or cfg.region_bytes % win != 0:
@@ -124,7 +125,7 @@ def main():
                 tried.append({"region_gib": cfg.region_bytes // GiB, "zones": len(ids), "gbps_plain": rate["plain"],
                               "gbps_zone_by_zone": rate["zone-by-zone"],
                               "chosen": "zone-by-zone" if order[cfg.name] is not None else "plain"})
-            zone_info = {"zone_of_window_8gib": zone_of_window, "regions_spanning_zones": tried,
+            zone_info = {"zone_of_window_8gib": zone_of_window, "probe": probe, "regions_spanning_zones": tried,
                          "seconds_before_timing": round(time.perf_counter() - t0, 2)}
         except Exception as e:   # the sweep itself does not depend on this: go on in plain order, and say so
             order = {cfg.name: None for cfg in configs}

@@ -82,7 +82,10 @@ typedef struct {
 
 typedef struct {
     uint64_t checksum;       /* see top of file                                             */
-    double kernel_ms_event;  /* HIP-event time around the read kernel launch(es)            */
+    double kernel_ms_event;  /* HIP-event time of the read kernel launch(es): events recorded
+                                on the stream before and after the launch; in a batch, events
+                                that take the start and the end of the dispatch itself
+                                (about 2 us less)                                           */
     double kernel_ms_device; /* in-kernel constant-clock time, first working wave's start to
                                 last working wave's end (excludes draining idle workgroups) */
     uint32_t waves_run;      /* hardware wavefronts that executed at least one logical wave */

@@ -8,6 +8,8 @@
 #include <utility>
 #include <vector>
 
+#include <hip/hip_ext.h>
+
 #include "rr_host.hpp"
 #include "rr_phased_kernel.hpp"
 #include "rr_update_kernel.hpp"
@@ -359,6 +361,7 @@ int run_plan(const Plan &pl, const void *region, uint32_t iters, const rr_window
     const int max_launches = p.ticket_mode ? 32 : 1;
     void *args[] = {(void *)&ln.p};
     for (int launch = 0;; ++launch) {
+        // (events attached to the dispatch, as in a batch, cost a single call 17 us more on the host)
         HIP_TRY(hipEventRecord(st.ev0, stream));
         HIP_TRY(hipLaunchKernel(ln.kernel, dim3(ln.grid), dim3(pl.block), args, 0, stream));
         HIP_TRY(hipEventRecord(st.ev1, stream));
@@ -468,9 +471,10 @@ extern "C" int rr_rand_read_batch(const void *region, const rr_read_item_t *item
             Launch &ln = launches[i];
             ln.p.scratch = st.batch_scratch + i;
             void *args[] = {(void *)&ln.p};
-            HIP_TRY(hipEventRecord(st.batch_ev[2 * i], stream));
-            HIP_TRY(hipLaunchKernel(ln.kernel, dim3(ln.grid), dim3(plans[i].block), args, 0, stream));
-            HIP_TRY(hipEventRecord(st.batch_ev[2 * i + 1], stream));
+            // the two events take the start and the end time of this dispatch itself: no marker packets between
+            // one read kernel and the next (the host work this costs, 17 us a launch, runs ahead of the device here)
+            HIP_TRY(hipExtLaunchKernel(ln.kernel, dim3(ln.grid), dim3(plans[i].block), args, 0, stream,
+                                       st.batch_ev[2 * i], st.batch_ev[2 * i + 1], 0));
         }
         return finish_batch(st, n_items, slots, stream);
     };

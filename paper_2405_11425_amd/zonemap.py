@@ -17,7 +17,7 @@ together are merged, and every window gets a second opinion against the first wi
 one that fails it, or sits alone, moves to a zone whose first window it does run with.
 """
 import statistics
-from typing import List
+from typing import List, Optional
 
 import numpy as np
 
@@ -26,10 +26,12 @@ from . import workloads as wl
 
 
 def detect_zone_map(region, region_bytes: int, n_cus: int, n_windows: int = 32, reps: int = 6,
-                    min_gap: float = 0.02, max_zones: int = 16, unroll: int = 8) -> List[int]:
+                    min_gap: float = 0.02, max_zones: int = 16, unroll: int = 8,
+                    details: Optional[dict] = None) -> List[int]:
     """zone_of_window[n_windows] for the first region_bytes of `region` (ids in order of first appearance).
     The probe launches use the ring-of-8 build of the read kernel by default, so that in a kernel trace they
-    stay apart from a caller's own launches of the default (ring of 16) kernel."""
+    stay apart from a caller's own launches of the default (ring of 16) kernel.  `details`, if given, receives
+    what the decision rests on: the same-zone rate, the cut, the first row of pair rates, the zones before merging."""
     if region_bytes % (n_windows * 128) != 0:
         raise ValueError("region_bytes must be a multiple of n_windows lines")
     waves = wl.resident_logical_waves(n_cus)
@@ -59,6 +61,10 @@ def detect_zone_map(region, region_bytes: int, n_cus: int, n_windows: int = 32, 
         cut = same * (1.0 - min_gap)
         band = 0.5 * min_gap * same
 
+    if details is not None:
+        details.update(gbps_same_zone=round(same, 1), gbps_cut=round(cut, 1), gbps_retest_band=round(band, 1),
+                       gbps_window0_with=[round(row[b], 1) for b in range(1, n_windows)])
+
     def together(a: int, b: int, first=None) -> bool:
         r = pair_rate(a, b) if first is None else first
         if abs(r - cut) < band:                        # too close to call: measure again, longer
@@ -69,6 +75,8 @@ def detect_zone_map(region, region_bytes: int, n_cus: int, n_windows: int = 32, 
     n_zones = 0
     while -1 in zone:
         if n_zones == max_zones:
+            if details is not None:
+                details.update(gave_up_with=list(zone))
             return [0] * n_windows
         ref = zone.index(-1)
         zone[ref] = n_zones
@@ -76,6 +84,8 @@ def detect_zone_map(region, region_bytes: int, n_cus: int, n_windows: int = 32, 
             if zone[b] == -1 and together(ref, b, row.get(b) if ref == 0 else None):
                 zone[b] = n_zones
         n_zones += 1
+    if details is not None:
+        details.update(zones_before_merging=list(zone))
     # zones whose first windows run together are one zone
     firsts = [zone.index(z) for z in range(n_zones)]
     merged = list(range(n_zones))
