@@ -4,8 +4,8 @@ The full pair matrix is the "zones" experiment of the sweep driver; this is the 
 callers that only want the map.  Two windows are read at the same time (even CUs one, odd CUs the
 other); a pair inside one zone runs several per cent faster than a pair across zones (measured:
 4 % apart, single launches scatter by 0.5 % inside a zone and 0.8 % across, and on a busy box a good
-part of the launches is slower by up to 10 %: a pair's rate is therefore that of its second fastest
-launch of six, not the median).
+part of the launches is slower by up to 10 %: a pair's rate is therefore the upper quartile of its
+launches, the second fastest of six, not the median).
 
 The decision is made against a fixed cut, not against the best rate seen.  A window paired with
 itself gives the rate of a pair that certainly shares a zone; the first row (window 0 with every
@@ -26,7 +26,7 @@ from . import workloads as wl
 
 
 def detect_zone_map(region, region_bytes: int, n_cus: int, n_windows: int = 32, reps: int = 6,
-                    min_gap: float = 0.02, max_zones: int = 16, unroll: int = 8,
+                    min_gap: float = 0.02, max_zones: int = 16, unroll: int = 8, warmup: int = 64,
                     details: Optional[dict] = None) -> List[int]:
     """zone_of_window[n_windows] for the first region_bytes of `region` (ids in order of first appearance).
     The probe launches use the ring-of-8 build of the read kernel by default, so that in a kernel trace they
@@ -45,14 +45,21 @@ def detect_zone_map(region, region_bytes: int, n_cus: int, n_windows: int = 32, 
         call(1000)                                     # the first launch with a new map is several per cent slower
         ms = sorted(call(wl.READ_SEED + i).kernel_ms_event for i in range(n))
         # What disturbs a launch makes it slower (on a busy box by up to 10 %, and often); launches faster than
-        # the rest by more than 1 % have not been seen.  The second fastest stands for the pair.
-        return waves * iters * 128 / ms[min(1, n - 1)] / 1e6
+        # the rest by more than 1 % have not been seen.  The upper quartile stands for the pair: the second
+        # fastest of six launches, the fifth fastest of eighteen.
+        return waves * iters * 128 / ms[n // 4] / 1e6
 
+    # The first launches of a process can run 2-3 % slow for some tens of milliseconds (seen: the first 50): a
+    # warm-up, and the anchor below is measured before and after the first row, the faster of the two counts.
+    for i in range(warmup):
+        rl.rand_read(region, 128, waves * iters, iters, 2000 + i, rl.WindowMap(n_windows, parity, np.array([0, 0], np.uint16)),
+                     region_bytes=region_bytes, unroll=unroll)
     # the rate of a pair that certainly shares a zone: a window with itself
     picks = sorted({0, n_windows // 3, 2 * n_windows // 3, n_windows - 1})
-    same = statistics.median(pair_rate(w, w) for w in picks)
+    before = statistics.median(pair_rate(w, w) for w in picks)
     # first row: window 0 with every other one; the rates fall into one or two clusters
     row = {b: pair_rate(0, b) for b in range(1, n_windows)}
+    same = max(before, statistics.median(pair_rate(w, w) for w in picks))
     low = [r for r in row.values() if r < same * (1.0 - min_gap)]
     if len(low) >= 2 and statistics.median(low) < same * (1.0 - 1.4 * min_gap):
         cut = 0.5 * (same + statistics.median(low))    # two clusters: halfway between them
