@@ -229,7 +229,11 @@ int rr_rand_read_batch(const void *region, const rr_read_item_t *items, uint32_t
  * grid is launched; workgroups that land elsewhere exit at once, the others
  * claim logical waves until none are left.  The checksum does not depend on
  * the pair.  rr_probe_cus is the same for an arbitrary non-empty set of CUs
- * (one CU alone; a whole group, Sec. 2.3).
+ * (one CU alone; a whole group, Sec. 2.3).  Zone-phased reads and flat mode
+ * are refused (RR_EINVAL).  RR_EPLACE: a target CU whose share of the work is
+ * at least 32 tickets (one per wave slot; a ticket is 1024 iterations of a pair
+ * of logical waves by default) executed none of it, so the time measured is
+ * not that of the whole set.
  */
 int rr_probe_pair(const void *region, uint64_t region_bytes, uint32_t cu_a, uint32_t cu_b,
                   uint64_t n_reads, uint32_t iters_per_wave, uint64_t read_seed, void *hip_stream,

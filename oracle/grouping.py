@@ -38,6 +38,13 @@ def groups_from_heatmap(T: np.ndarray, singles: Optional[np.ndarray] = None,
     pairs = [(a, b) for a in range(n) for b in range(a + 1, n)]
     if not pairs:
         return np.zeros(n, dtype=np.int64), np.arange(n, dtype=np.int64), float("nan")
+    # the rule is defined for ordinary throughputs only: finite, not negative, not all zero, singles positive
+    if any(not np.isfinite(T[a, b]) or T[a, b] < 0 for a, b in pairs):
+        raise ValueError("pair throughputs must be finite and non-negative")
+    if singles is not None and any(not np.isfinite(x) or not x > 0 for x in np.asarray(singles, dtype=np.float64)):
+        raise ValueError("single-unit throughputs must be finite and positive")
+    if singles is None and not max(T[a, b] for a, b in pairs) > 0:
+        raise ValueError("every pair throughput is zero")
     if singles is not None:
         S = np.asarray(singles, dtype=np.float64)
         r = np.array([T[a, b] / (S[a] + S[b]) for a, b in pairs], dtype=np.float64)

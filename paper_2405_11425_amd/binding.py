@@ -228,20 +228,25 @@ def fill(region, fill_seed: int, region_bytes: Optional[int] = None, stream=None
     _check(lib().rr_fill(ptr, nbytes, fill_seed, _stream(stream)))
 
 
-def rand_read(region, line_bytes: int, n_reads: int, iters_per_wave: int, read_seed: int,
-              window_map: Optional[WindowMap] = None, lanes_per_line: int = 32,
-              region_bytes: Optional[int] = None, stream=None, want_placement: bool = False,
-              want_cu_waves: bool = False, **launch) -> ReadResult:
+def _rand_read(entry, region, line_bytes, n_reads, iters_per_wave, read_seed, window_map, lanes_per_line,
+               region_bytes, stream, want_placement, want_cu_waves, launch) -> ReadResult:
     ptr, nbytes = _region(region, region_bytes)
     W = n_reads // iters_per_wave if iters_per_wave else 0
     o, placement, cu_waves = _opts(W, 1024, want_placement=want_placement, want_cu_waves=want_cu_waves, **launch)
     res = _Result()
     wm = window_map._c() if window_map is not None else None
-    _check(lib().rr_rand_read(ptr, nbytes, line_bytes, lanes_per_line, n_reads, iters_per_wave,
-                              C.byref(wm) if wm is not None else None, read_seed, _stream(stream),
-                              C.byref(o), C.byref(res)))
+    _check(entry(ptr, nbytes, line_bytes, lanes_per_line, n_reads, iters_per_wave,
+                 C.byref(wm) if wm is not None else None, read_seed, _stream(stream), C.byref(o), C.byref(res)))
     return ReadResult(int(res.checksum), res.kernel_ms_event, res.kernel_ms_device, int(res.waves_run),
                       int(res.launches), placement[:W] if placement is not None else None, cu_waves)
+
+
+def rand_read(region, line_bytes: int, n_reads: int, iters_per_wave: int, read_seed: int,
+              window_map: Optional[WindowMap] = None, lanes_per_line: int = 32,
+              region_bytes: Optional[int] = None, stream=None, want_placement: bool = False,
+              want_cu_waves: bool = False, **launch) -> ReadResult:
+    return _rand_read(lib().rr_rand_read, region, line_bytes, n_reads, iters_per_wave, read_seed, window_map,
+                      lanes_per_line, region_bytes, stream, want_placement, want_cu_waves, launch)
 
 
 class ReadBatch:
@@ -414,8 +419,7 @@ def groups_from_heatmap(T: np.ndarray, singles: Optional[np.ndarray] = None, min
     rc = lib().rr_groups_from_heatmap(T.ctypes.data_as(C.POINTER(C.c_double)), n, s_ptr, min_gap,
                                       group.ctypes.data_as(C.POINTER(C.c_uint16)),
                                       order.ctypes.data_as(C.POINTER(C.c_uint32)), C.byref(ng), C.byref(thr))
-    if rc != RR_OK:
-        raise RandlineError(rc, lib().rr_strerror(rc).decode())
+    _check(rc)
     return group, order, float(thr.value)
 
 

@@ -4,8 +4,6 @@
 // rr_phased_kernel.hpp and rr_update_kernel.hpp and are instantiated in the rr_inst_*.hip files.
 #include <algorithm>
 #include <cstring>
-#include <map>
-#include <utility>
 #include <vector>
 
 #include <hip/hip_ext.h>
@@ -177,16 +175,20 @@ int make_plan(const void *region, uint64_t region_bytes, uint32_t line_bytes, ui
 // Workgroups of `block` threads of this kernel that one CU holds at a time, as the runtime computes it from the
 // kernel's registers and LDS (the 8-per-SIMD wave limit if it cannot say).  Cached per (kernel, block).
 u32 resident_blocks_per_cu(kernel_handle kernel, u32 block) {
-    static std::map<std::pair<kernel_handle, u32>, u32> cache;  // guarded by g_mutex (run_plan holds it)
-    auto key = std::make_pair(kernel, block);
-    auto it = cache.find(key);
-    if (it != cache.end()) return it->second;
+    struct Entry {
+        kernel_handle kernel;
+        u32 block, blocks;
+    };
+    static Entry cache[256];  // guarded by g_mutex (run_plan holds it); a fixed table, so that a lookup allocates nothing
+    static u32 n_cached = 0;
+    for (u32 i = 0; i < n_cached; ++i)
+        if (cache[i].kernel == kernel && cache[i].block == block) return cache[i].blocks;
     int n = 0;
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel, (int)block, 0) != hipSuccess || n <= 0) {
         (void)hipGetLastError();
         n = (int)(32 / (block / 64));
     }
-    cache[key] = (u32)n;
+    if (n_cached < 256) cache[n_cached++] = Entry{kernel, block, (u32)n};
     return (u32)n;
 }
 
@@ -195,14 +197,14 @@ u32 resident_blocks_per_cu(kernel_handle kernel, u32 block) {
 // from what the device already holds.
 int prepare_tables(DeviceState &st, const Plan &pl, const rr_window_map_t *wm, u64 units, u64 L_win,
                    hipStream_t stream) {
-    const u32 n_cus = (u32)st.cus.size();
+    const u32 n_cus = st.n_cus;
     Tables &tb = *st.tables_host;
     memset(&tb, 0, sizeof tb);
     for (u32 k = 0; k < kNumKeys; ++k) {
         tb.group_of_key[k] = kExcluded;
         tb.dense_of_key[k] = st.dense_of_key_host[k];
     }
-    std::vector<u32> cus_in_group(pl.G, 0);
+    u32 cus_in_group[kMaxGroups] = {}, fill_pos[kMaxGroups] = {};
     for (u32 c = 0; c < n_cus; ++c) {
         const u16 g = wm ? wm->group_of_cu[c] : 0;
         tb.group_of_key[key_of(st.cus[c])] = g;
@@ -213,7 +215,6 @@ int prepare_tables(DeviceState &st, const Plan &pl, const rr_window_map_t *wm, u
         tb.window_base[g] = wm ? (u32)(wm->window_of_group[g] * L_win) : 0u;
         tb.group_begin[g + 1] = tb.group_begin[g] + cus_in_group[g];
     }
-    std::vector<u32> fill_pos(pl.G, 0);
     for (u32 c = 0; c < n_cus; ++c) {  // ascending dense id within each group
         const u16 g = wm ? wm->group_of_cu[c] : 0;
         if (g == kExcluded) continue;
@@ -244,7 +245,7 @@ struct Launch {
 
 int make_launch(const Plan &pl, DeviceState &st, const void *region, uint32_t iters, bool has_map, uint64_t read_seed,
                 const rr_launch_opts_t *opts, u16 *placement, Launch &ln) {
-    const u32 n_cus = (u32)st.cus.size();
+    const u32 n_cus = st.n_cus;
     const u32 lpw = 64 / pl.lanes;
     const u64 L_win = pl.n_lines / pl.n_windows;
     const u64 quota = pl.W / pl.G;
@@ -308,20 +309,14 @@ int make_launch(const Plan &pl, DeviceState &st, const void *region, uint32_t it
     return RR_OK;
 }
 
-int run_plan(const Plan &pl, const void *region, uint32_t iters, const rr_window_map_t *wm,
-             uint64_t read_seed, hipStream_t stream, const rr_launch_opts_t *opts, rr_result_t *out) {
+// ------------------------------------------------------------------ the launch loop
+
+int run_plan_locked(DeviceState &st, const Plan &pl, const void *region, uint32_t iters, const rr_window_map_t *wm,
+                    uint64_t read_seed, hipStream_t stream, const rr_launch_opts_t *opts, rr_result_t *out) {
     rr_result_t res;
     memset(&res, 0, sizeof res);
-    if (pl.W == 0) {  // nothing to read
-        *out = res;
-        return RR_OK;
-    }
-    std::lock_guard<std::mutex> lock(g_mutex);
-    DeviceState *stp = nullptr;
-    int rc = get_state(stream, &stp);
-    if (rc != RR_OK) return rc;
-    DeviceState &st = *stp;
-    const u32 n_cus = (u32)st.cus.size();
+    int rc;
+    const u32 n_cus = st.n_cus;
     if (wm && wm->n_cus != n_cus)
         return fail(RR_EINVAL, "window map describes %u compute units, the device has %u", wm->n_cus, n_cus);
 
@@ -344,7 +339,10 @@ int run_plan(const Plan &pl, const void *region, uint32_t iters, const rr_window
         HIP_TRY(hipMalloc((void **)&st.placement, pl.W * sizeof(u16)));
         st.placement_cap = pl.W;
     }
-    if (want_placement) HIP_TRY(hipMemsetAsync(st.placement, 0xFF, pl.W * sizeof(u16), stream));
+    if (want_placement) {  // every entry "not executed" (a fill kernel: a memset node is not safe to capture)
+        rc = launch_fill_u16(st.placement, pl.W, 0xFFFFu, stream);
+        if (rc != RR_OK) return rc;
+    }
 
     Launch ln;
     rc = make_launch(pl, st, region, iters, wm != nullptr, read_seed, opts, want_placement ? st.placement : nullptr, ln);
@@ -362,15 +360,15 @@ int run_plan(const Plan &pl, const void *region, uint32_t iters, const rr_window
     void *args[] = {(void *)&ln.p};
     for (int launch = 0;; ++launch) {
         // (events attached to the dispatch, as in a batch, cost a single call 17 us more on the host)
-        HIP_TRY(hipEventRecord(st.ev0, stream));
+        if (st.ev0) HIP_TRY(hipEventRecord(st.ev0, stream));
         HIP_TRY(hipLaunchKernel(ln.kernel, dim3(ln.grid), dim3(pl.block), args, 0, stream));
-        HIP_TRY(hipEventRecord(st.ev1, stream));
+        if (st.ev1) HIP_TRY(hipEventRecord(st.ev1, stream));
         rc = finish_and_wait(st, n_cus, ln.tickets_per_unit, p.ticket_mode, stream);
         if (rc != RR_OK) return rc;
         st.tables_valid = true;
         if (flat_no_map) st.flat_tables_ready = true;
         float ms = 0.f;
-        HIP_TRY(hipEventElapsedTime(&ms, st.ev0, st.ev1));
+        if (st.ev0 && st.ev1) HIP_TRY(hipEventElapsedTime(&ms, st.ev0, st.ev1));
         res.launches++;
         res.kernel_ms_event += ms;
         res.checksum += st.head->checksum;
@@ -386,13 +384,38 @@ int run_plan(const Plan &pl, const void *region, uint32_t iters, const rr_window
         HIP_TRY(hipMemcpyAsync(opts->placement_out, st.placement, pl.W * sizeof(u16), hipMemcpyDeviceToHost, stream));
         HIP_TRY(hipStreamSynchronize(stream));
     }
-    if (want_cu_waves) {
+    if (want_cu_waves || pl.pinned) {
         HIP_TRY(hipMemcpyAsync(st.cu_waves_host, st.scratch->cu_waves, n_cus * sizeof(u32), hipMemcpyDeviceToHost, stream));
         HIP_TRY(hipStreamSynchronize(stream));
-        memcpy(opts->cu_waves_out, st.cu_waves_host, n_cus * sizeof(u32));
+        if (want_cu_waves) memcpy(opts->cu_waves_out, st.cu_waves_host, n_cus * sizeof(u32));
+    }
+    if (pl.pinned && wm) {
+        // A pinned run measures its target compute units together: if one of them executed nothing (the others
+        // stole its share) the figure would be that of a smaller set.  Only shares of at least one ticket per wave
+        // slot of a CU are checked: the others' waves start to steal when their own share is drained, which takes
+        // them at least one whole ticket then, far longer than the dispatcher needs to reach every CU; a smaller
+        // share can be gone before its CU's first wave arrives without anything being wrong.
+        const Tables &tb = *st.tables_host;
+        for (u32 c = 0; c < n_cus; ++c)
+            if (wm->group_of_cu[c] != RR_CU_EXCLUDED && (u64)tb.cu_unit_count[c] * ln.tickets_per_unit >= 32 &&
+                st.cu_waves_host[c] == 0)
+                return fail(RR_EPLACE, "target compute unit %u executed none of the work (no resident wave in time)", c);
     }
     *out = res;
     return RR_OK;
+}
+
+int run_plan(const Plan &pl, const void *region, uint32_t iters, const rr_window_map_t *wm, uint64_t read_seed,
+             hipStream_t stream, const rr_launch_opts_t *opts, rr_result_t *out) {
+    if (pl.W == 0) {  // nothing to read
+        memset(out, 0, sizeof *out);
+        return RR_OK;
+    }
+    std::lock_guard<std::mutex> lock(g_mutex);
+    DeviceState *st = nullptr;
+    int rc = get_state(stream, &st);
+    if (rc != RR_OK) return rc;
+    return run_plan_locked(*st, pl, region, iters, wm, read_seed, stream, opts, out);
 }
 
 }  // namespace
@@ -512,6 +535,9 @@ extern "C" int rr_probe_cus(const void *region, uint64_t region_bytes, const uin
         for (u32 b = a + 1; b < n_target; ++b)
             if (cus[a] == cus[b]) return fail(RR_EINVAL, "compute unit %u is named twice", cus[a]);
     if (opts && opts->mode == RR_MODE_FLAT) return fail(RR_EINVAL, "a pinned run cannot use flat mode");
+    // the zone-phased kernel knows no excluded compute units: its waves would run everywhere and steal the targets' work
+    if (opts && (opts->zone_bytes || opts->zone_of_window || opts->phase_ticks))
+        return fail(RR_EINVAL, "a pinned run cannot be zone-phased");
     // validate everything else before touching the device (map filled in below)
     Plan pl;
     int rc = make_plan(region, region_bytes, 128, 32, n_reads, iters_per_wave, nullptr, opts, out, pl);
@@ -522,7 +548,7 @@ extern "C" int rr_probe_cus(const void *region, uint64_t region_bytes, const uin
         DeviceState *st = nullptr;
         rc = get_state((hipStream_t)hip_stream, &st);
         if (rc != RR_OK) return rc;
-        n_cus = (u32)st->cus.size();
+        n_cus = st->n_cus;
     }
     std::vector<uint16_t> group_of_cu(n_cus, RR_CU_EXCLUDED);
     for (u32 a = 0; a < n_target; ++a) {

@@ -163,7 +163,7 @@ extern "C" int rr_seq_read(const void *region, uint64_t region_bytes, void *hip_
     if (rc != RR_OK) return rc;
     const u64 n_vec = region_bytes / 16;
     u64 blocks = (n_vec + 255) / 256;
-    const u64 cap = 16ull * st->cus.size();  // two rounds of resident workgroups; each wave loops over its chunks
+    const u64 cap = 16ull * st->n_cus;  // two rounds of resident workgroups; each wave loops over its chunks
     if (blocks > cap) blocks = cap;
     // Regions that may span several memory zones (more than 96 GiB) are swept front to back in blocks of 2 MiB
     // from one counter: 6.82 / 6.91 / 6.89 TB/s over 128 / 192 / 256 GiB against 6.77 / 6.75 / 6.48 with the static
@@ -238,8 +238,10 @@ extern "C" int rr_copy(void *dst, const void *src, uint64_t bytes, void *hip_str
         return fail(RR_EINVAL, "dst, src and bytes must be multiples of 16");
     const uintptr_t d = (uintptr_t)dst, c = (uintptr_t)src;
     if (d < c + bytes && c < d + bytes && bytes > 0) return fail(RR_EINVAL, "dst and src overlap");
-    if (kernel_ms) *kernel_ms = 0.0;
-    if (bytes == 0) return RR_OK;
+    if (bytes == 0) {
+        if (kernel_ms) *kernel_ms = 0.0;
+        return RR_OK;
+    }
     hipStream_t stream = (hipStream_t)hip_stream;
     std::lock_guard<std::mutex> lock(g_mutex);
     DeviceState *st = nullptr;
@@ -247,7 +249,7 @@ extern "C" int rr_copy(void *dst, const void *src, uint64_t bytes, void *hip_str
     if (rc != RR_OK) return rc;
     const u64 n_vec = bytes / 16;
     u64 blocks = (n_vec + 255) / 256;
-    const u64 cap = (u64)st->cus.size() * 8;
+    const u64 cap = (u64)st->n_cus * 8;
     if (blocks > cap) blocks = cap;
     HIP_TRY(hipEventRecord(st->ev0, stream));
     hipLaunchKernelGGL(copy_kernel, dim3((u32)blocks), dim3(256), 0, stream, (u32x4 *)dst, (const u32x4 *)src, n_vec);

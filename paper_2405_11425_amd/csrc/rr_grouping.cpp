@@ -11,6 +11,11 @@
 
 #include "../../include/randline.h"
 
+namespace rr {
+int fail(int code, const char *fmt, ...);  // rr_state.hip: records the message for rr_last_error
+}
+using rr::fail;
+
 namespace {
 
 // Union-find over CU indices.
@@ -36,15 +41,30 @@ struct DisjointSets {
 extern "C" int rr_groups_from_heatmap(const double *T, uint32_t n, const double *singles, double min_gap,
                                       uint16_t *group_out, uint32_t *order_out, uint32_t *n_groups_out,
                                       double *threshold_out) {
-    if (!T || n == 0 || n > RR_MAX_CUS || !group_out || !order_out || !n_groups_out || !threshold_out)
-        return RR_EINVAL;
+    if (!T) return fail(RR_EINVAL, "T is NULL");
+    if (n == 0 || n > RR_MAX_CUS) return fail(RR_EINVAL, "n must be in [1, %u] (got %u)", RR_MAX_CUS, n);
+    if (!group_out || !order_out || !n_groups_out || !threshold_out) return fail(RR_EINVAL, "an output pointer is NULL");
+    if (!(min_gap >= 0.0) || !std::isfinite(min_gap)) return fail(RR_EINVAL, "min_gap must be finite and not negative");
+    // Every ratio below must be an ordinary number: a NaN among them would make the sort's order meaningless.
+    for (uint32_t a = 0; a < n; ++a)
+        for (uint32_t b = a + 1; b < n; ++b) {
+            const double t = T[(size_t)a * n + b];
+            if (!std::isfinite(t) || t < 0.0)
+                return fail(RR_EINVAL, "T[%u][%u] is not a finite, non-negative throughput", a, b);
+        }
+    if (singles)
+        for (uint32_t a = 0; a < n; ++a)
+            if (!std::isfinite(singles[a]) || !(singles[a] > 0.0))
+                return fail(RR_EINVAL, "singles[%u] is not a finite, positive throughput", a);
     const double nan = std::numeric_limits<double>::quiet_NaN();
     const size_t m = (size_t)n * (n - 1) / 2;
     std::vector<double> ratio(m);
     double top = 0.0;
-    if (!singles)
+    if (!singles) {
         for (uint32_t a = 0; a < n; ++a)
             for (uint32_t b = a + 1; b < n; ++b) top = std::max(top, T[(size_t)a * n + b]);
+        if (m > 0 && !(top > 0.0)) return fail(RR_EINVAL, "every pair throughput is zero");
+    }
     size_t k = 0;
     for (uint32_t a = 0; a < n; ++a)
         for (uint32_t b = a + 1; b < n; ++b, ++k)

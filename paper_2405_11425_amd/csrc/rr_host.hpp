@@ -35,13 +35,19 @@ struct DeviceState {
     size_t placement_cap = 0;
     ResultHead *head = nullptr;      // [kMaxBatch] pinned host memory, mapped ...
     ResultHead *head_dev = nullptr;  // ... and its address as the device sees it; single calls use entry 0
+    // The state behind the entry point that allocates nothing keeps its device data in a file-scope device
+    // array: head_dev is then plain device memory, head points at head_copy below, and finish_and_wait copies
+    // the one into the other before it waits.  Such a state has no events and a placement buffer of fixed size.
+    bool fixed = false;
+    ResultHead head_copy = {};
     u32 *cu_waves_host = nullptr;    // pinned staging for the per-CU wave counts
     bool flat_tables_ready = false;  // the device tables are those of a call without a window map
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
     std::vector<hipEvent_t> batch_ev;     // two per launch of a batch, created when first needed
     int wall_khz = 0;
-    std::vector<rr_cu_t> cus;             // dense id -> coordinates
-    std::vector<u16> dense_of_key_host;   // [kNumKeys], kExcluded if no such CU
+    u32 n_cus = 0;
+    rr_cu_t cus[kMaxCus];                 // dense id -> coordinates
+    u16 dense_of_key_host[kNumKeys];      // kExcluded if no such CU
 };
 
 constexpr int kMaxDevices = 16;
@@ -61,6 +67,9 @@ extern std::mutex g_mutex;
 // The state of the current device, created on first use (scratch, tables, events, CU enumeration on
 // `stream`).  g_mutex must be held.
 int get_state(hipStream_t stream, DeviceState **out);
+// Lists the device's compute units into st (needs st.scratch); used by get_state and by the state that
+// allocates nothing.
+int enumerate(DeviceState &st, hipStream_t stream);
 
 inline u32 key_of(const rr_cu_t &c) { return (c.xcc << 8) | (c.se << 5) | (c.sh << 4) | c.cu; }
 
@@ -74,6 +83,8 @@ inline Reducer make_reducer(u64 L) {
 
 // reset_kernel on `stream`; what: bit 0 result cells, bit 1 ticket counters, bit 2 per-CU wave counts, bit 3 key marks
 int launch_reset(DeviceState &st, u32 what, hipStream_t stream);
+// p[0 .. n) = v on `stream` (device memory)
+int launch_fill_u16(u16 *p, u64 n, u16 v, hipStream_t stream);
 // Make sure the result cells are cleared before a kernel that adds into them (marks them used).
 int begin_cells(DeviceState &st, hipStream_t stream);
 // finish_kernel (cells -> result head 0 in mapped host memory, cells left cleared), then wait for the stream.

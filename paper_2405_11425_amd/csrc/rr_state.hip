@@ -3,7 +3,6 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
-#include <string>
 
 #include "rr_host.hpp"
 
@@ -38,6 +37,12 @@ __device__ __forceinline__ void reset_scratch(Scratch *s, u32 what) {
 }
 
 __global__ void __launch_bounds__(256) reset_kernel(Scratch *s, u32 what) { reset_scratch(s, what); }
+
+// p[0 .. n) = v, grid-stride (used where a memset node would otherwise end up in a caller's captured graph).
+__global__ void __launch_bounds__(256) fill_u16_kernel(u16 *p, u64 n, u16 v) {
+    const u64 stride = (u64)gridDim.x * blockDim.x;
+    for (u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = v;
+}
 
 // One workgroup per slot of a batch: slot b has its own scratch, slots[b].
 __global__ void __launch_bounds__(256) reset_batch_kernel(Scratch *slots, BatchSlots b) {
@@ -100,15 +105,13 @@ static_assert(kMaxCus <= kNumCells, "finish_kernel checks one compute unit per t
 
 // ------------------------------------------------------------------ errors
 
-static thread_local std::string g_last_error;
+static thread_local char g_last_error[512] = "";  // a fixed buffer: reporting a failure allocates nothing
 
 int fail(int code, const char *fmt, ...) {
-    char buf[512];
     va_list ap;
     va_start(ap, fmt);
-    vsnprintf(buf, sizeof buf, fmt, ap);
+    vsnprintf(g_last_error, sizeof g_last_error, fmt, ap);
     va_end(ap);
-    g_last_error = buf;
     return code;
 }
 
@@ -120,11 +123,13 @@ namespace {
 
 DeviceState g_state[kMaxDevices];
 
+}  // namespace
+
 int enumerate(DeviceState &st, hipStream_t stream) {
     int dev = 0, n_expected = 0;
     HIP_TRY(hipGetDevice(&dev));
     HIP_TRY(hipDeviceGetAttribute(&n_expected, hipDeviceAttributeMultiprocessorCount, dev));
-    std::vector<u32> seen(kNumKeys);
+    u32 seen[kNumKeys];
     u32 found = 0;
     for (int attempt = 0; attempt < 4 && (int)found < n_expected; ++attempt) {
         int rc = launch_reset(st, 8u, stream);
@@ -132,7 +137,7 @@ int enumerate(DeviceState &st, hipStream_t stream) {
         const u32 blocks = (u32)n_expected * 64u << attempt;
         hipLaunchKernelGGL(enumerate_kernel, dim3(blocks), dim3(64), 0, stream, st.scratch, 4u << attempt);
         HIP_TRY(hipGetLastError());
-        HIP_TRY(hipMemcpyAsync(seen.data(), st.scratch->key_seen, kNumKeys * sizeof(u32),
+        HIP_TRY(hipMemcpyAsync(seen, st.scratch->key_seen, kNumKeys * sizeof(u32),
                                hipMemcpyDeviceToHost, stream));
         HIP_TRY(hipStreamSynchronize(stream));
         found = 0;
@@ -142,22 +147,20 @@ int enumerate(DeviceState &st, hipStream_t stream) {
         return fail(RR_EPLACE, "CU enumeration found %u compute units (device reports %d)", found, n_expected);
     if ((int)found != n_expected)
         return fail(RR_EPLACE, "CU enumeration found %u of %d compute units", found, n_expected);
-    st.cus.clear();
-    st.dense_of_key_host.assign(kNumKeys, kExcluded);
+    st.n_cus = 0;
     for (u32 k = 0; k < kNumKeys; ++k) {  // ascending key == sorted (xcc, se, sh, cu)
+        st.dense_of_key_host[k] = kExcluded;
         if (!seen[k]) continue;
         rr_cu_t c;
         c.xcc = k >> 8;
         c.se = (k >> 5) & 7u;
         c.sh = (k >> 4) & 1u;
         c.cu = k & 15u;
-        st.dense_of_key_host[k] = (u16)st.cus.size();
-        st.cus.push_back(c);
+        st.dense_of_key_host[k] = (u16)st.n_cus;
+        st.cus[st.n_cus++] = c;
     }
     return RR_OK;
 }
-
-}  // namespace
 
 // Create (once per device) the scratch, tables, events and the CU list.
 int get_state(hipStream_t stream, DeviceState **out) {
@@ -189,6 +192,15 @@ int get_state(hipStream_t stream, DeviceState **out) {
 
 int launch_reset(DeviceState &st, u32 what, hipStream_t stream) {
     hipLaunchKernelGGL(reset_kernel, dim3(1), dim3(256), 0, stream, st.scratch, what);
+    HIP_TRY(hipGetLastError());
+    return RR_OK;
+}
+
+int launch_fill_u16(u16 *p, u64 n, u16 v, hipStream_t stream) {
+    if (n == 0) return RR_OK;
+    u64 blocks = (n + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(fill_u16_kernel, dim3((u32)blocks), dim3(256), 0, stream, p, n, v);
     HIP_TRY(hipGetLastError());
     return RR_OK;
 }
@@ -235,7 +247,7 @@ int prepare_batch(DeviceState &st, u32 n, const u32 *tickets_per_unit, const u32
 
 int finish_batch(DeviceState &st, u32 n, const BatchSlots &b, hipStream_t stream) {
     hipLaunchKernelGGL(finish_batch_kernel, dim3(n), dim3(kNumCells), 0, stream, st.batch_scratch, st.head_dev, st.tables,
-                       (u32)st.cus.size(), b);
+                       st.n_cus, b);
     HIP_TRY(hipGetLastError());
     HIP_TRY(hipStreamSynchronize(stream));
     st.batch_dirty = false;
@@ -246,6 +258,8 @@ int finish_and_wait(DeviceState &st, u32 n_cus, u32 tickets_per_unit, u32 ticket
     hipLaunchKernelGGL(finish_kernel, dim3(1), dim3(kNumCells), 0, stream, st.scratch, st.head_dev, st.tables, n_cus,
                        tickets_per_unit, ticket_mode);
     HIP_TRY(hipGetLastError());
+    if (st.fixed)  // the head is in device memory: fetch it (the wait below covers the copy)
+        HIP_TRY(hipMemcpyAsync(st.head, st.head_dev, sizeof(ResultHead), hipMemcpyDeviceToHost, stream));
     HIP_TRY(hipStreamSynchronize(stream));
     st.cells_clean = true;
     return RR_OK;
@@ -267,7 +281,7 @@ extern "C" const char *rr_strerror(int code) {
     }
 }
 
-extern "C" const char *rr_last_error(void) { return g_last_error.c_str(); }
+extern "C" const char *rr_last_error(void) { return g_last_error; }
 
 extern "C" int rr_enumerate_cus(rr_cu_t *out, uint32_t cap, uint32_t *n_cus, void *hip_stream) {
     if (!n_cus) return fail(RR_EINVAL, "n_cus is NULL");
@@ -276,7 +290,7 @@ extern "C" int rr_enumerate_cus(rr_cu_t *out, uint32_t cap, uint32_t *n_cus, voi
     DeviceState *st = nullptr;
     int rc = get_state((hipStream_t)hip_stream, &st);
     if (rc != RR_OK) return rc;
-    const u32 n = (u32)st->cus.size();
+    const u32 n = st->n_cus;
     for (u32 i = 0; i < n && i < cap; ++i) out[i] = st->cus[i];
     *n_cus = n;
     return RR_OK;

@@ -31,7 +31,14 @@ def region():
     assert gib >= 2, "not enough free device memory"
     buf = torch.empty(gib * GiB, dtype=torch.uint8, device="cuda")
     rl.fill(buf, wl.FILL_SEED)
+    print(f"\n[region fixture] {free / GiB:.1f} GiB free, allocated {gib} GiB", flush=True)
     return buf
+
+
+def need(region, gib):
+    """Skip (with the reason) a case that needs a larger allocation than this card gave."""
+    if region.numel() < gib * GiB:
+        pytest.skip(f"needs a {gib} GiB region, the allocation is {region.numel() // GiB} GiB")
 
 
 @pytest.fixture(scope="module")
@@ -583,6 +590,12 @@ def test_probe_rejects_bad_targets(region, cu_table):
 
 
 # ------------------------------------------------------------------ full sizes, as bench.py launches them
+def test_allocation_is_256_gib(region):
+    """The tests below are 'full size' only if the allocation is: on an idle MI355X (288 GB) the fixture gets its
+    256 GiB.  A smaller one fails here, loudly, instead of letting the full-size tests pass at a smaller size."""
+    assert region.numel() == 256 * GiB, f"the allocation is only {region.numel() // GiB} GiB: the card is not idle"
+
+
 def test_region_sweep_full_size(region, cu_table):
     """Every point of the region-size sweep (all wave slots occupied, 4096 reads per logical
     wave, default launch options -- what bench.py times) against the oracle."""
@@ -652,24 +665,36 @@ def test_batch_rejects_what_it_cannot_do(region):
     assert rl.rand_read(region, 128, 640, 10, 5, region_bytes=1 << 20).checksum == oracle(1 << 20, 128, 64, 10, read_seed=5)
 
 
-def test_line_width_sweep_full_size(region):
-    """2^30 reads per line shape at the largest region: the whole run must equal the sum of its
-    16 wave sub-ranges (GPU), and sampled sub-ranges must equal the oracle."""
-    R = region.numel()
-    if R >= 256 * GiB:
-        R = 256 * GiB
-    for cfg in wl.line_width_sweep(R):
-        kw = dict(lanes_per_line=cfg.lanes_per_line, region_bytes=R)
-        whole = rl.rand_read(region, cfg.line_bytes, cfg.n_reads, cfg.iters_per_wave, cfg.read_seed, **kw).checksum
-        sub = cfg.logical_waves // 16
-        total = 0
-        for k in range(16):
-            part = rl.rand_read(region, cfg.line_bytes, sub * cfg.iters_per_wave, cfg.iters_per_wave, cfg.read_seed,
-                                first_wave=k * sub, **kw).checksum
-            total += part
-            if k in (0, 7, 15):
-                assert part == oracle(R, cfg.line_bytes, sub, cfg.iters_per_wave, first_wave=k * sub), (cfg.name, k)
-        assert total & M64 == whole, cfg.name
+@pytest.fixture(scope="module")
+def zone_map(region):
+    """zone_of_window for the whole allocation in 32 windows, from the quick probe (what bench.py orders its
+    largest regions by)."""
+    need(region, 256)
+    from paper_2405_11425_amd import zonemap
+    zm = zonemap.detect_zone_map(region, 256 * GiB, len(rl.enumerate_cus()))
+    print(f"\n[zone map] {zm}", flush=True)
+    return zm
+
+
+@pytest.mark.parametrize("gib", [128, 256])
+@pytest.mark.parametrize("line_bytes,lanes", wl.LINE_SHAPES)
+def test_line_width_sweep_full_size(region, zone_map, gib, line_bytes, lanes):
+    """2^30 reads of every line shape over 128 and 256 GiB (paper Sec. 2.1: the wider accesses), in plain order
+    and zone by zone: the checksum of the whole launch against the oracle's for all 2^30 reads."""
+    need(region, gib)
+    cfg = [c for c in wl.line_width_sweep(gib * GiB) if (c.line_bytes, c.lanes_per_line) == (line_bytes, lanes)][0]
+    assert cfg.n_reads == 1 << 30
+    want = oracle(cfg.region_bytes, cfg.line_bytes, cfg.logical_waves, cfg.iters_per_wave)
+    kw = dict(lanes_per_line=cfg.lanes_per_line, region_bytes=cfg.region_bytes)
+    plain = rl.rand_read(region, cfg.line_bytes, cfg.n_reads, cfg.iters_per_wave, cfg.read_seed, **kw)
+    assert plain.checksum == want, "plain order"
+    windows = zone_map[:32 * gib // 256]                   # windows of 8 GiB
+    ids = {z: i for i, z in enumerate(dict.fromkeys(windows))}
+    zoned = rl.rand_read(region, cfg.line_bytes, cfg.n_reads, cfg.iters_per_wave, cfg.read_seed,
+                         zone_of_window=[ids[z] for z in windows], **kw)
+    assert zoned.checksum == want, "zone order"
+    gbps = lambda r: cfg.bytes_read / r.kernel_ms_event / 1e6
+    print(f"\n[{cfg.name}] plain {gbps(plain):.0f} GB/s, zone order ({len(ids)} zones) {gbps(zoned):.0f} GB/s", flush=True)
 
 
 def test_windowed_full_size(region, cu_table):
@@ -689,12 +714,86 @@ def test_windowed_full_size(region, cu_table):
             assert got.checksum == want, (n_windows, scheme)
 
 
-def test_probe_full_size(region, cu_table):
-    """The pair-probe configuration (16 GiB, 2^22 reads) on a few sampled pairs."""
-    cfg = wl.probe_config(min(16 * GiB, region.numel()))
+def oracle_groups_equal_library(T, singles, min_gap=0.05):
+    """The measured matrix through the library's clustering and through the oracle's: identical groups, order, threshold."""
+    from oracle.grouping import groups_from_heatmap as oracle_groups
+    g_lib, o_lib, t_lib = rl.groups_from_heatmap(T, singles, min_gap)
+    g_orc, o_orc, t_orc = oracle_groups(T, singles, min_gap)
+    assert g_lib.tolist() == g_orc.tolist() and o_lib.tolist() == o_orc.tolist()
+    assert (np.isnan(t_lib) and np.isnan(t_orc)) or t_lib == t_orc
+    return g_lib, t_lib
+
+
+def probe_matrix(region, units, cfg, want):
+    """Singles and all pairs of the probe units (lists of CUs): every run must return the one checksum `want`
+    and must have had working waves on every one of its CUs."""
+    n_reads = cfg.n_reads * len(units[0])
+    gbps = lambda r: n_reads * cfg.line_bytes / r.kernel_ms_device / 1e6
+    run = lambda cus: rl.probe_cus(region, cus, n_reads, cfg.iters_per_wave, cfg.read_seed, region_bytes=cfg.region_bytes,
+                                   want_cu_waves=True)
+    m = len(units)
+    singles, T = np.zeros(m), np.zeros((m, m))
+    run(units[0] + units[1])
+    for i in range(m):
+        r = run(units[i])
+        assert r.checksum == want, f"unit {i} alone"
+        singles[i] = gbps(r)
+    for i in range(m):
+        for j in range(i + 1, m):
+            cus = units[i] + units[j]
+            r = run(cus)
+            assert r.checksum == want, f"pair {i},{j}"
+            assert (r.cu_waves[cus] > 0).all() and r.cu_waves.sum() == r.cu_waves[cus].sum() == r.waves_run
+            T[i, j] = T[j, i] = gbps(r)
+    return singles, T
+
+
+def test_probe_all_pairs_full_size(region, cu_table):
+    """Paper Sec. 2.2 at full extent: the access kernel on every pair of the 64 sampled compute units (2016 pairs,
+    16 GiB, 2^22 reads each) and on each alone.  Every run returns the checksum of one oracle evaluation; the
+    measured heatmap gives the same groups through the library's clustering and through the oracle's."""
+    need(region, 16)
+    cfg = wl.probe_config(16 * GiB)
     want = oracle(cfg.region_bytes, 128, cfg.logical_waves, cfg.iters_per_wave)
     sample = wl.probe_cu_sample(cu_table)
-    for a, b in ((sample[0], sample[1]), (sample[0], sample[-1]), (sample[10], sample[40])):
-        got = rl.probe_pair(region, int(a), int(b), cfg.n_reads, cfg.iters_per_wave, cfg.read_seed,
-                            region_bytes=cfg.region_bytes)
-        assert got.checksum == want
+    assert len(sample) == 64
+    singles, T = probe_matrix(region, [[int(c)] for c in sample], cfg, want)
+    group, thr = oracle_groups_equal_library(T, singles)
+    iu = np.triu_indices(64, 1)
+    ratio = (T / (singles[:, None] + singles[None, :]))[iu]
+    print(f"\n[probe 64x1] single {np.median(singles):.1f} GB/s, pair ratio {ratio.min():.3f}..{ratio.max():.3f}, "
+          f"threshold {thr}, {group.max() + 1} groups", flush=True)
+
+
+def test_probe_blocks_of_four_full_size(region, cu_table):
+    """The same with blocks of four adjacent compute units as probe units (all 256 CUs in 64 blocks): two CUs
+    cannot load a shared resource on this GPU, two blocks can.  Library and oracle must agree on the measured
+    matrix whatever it shows; what it showed so far (32 groups of two blocks, the shader engines) is printed."""
+    need(region, 16)
+    n = len(cu_table)
+    if n % 4 != 0 or n // 4 < 2:
+        pytest.skip(f"{n} compute units do not split into blocks of four")
+    cfg = wl.probe_config(16 * GiB)
+    want = oracle(cfg.region_bytes, 128, cfg.logical_waves * 4, cfg.iters_per_wave)
+    m = min(64, n // 4)
+    step = (n // 4) / m
+    units = [list(range(int(i * step) * 4, int(i * step) * 4 + 4)) for i in range(m)]
+    singles, T = probe_matrix(region, units, cfg, want)
+    group, thr = oracle_groups_equal_library(T, singles)
+    sizes = np.bincount(group)
+    print(f"\n[probe {m}x4] single {np.median(singles):.1f} GB/s, threshold {thr}, {group.max() + 1} groups of "
+          f"{sorted(set((sizes * 4).tolist()))} CUs", flush=True)
+    if not np.isnan(thr):
+        # whatever was linked shares a shader engine: blocks of different XCDs are never in one group
+        for g in range(group.max() + 1):
+            members = np.flatnonzero(group == g)
+            assert len({int(cu_table[units[u][0], 0]) for u in members}) == 1
+
+
+def test_planted_heatmaps_library_equals_oracle():
+    """The clustering is host code; run here as well so that the suite on the GPU machine exercises it."""
+    from test_grouping_oracle import planted, same_partition
+    for sizes, seed in (([8] * 8, 1), ([8, 6, 8, 8, 6, 8, 8, 8, 8, 8, 8, 8, 8, 8], 2), ([2] * 32, 3)):
+        T, truth = planted(sizes, seed)
+        group, _ = oracle_groups_equal_library(T, None)
+        assert same_partition(group, truth)

@@ -63,3 +63,52 @@ def test_two_by_two_boxes():
     T, truth = planted([2] * 8, seed=5, shuffle=False)
     group, _, _ = groups_from_heatmap(T)
     assert list(group) == [i // 2 for i in range(16)]
+
+
+def sym(n, entries):
+    T = np.zeros((n, n))
+    for (a, b), v in entries.items():
+        T[a, b] = T[b, a] = v
+    return T
+
+
+def test_first_of_two_equal_largest_gaps_splits():
+    """Worked by hand from the rule's statement (step 2: the first of equal gaps).  Ratios T/max are
+    0.25, 0.25, 0.625, 0.625, 1, 1 (all exact in binary): the gaps 0.25 -> 0.625 and 0.625 -> 1 are both 0.375.
+    The first one splits: threshold 0.4375, only the 0.25 pairs are linked -> {0,1}, {2,3}.  Taking the last of
+    the equal gaps instead would give 0.8125 and one group of four."""
+    T = sym(4, {(0, 1): 0.25, (2, 3): 0.25, (0, 2): 0.625, (1, 3): 0.625, (0, 3): 1.0, (1, 2): 1.0})
+    group, order, thr = groups_from_heatmap(T, None, 0.05)
+    assert group.tolist() == [0, 0, 1, 1] and order.tolist() == [0, 1, 2, 3] and thr == 0.4375
+
+
+def test_gap_exactly_at_min_gap_times_median_counts_as_structure():
+    """Step 3 says "smaller than": ratios 0.5, 1, 1 -> largest gap 0.5, median 1.  With min_gap = 0.5 the gap is
+    not smaller than min_gap x median, so the matrix has structure (threshold 0.75, units 0 and 1 linked); with
+    min_gap just above, it has none."""
+    T = sym(3, {(0, 1): 50.0, (0, 2): 100.0, (1, 2): 100.0})
+    group, order, thr = groups_from_heatmap(T, None, 0.5)
+    assert group.tolist() == [0, 0, 1] and thr == 0.75
+    group, order, thr = groups_from_heatmap(T, None, 0.5 + 2.0 ** -40)
+    assert group.tolist() == [0, 1, 2] and np.isnan(thr)
+    # the same with single-unit rates: ratio = T / (S_a + S_b) = 0.25, 0.5, 0.5 -> gap 0.25 = 0.5 x median 0.5
+    group, order, thr = groups_from_heatmap(T, np.array([100.0, 100.0, 100.0]), 0.5)
+    assert group.tolist() == [0, 0, 1] and thr == 0.375
+
+
+@pytest.mark.parametrize("bad", ["nan", "negative", "zero", "single_zero", "single_nan"])
+def test_matrices_the_rule_is_not_defined_for_are_refused(bad):
+    T = sym(3, {(0, 1): 50.0, (0, 2): 100.0, (1, 2): 100.0})
+    singles = None
+    if bad == "nan":
+        T[0, 2] = T[2, 0] = float("nan")
+    elif bad == "negative":
+        T[0, 1] = T[1, 0] = -1.0
+    elif bad == "zero":
+        T[:] = 0.0
+    elif bad == "single_zero":
+        singles = np.array([100.0, 0.0, 100.0])
+    else:
+        singles = np.array([100.0, float("nan"), 100.0])
+    with pytest.raises(ValueError):
+        groups_from_heatmap(T, singles)

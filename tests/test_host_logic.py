@@ -13,6 +13,14 @@ from paper_2405_11425_amd import workloads as wl
 from oracle.grouping import groups_from_heatmap as oracle_groups
 from test_grouping_oracle import planted, same_partition
 
+
+def _has_gpu():
+    try:
+        import torch
+        return torch.cuda.is_available()
+    except ImportError:
+        return False
+
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
@@ -187,6 +195,14 @@ def test_fill_and_probe_validation():
     assert "twice" in str(e.value)
     with pytest.raises(rl.RandlineError):
         rl.probe_cus(FAKE, [], 8, 8, 7)
+    # a pinned run cannot be zone-phased (that kernel knows no excluded compute units) nor flat
+    for kw in ({"zone_bytes": 1 << 19}, {"zone_of_window": [0, 1]}, {"mode": rl.MODE_FLAT}):
+        with pytest.raises(rl.RandlineError) as e:
+            rl.probe_cus(FAKE, [0, 1], 8, 8, 7, **kw)
+        assert e.value.code == rl.RR_EINVAL and "pinned" in str(e.value)
+        with pytest.raises(rl.RandlineError) as e:
+            rl.probe_pair(FAKE, 0, 1, 8, 8, 7, **kw)
+        assert e.value.code == rl.RR_EINVAL and "pinned" in str(e.value)
 
 
 def test_rand_update_validation():
@@ -398,6 +414,70 @@ def test_groups_from_heatmap_noisy_random_matrices_match_oracle():
             g_orc, o_orc, t_orc = oracle_groups(T, None, gap)
             assert g_lib.tolist() == g_orc.tolist() and o_lib.tolist() == o_orc.tolist()
             assert (np.isnan(t_lib) and np.isnan(t_orc)) or t_lib == t_orc
+
+
+def test_groups_from_heatmap_tie_break_and_boundary_match_oracle():
+    """The two corners of the rule that planted matrices do not reach: the first of two equal largest gaps
+    splits, and a gap exactly at min_gap x median still counts as structure (values worked by hand in
+    tests/test_grouping_oracle.py)."""
+    T = np.zeros((4, 4))
+    for (a, b), v in {(0, 1): 0.25, (2, 3): 0.25, (0, 2): 0.625, (1, 3): 0.625, (0, 3): 1.0, (1, 2): 1.0}.items():
+        T[a, b] = T[b, a] = v
+    g, o, t = rl.groups_from_heatmap(T, None, 0.05)
+    assert g.tolist() == [0, 0, 1, 1] and t == 0.4375
+    assert oracle_groups(T, None, 0.05)[0].tolist() == g.tolist()
+    T = np.array([[0, 50.0, 100.0], [50.0, 0, 100.0], [100.0, 100.0, 0]])
+    for gap, groups in ((0.5, [0, 0, 1]), (0.5 + 2.0 ** -40, [0, 1, 2])):
+        g, o, t = rl.groups_from_heatmap(T, None, gap)
+        g_orc, _, t_orc = oracle_groups(T, None, gap)
+        assert g.tolist() == groups == g_orc.tolist()
+        assert (np.isnan(t) and np.isnan(t_orc)) or t == t_orc == 0.75
+
+
+def test_groups_from_heatmap_refuses_what_the_rule_is_not_defined_for():
+    """NaN, negative or all-zero matrices and non-positive single rates: RR_EINVAL with a message of its own
+    (never a stale one), outputs untouched; the oracle refuses the same inputs."""
+    good = np.array([[0, 50.0, 100.0], [50.0, 0, 100.0], [100.0, 100.0, 0]])
+    cases = []
+    T = good.copy(); T[0, 2] = T[2, 0] = np.nan; cases.append((T, None, "T[0][2]"))
+    T = good.copy(); T[0, 1] = T[1, 0] = -1.0; cases.append((T, None, "T[0][1]"))
+    T = good.copy(); T[1, 2] = T[2, 1] = np.inf; cases.append((T, None, "T[1][2]"))
+    cases.append((np.zeros((3, 3)), None, "zero"))
+    cases.append((good, np.array([100.0, 0.0, 100.0]), "singles[1]"))
+    cases.append((good, np.array([100.0, 100.0, np.nan]), "singles[2]"))
+    for T, singles, word in cases:
+        with pytest.raises(ValueError):
+            oracle_groups(T, singles)
+        rl.lib().rr_rand_read(None, 0, 0, 0, 0, 0, None, 0, None, None, None)      # leaves some other message behind
+        with pytest.raises(rl.RandlineError) as e:
+            rl.groups_from_heatmap(T, singles)
+        assert e.value.code == rl.RR_EINVAL and word in str(e.value), str(e.value)
+    # raw call: NULL matrix, n out of range, bad min_gap -- each with its own message, outputs untouched
+    group = (C.c_uint16 * 3)(7, 7, 7)
+    order = (C.c_uint32 * 3)(9, 9, 9)
+    ng, thr = C.c_uint32(5), C.c_double(-2.0)
+    Tp = good.ctypes.data_as(C.POINTER(C.c_double))
+    L = rl.lib()
+    for args, word in (((None, 3, None, 0.05), "NULL"), ((Tp, 0, None, 0.05), "n must"), ((Tp, 2000, None, 0.05), "n must"),
+                       ((Tp, 3, None, float("nan")), "min_gap"), ((Tp, 3, None, -0.1), "min_gap")):
+        assert L.rr_groups_from_heatmap(args[0], args[1], args[2], args[3], group, order, C.byref(ng), C.byref(thr)) == rl.RR_EINVAL
+        assert word in L.rr_last_error().decode()
+    assert L.rr_groups_from_heatmap(Tp, 3, None, 0.05, None, order, C.byref(ng), C.byref(thr)) == rl.RR_EINVAL
+    assert "output" in L.rr_last_error().decode()
+    assert list(group) == [7, 7, 7] and list(order) == [9, 9, 9] and ng.value == 5 and thr.value == -2.0
+
+
+def test_copy_reports_time_on_success_only():
+    """rr_copy writes *kernel_ms when it succeeds (an empty copy: 0) and leaves it alone on every failure."""
+    L = rl.lib()
+    ms = C.c_double(-1.0)
+    assert L.rr_copy(0x1000, 0x2000, 0, None, C.byref(ms)) == rl.RR_OK and ms.value == 0.0
+    ms = C.c_double(-1.0)
+    assert L.rr_copy(0x1000, 0x1008, 64, None, C.byref(ms)) == rl.RR_EINVAL and ms.value == -1.0     # misaligned
+    assert L.rr_copy(0x1000, 0x1010, 64, None, C.byref(ms)) == rl.RR_EINVAL and ms.value == -1.0     # overlap
+    if not _has_gpu():
+        # without a device the call fails in the HIP runtime, after validation: still untouched
+        assert L.rr_copy(0x10000, 0x20000, 64, None, C.byref(ms)) == rl.RR_EHIP and ms.value == -1.0
 
 
 def test_groups_from_heatmap_single_unit():
