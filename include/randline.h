@@ -194,6 +194,35 @@ int rr_rand_read(const void *region, uint64_t region_bytes, uint32_t line_bytes,
                  const rr_launch_opts_t *opts, rr_result_t *out);
 
 /*
+ * rr_rand_read for callers that cannot allocate: code that runs where hipMalloc
+ * is forbidden or too slow (tight serving loops, harnesses that intercept the
+ * allocator, set-up phases of a graph capture).  Same arguments, same result,
+ * same kernels; but the call allocates nothing -- no hipMalloc, hipHostMalloc,
+ * hipFree, events or host heap -- not even the first time.  The device data the
+ * other entry points keep in allocated memory (result cells, ticket counters,
+ * lookup tables, result head; 320 KB) plus a placement log of fixed capacity
+ * live in a device array that is part of the library's code object (450 KB per
+ * GPU, held until the process ends); its address on the current device is
+ * looked up once, on the first call on that device, which also lists the
+ * compute units (one short kernel on hip_stream).
+ * Differences from rr_rand_read:
+ *   - opts->placement_out is limited to RR_NOALLOC_MAX_PLACEMENT logical waves
+ *     (RR_EINVAL beyond, before any HIP call); everything else has the limits
+ *     of rr_rand_read (they do not grow with the input);
+ *   - out->kernel_ms_event is 0: no events are created; use kernel_ms_device;
+ *   - results come back by a 32-byte device-to-host copy on hip_stream.
+ * The array keeps the previous call's contents; every call clears what it
+ * needs cleared.  All calls on one GPU share the array: within a process the
+ * library runs them one at a time (the lock it uses for every launching
+ * call), so they do not race; nothing else may write to it.
+ */
+#define RR_NOALLOC_MAX_PLACEMENT 65536u
+int rr_rand_read_noalloc(const void *region, uint64_t region_bytes, uint32_t line_bytes,
+                         uint32_t lanes_per_line, uint64_t n_reads, uint32_t iters_per_wave,
+                         const rr_window_map_t *wm, uint64_t read_seed, void *hip_stream,
+                         const rr_launch_opts_t *opts, rr_result_t *out);
+
+/*
  * A series of measurements in one call (the paper's throughput curve, Sec. 2.1,
  * is such a series: the same number of reads over regions of growing size).
  * Item i is the call rr_rand_read(region, items[i].region_bytes, line_bytes,

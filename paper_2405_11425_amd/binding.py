@@ -60,7 +60,7 @@ class _ReadItem(C.Structure):
     _fields_ = [("region_bytes", C.c_uint64), ("read_seed", C.c_uint64), ("opts", C.POINTER(_Opts))]
 
 
-EXPORTS = ["rr_enumerate_cus", "rr_fill", "rr_rand_read", "rr_rand_read_batch", "rr_probe_pair", "rr_probe_cus", "rr_seq_read", "rr_copy", "rr_chase", "rr_rand_update",
+EXPORTS = ["rr_enumerate_cus", "rr_fill", "rr_rand_read", "rr_rand_read_noalloc", "rr_rand_read_batch", "rr_probe_pair", "rr_probe_cus", "rr_seq_read", "rr_copy", "rr_chase", "rr_rand_update",
            "rr_region_granularity", "rr_region_create", "rr_region_destroy",
            "rr_groups_from_heatmap", "rr_shutdown", "rr_strerror", "rr_last_error"]
 
@@ -93,6 +93,8 @@ def lib():
         L.rr_rand_read.restype = C.c_int
         L.rr_rand_read.argtypes = [vp, u64, u32, u32, u64, u32, C.POINTER(_WindowMap), u64, vp,
                                    C.POINTER(_Opts), C.POINTER(_Result)]
+        L.rr_rand_read_noalloc.restype = C.c_int
+        L.rr_rand_read_noalloc.argtypes = L.rr_rand_read.argtypes
         L.rr_rand_read_batch.restype = C.c_int
         L.rr_rand_read_batch.argtypes = [vp, C.POINTER(_ReadItem), u32, u32, u32, u64, u32, vp, C.POINTER(_Result)]
         L.rr_probe_pair.restype = C.c_int
@@ -246,6 +248,15 @@ def rand_read(region, line_bytes: int, n_reads: int, iters_per_wave: int, read_s
               region_bytes: Optional[int] = None, stream=None, want_placement: bool = False,
               want_cu_waves: bool = False, **launch) -> ReadResult:
     return _rand_read(lib().rr_rand_read, region, line_bytes, n_reads, iters_per_wave, read_seed, window_map,
+                      lanes_per_line, region_bytes, stream, want_placement, want_cu_waves, launch)
+
+
+def rand_read_noalloc(region, line_bytes: int, n_reads: int, iters_per_wave: int, read_seed: int,
+                      window_map: Optional[WindowMap] = None, lanes_per_line: int = 32,
+                      region_bytes: Optional[int] = None, stream=None, want_placement: bool = False,
+                      want_cu_waves: bool = False, **launch) -> ReadResult:
+    """rand_read through the entry point that allocates nothing (see rr_rand_read_noalloc)."""
+    return _rand_read(lib().rr_rand_read_noalloc, region, line_bytes, n_reads, iters_per_wave, read_seed, window_map,
                       lanes_per_line, region_bytes, stream, want_placement, want_cu_waves, launch)
 
 

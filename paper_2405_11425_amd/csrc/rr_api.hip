@@ -309,6 +309,63 @@ int make_launch(const Plan &pl, DeviceState &st, const void *region, uint32_t it
     return RR_OK;
 }
 
+// ------------------------------------------------------------------ the state that allocates nothing
+
+// Device data of the entry point that allocates nothing (rr_rand_read_noalloc): what the other entry points keep
+// in hipMalloc'ed and pinned memory -- result cells, counters, lookup tables, the result head -- plus a placement
+// log of fixed capacity.  One copy of this array exists on every GPU the library's code object is loaded on, at an
+// address of its own; host code gets that address from hipGetSymbolAddress (never from the array's name, which in
+// host code is only a stand-in for the symbol).
+struct FixedArea {
+    Scratch scratch;
+    Tables tables;
+    ResultHead head;
+    u16 placement[RR_NOALLOC_MAX_PLACEMENT];
+};
+static __device__ __align__(256) unsigned char scratch[sizeof(FixedArea)];
+
+// Host-side companions of that array (plain static memory): table staging, the last upload, per-CU counts.
+struct FixedHost {
+    Tables staging, last;
+    u32 cu_waves[kMaxCus];
+};
+FixedHost g_fixed_host[kMaxDevices];
+DeviceState g_fixed_state[kMaxDevices];
+
+// Set-up of the current device's fixed state, once per device: the address of this device's copy of the
+// array, the clock rate, the CU list (enumeration kernel on `stream`).  Allocates nothing.  g_mutex held.
+int get_fixed_state(hipStream_t stream, DeviceState **out) {
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(RR_EHIP, "device index %d not supported", dev);
+    DeviceState &st = g_fixed_state[dev];
+    if (!st.ready) {
+        unsigned char *ptr = nullptr;
+        HIP_TRY(hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr) return fail(RR_EHIP, "the device array has no address on device %d", dev);
+        FixedArea *area = (FixedArea *)ptr;  // a device address: host code only does arithmetic on it
+        st.fixed = true;
+        st.scratch = &area->scratch;
+        st.tables = &area->tables;
+        st.head_dev = &area->head;
+        st.head = &st.head_copy;
+        st.placement = area->placement;
+        st.placement_cap = RR_NOALLOC_MAX_PLACEMENT;
+        st.tables_host = &g_fixed_host[dev].staging;
+        st.tables_last = &g_fixed_host[dev].last;
+        st.cu_waves_host = g_fixed_host[dev].cu_waves;
+        st.tables_valid = false;
+        st.cells_clean = false;  // the array holds whatever was there: the first launch clears the cells
+        HIP_TRY(hipDeviceGetAttribute(&st.wall_khz, hipDeviceAttributeWallClockRate, dev));
+        if (st.wall_khz <= 0) st.wall_khz = 100000;  // s_memrealtime: 100 MHz
+        int rc = enumerate(st, stream);
+        if (rc != RR_OK) return rc;
+        st.ready = true;
+    }
+    *out = &st;
+    return RR_OK;
+}
+
 // ------------------------------------------------------------------ the launch loop
 
 int run_plan_locked(DeviceState &st, const Plan &pl, const void *region, uint32_t iters, const rr_window_map_t *wm,
@@ -332,6 +389,9 @@ int run_plan_locked(DeviceState &st, const Plan &pl, const void *region, uint32_
     }
     const bool want_placement = opts && opts->placement_out;
     if (want_placement && st.placement_cap < pl.W) {
+        if (st.fixed)
+            return fail(RR_EINVAL, "placement_out for %llu logical waves is beyond the %u this entry point has room for",
+                        pl.W, (u32)RR_NOALLOC_MAX_PLACEMENT);
         HIP_TRY(hipStreamSynchronize(stream));
         if (st.placement) HIP_TRY(hipFree(st.placement));
         st.placement = nullptr;
@@ -405,17 +465,22 @@ int run_plan_locked(DeviceState &st, const Plan &pl, const void *region, uint32_
     return RR_OK;
 }
 
+// fixed: use the state that allocates nothing (rr_rand_read_noalloc) instead of the hipMalloc'ed one.
 int run_plan(const Plan &pl, const void *region, uint32_t iters, const rr_window_map_t *wm, uint64_t read_seed,
-             hipStream_t stream, const rr_launch_opts_t *opts, rr_result_t *out) {
+             hipStream_t stream, const rr_launch_opts_t *opts, rr_result_t *out, bool fixed = false) {
     if (pl.W == 0) {  // nothing to read
         memset(out, 0, sizeof *out);
         return RR_OK;
     }
     std::lock_guard<std::mutex> lock(g_mutex);
     DeviceState *st = nullptr;
-    int rc = get_state(stream, &st);
+    int rc = fixed ? get_fixed_state(stream, &st) : get_state(stream, &st);
     if (rc != RR_OK) return rc;
-    return run_plan_locked(*st, pl, region, iters, wm, read_seed, stream, opts, out);
+    rc = run_plan_locked(*st, pl, region, iters, wm, read_seed, stream, opts, out);
+    // A fixed state stages its tables in plain static memory: nothing of this call may still be in flight
+    // when the next one rewrites them.
+    if (rc != RR_OK && fixed) (void)hipStreamSynchronize(stream);
+    return rc;
 }
 
 }  // namespace
@@ -430,6 +495,19 @@ extern "C" int rr_rand_read(const void *region, uint64_t region_bytes, uint32_t 
     int rc = make_plan(region, region_bytes, line_bytes, lanes_per_line, n_reads, iters_per_wave, wm, opts, out, pl);
     if (rc != RR_OK) return rc;
     return run_plan(pl, region, iters_per_wave, wm, read_seed, (hipStream_t)hip_stream, opts, out);
+}
+
+extern "C" int rr_rand_read_noalloc(const void *region, uint64_t region_bytes, uint32_t line_bytes,
+                                    uint32_t lanes_per_line, uint64_t n_reads, uint32_t iters_per_wave,
+                                    const rr_window_map_t *wm, uint64_t read_seed, void *hip_stream,
+                                    const rr_launch_opts_t *opts, rr_result_t *out) {
+    Plan pl;
+    int rc = make_plan(region, region_bytes, line_bytes, lanes_per_line, n_reads, iters_per_wave, wm, opts, out, pl);
+    if (rc != RR_OK) return rc;
+    if (opts && opts->placement_out && pl.W > RR_NOALLOC_MAX_PLACEMENT)
+        return fail(RR_EINVAL, "placement_out for %llu logical waves is beyond the %u this entry point has room for",
+                    pl.W, (u32)RR_NOALLOC_MAX_PLACEMENT);
+    return run_plan(pl, region, iters_per_wave, wm, read_seed, (hipStream_t)hip_stream, opts, out, true);
 }
 
 extern "C" int rr_rand_read_batch(const void *region, const rr_read_item_t *items, uint32_t n_items,

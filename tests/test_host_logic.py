@@ -205,6 +205,24 @@ def test_fill_and_probe_validation():
         assert e.value.code == rl.RR_EINVAL and "pinned" in str(e.value)
 
 
+def test_noalloc_entry_point_validates_like_rand_read_and_knows_its_limit():
+    """Same argument rules as rr_rand_read, checked before any device work; on top of them the fixed capacity
+    of its placement log."""
+    for args, kw, needle in ((((0, 4096), 128, 8, 8, 7), {}, "NULL"), ((FAKE, 100, 8, 8, 7), {}, "line_bytes"),
+                             ((FAKE, 128, 9, 8, 7), {}, "multiple of iters_per_wave"),
+                             ((FAKE, 128, 8, 8, 7), {"unroll": 3}, "unroll")):
+        with pytest.raises(rl.RandlineError) as e:
+            rl.rand_read_noalloc(*args, **kw)
+        assert e.value.code == rl.RR_EINVAL and needle in str(e.value)
+    W = 65536 + 1
+    with pytest.raises(rl.RandlineError) as e:
+        rl.rand_read_noalloc(FAKE, 128, W * 2, 2, 7, want_placement=True)
+    assert e.value.code == rl.RR_EINVAL and "beyond" in str(e.value)
+    assert rl.rand_read_noalloc(FAKE, 128, 0, 8, 7).checksum == 0         # nothing to read: no device work at all
+    header = open(os.path.join(ROOT, "include", "randline.h")).read()
+    assert "#define RR_NOALLOC_MAX_PLACEMENT 65536u" in header
+
+
 def test_rand_update_validation():
     with pytest.raises(rl.RandlineError) as e:
         rl.rand_update(FAKE, 128, 8, 8, 7, 3, 1)
