@@ -1,0 +1,135 @@
+"""Pins of the zone oracle (oracle/zones.py): values worked by hand from the rule's six steps, exhaustive recovery
+of every partition of six windows from noise-free rates, planted maps under noise, and the number of pair rates the
+rule consults."""
+import itertools
+
+import numpy as np
+import pytest
+
+from oracle.zones import zones_from_pair_rates
+
+SAME, CROSS = 6800.0, 6540.0      # GB/s inside one zone and across two, as measured on the MI355X (4 % apart)
+
+
+def table_rate(table, default=None, log=None):
+    """rate(a, b[, again]) from a dict {(a, b): value or (first, again)} with a <= b."""
+    def rate(a, b, again=False):
+        v = table.get((min(a, b), max(a, b)), default)
+        assert v is not None, f"pair {(a, b)} is not in the table: the rule was not expected to ask for it"
+        if log is not None:
+            log.append((a, b, again))
+        if isinstance(v, tuple):
+            return v[1] if again else v[0]
+        return v
+    return rate
+
+
+def planted_rate(truth, noise=0.0, seed=0):
+    rng = np.random.default_rng(seed)
+    def rate(a, b, again=False):
+        base = SAME if truth[a] == truth[b] else CROSS
+        return base * (1.0 + noise * abs(rng.standard_normal()) * -1.0)      # disturbances only slow a launch down
+    return rate
+
+
+def canonical(labels):
+    ids = {}
+    return [ids.setdefault(z, len(ids)) for z in labels]
+
+
+def test_worked_example_two_zones():
+    """n = 4, min_gap = 0.02.  Anchors 100.  Row: (0,1) 100, (0,2) 95, (0,3) 95.2.  low = {95, 95.2}, median 95.1 <
+    100 * (1 - 0.028) = 97.2 -> two clusters, cut = (100 + 95.1) / 2 = 97.55, band = 0.6125.  Zone 0 = {0, 1}.
+    Window 2 opens zone 1; rate(2,3) = 99.5 >= cut -> [0, 0, 1, 1].  Rates consulted: 2 x 4 anchors + 3 + 1 = 12."""
+    t = {(p, p): 100.0 for p in range(4)}
+    t.update({(0, 1): 100.0, (0, 2): 95.0, (0, 3): 95.2, (2, 3): 99.5})
+    d = {}
+    assert zones_from_pair_rates(table_rate(t), 4, 0.02, details=d) == [0, 0, 1, 1]
+    assert d["same"] == 100.0 and d["cut"] == pytest.approx(97.55, abs=1e-12) and d["band"] == pytest.approx(0.6125, abs=1e-12)
+    assert d["n_zones"] == 2 and d["pair_rates"] == 12 and not d["gave_up"]
+    t[(2, 3)] = 95.0                                    # windows 2 and 3 do not run together either: three zones
+    assert zones_from_pair_rates(table_rate(t), 4, 0.02) == [0, 0, 1, 2]
+
+
+def test_worked_example_single_cluster_uses_min_gap():
+    """No second cluster in the row (one low entry only): cut = same * (1 - min_gap) = 98, band = 0.5.  (0,2) = 97
+    is below the cut and outside the band -> window 2 is a zone of its own."""
+    t = {(p, p): 100.0 for p in range(4)}
+    t.update({(0, 1): 99.9, (0, 2): 97.0, (0, 3): 99.2, (2, 3): 90.0})
+    d = {}
+    assert zones_from_pair_rates(table_rate(t), 4, 0.02, details=d) == [0, 0, 1, 0]
+    assert d["cut"] == 98.0 and d["band"] == 0.5
+
+
+def test_anchor_is_the_largest_before_or_after_the_row():
+    """The anchors measured before the row are slow (a process' first launches), those after it are not: the cut
+    follows the later, larger value.  With the early value (97) the cut would be 95.06 and (0,2) = 96 would pass."""
+    calls = {"n": 0}
+    def rate(a, b, again=False):
+        if a == b:
+            calls["n"] += 1
+            return 97.0 if calls["n"] <= 4 else 100.0
+        return {(0, 1): 100.0, (0, 2): 96.0, (0, 3): 95.9, (2, 3): 100.0}[(min(a, b), max(a, b))]
+    d = {}
+    assert zones_from_pair_rates(rate, 4, 0.02, details=d) == [0, 0, 1, 1]
+    assert d["same"] == 100.0
+
+
+def test_rate_close_to_the_cut_is_taken_again_and_the_larger_counts():
+    t = {(p, p): 100.0 for p in range(4)}
+    t.update({(0, 1): (97.3, 99.8), (0, 2): 95.0, (0, 3): 95.2, (2, 3): (97.8, 94.0)})
+    log = []
+    # cut 97.55, band 0.6125: (0,1) first reads 97.3 (inside the band, below the cut), again 99.8 -> together;
+    # (2,3) first reads 97.8 (inside the band, above the cut), again 94.0 -> the larger still counts -> together
+    assert zones_from_pair_rates(table_rate(t, log=log), 4, 0.02) == [0, 0, 1, 1]
+    assert (0, 1, True) in log and (2, 3, True) in log and (0, 2, True) not in log
+
+
+def test_every_partition_of_six_windows_is_recovered_from_exact_rates():
+    seen = set()
+    for labels in itertools.product(range(3), repeat=6):
+        truth = tuple(canonical(labels))
+        if truth in seen:
+            continue
+        seen.add(truth)
+        assert zones_from_pair_rates(planted_rate(truth), 6, 0.02) == list(truth)
+    assert len(seen) == 122          # set partitions of 6 elements into at most 3 blocks: 1 + 31 + 90
+
+
+@pytest.mark.parametrize("truth", [
+    [0] * 12 + [1] * 12 + [2] * 8,                                   # three contiguous zones (96, 96, 64 GiB)
+    [0] * 8 + [1] * 8 + [2] * 4 + [0] * 4 + [2] * 6 + [1] * 2,      # interleaved pieces
+    [0] * 32,                                                         # one zone
+    [0, 1] * 16,                                                      # alternating
+    [0] + [1] * 31,                                                   # window 0 alone
+    list(range(16)) * 2,                                              # the most zones a map may have
+])
+def test_planted_maps_under_noise(truth):
+    for seed in range(20):
+        d = {}
+        got = zones_from_pair_rates(planted_rate(truth, noise=0.003, seed=seed), len(truth), 0.02, details=d)
+        assert got == truth, seed
+        k = max(truth) + 1
+        assert d["n_zones"] == k and d["pair_rates"] <= 8 + 31 + (k - 1) * 30
+
+
+def test_number_of_rates_consulted_for_three_contiguous_zones():
+    truth = [0] * 12 + [1] * 12 + [2] * 8
+    d = {}
+    zones_from_pair_rates(planted_rate(truth), 32, 0.02, details=d)
+    assert d["pair_rates"] == 8 + 31 + 19 + 7
+
+
+def test_too_many_zones_means_no_usable_structure():
+    truth = list(range(17))
+    d = {}
+    assert zones_from_pair_rates(planted_rate(truth), 17, 0.02, details=d) == [0] * 17
+    assert d["gave_up"] and d["n_zones"] == 1
+    d = {}
+    assert zones_from_pair_rates(planted_rate(truth[:16]), 16, 0.02, details=d) == truth[:16] and not d["gave_up"]
+
+
+def test_one_and_two_windows():
+    assert zones_from_pair_rates(planted_rate([0]), 1, 0.02) == [0]
+    assert zones_from_pair_rates(planted_rate([0, 0]), 2, 0.02) == [0, 0]
+    assert zones_from_pair_rates(planted_rate([0, 1]), 2, 0.02) == [0, 1]
