@@ -27,10 +27,20 @@ rule that turns such rates into a zone per window, step by step:
      without a zone: the first such window opens the next zone and takes every
      later window without a zone that runs together with it.
   6. more than max_zones zones: no usable structure, every window gets zone 0.
+  7. merge: rates taken while the process was still starting up can be a few
+     per cent low (seen on the GPU: the first 50 launches of one process in
+     five), which makes windows of zone 0 look foreign in step 2; they then
+     open a zone of their own in step 5.  So the zones' first windows are
+     compared once more, each pair with the longer measurement of step 4
+     (again=True): going through the zones in order, a zone whose first window
+     runs together (rate >= cut) with the first window of an earlier zone that
+     is still on its own joins that zone (the earliest such one).  Ids are then
+     renumbered in order of first appearance.
 
-Zone ids are thereby numbered in order of first appearance.  With k zones the
-rule consults at most 8 + (n - 1) + (k - 1)(n - 2) rates and, for zones that
-are found large first, far fewer.
+Zone ids are thereby numbered in order of first appearance.  With k zones
+before merging the rule consults at most 8 + (n - 1) + (k - 1)(n - 2) rates in
+steps 1-5 (for zones that are found large first, far fewer) and at most
+k (k - 1) / 2 in step 7.
 """
 from statistics import median
 from typing import Callable, Dict, List, Optional
@@ -76,7 +86,23 @@ def zones_from_pair_rates(rate: Callable[..., float], n: int, min_gap: float = 0
             if zone[b] == -1 and together(ref, b, row[b] if ref == 0 else None):
                 zone[b] = n_zones
         n_zones += 1
+    before = list(zone)
+    merge_rates = 0
+    if not gave_up:                                                              # step 7
+        firsts = [zone.index(z) for z in range(n_zones)]
+        joined = list(range(n_zones))
+        for zb in range(1, n_zones):
+            for za in range(zb):
+                if joined[za] != za:
+                    continue
+                merge_rates += 1
+                if rate(firsts[za], firsts[zb], again=True) >= cut:
+                    joined[zb] = za
+                    break
+        ids: Dict[int, int] = {}
+        zone = [ids.setdefault(joined[z], len(ids)) for z in zone]
+        n_zones = len(ids)
     if details is not None:
         details.update(same=same, cut=cut, band=band, n_zones=n_zones, pair_rates=consulted[0], gave_up=gave_up,
-                       row=[row[b] for b in range(1, n)])
+                       row=[row[b] for b in range(1, n)], merge_rates=merge_rates, zones_before_merging=before)
     return zone
