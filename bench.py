@@ -99,12 +99,13 @@ def main():
     zone_info = None
     if not args.plain_order and max_gib >= 32:
         try:
-            from paper_2405_11425_amd import zonemap
             t0 = time.perf_counter()
             whole = (max_gib // 32) * 32 * GiB
             win = whole // 32
             probe = {}
-            zone_of_window = zonemap.detect_zone_map(region, whole, n_cus, details=probe)
+            zone_of_window = rl.detect_zones(region, 32, region_bytes=whole, details=probe)
+            probe = {k: (round(v, 1) if isinstance(v, float) and k != "seconds" else v) for k, v in probe.items()}
+            probe["row"] = [round(x, 1) for x in probe["row"]]
             tried = []
             for cfg in configs:
                 if cfg.region_bytes > whole or cfg.region_bytes % win != 0:

@@ -372,6 +372,87 @@ int rr_groups_from_heatmap(const double *T, uint32_t n, const double *singles, d
                            uint16_t *group_out, uint32_t *order_out, uint32_t *n_groups_out,
                            double *threshold_out);
 
+/*
+ * Memory zones of a region from pair rates of its windows: the pair probe of
+ * the paper (Sec. 2.2) with pieces of memory in the place of compute units.
+ * The region is cut into n_windows equal windows; rate(a, b) is the read rate
+ * (any unit) while one half of the device reads window a and the other half
+ * window b.  On the MI355X a pair inside one memory zone runs a few per cent
+ * faster than a pair across two.  The rule, step by step:
+ *   1. same = the largest of rate(p, p) over p in {0, n/3, 2n/3, n-1}, each
+ *      taken once before and once after step 2 (what disturbs a launch only
+ *      ever makes it slower, and a process' first launches can run slow).
+ *   2. row[b] = rate(0, b) for b = 1 .. n-1.
+ *   3. low = the row entries below same * (1 - min_gap).  With at least two of
+ *      them and their median below same * (1 - 1.4 * min_gap) the row has two
+ *      clusters and cut = (same + median(low)) / 2; otherwise
+ *      cut = same * (1 - min_gap).  band = (same - cut) / 4.
+ *   4. a and b "run together" when rate(a, b) >= cut; a rate closer to the cut
+ *      than band is taken again (again = 1) and the larger of the two counts.
+ *   5. window 0 opens zone 0 and takes every b that runs together with it
+ *      (row[b] is the first measurement of that pair); then, while a window
+ *      has no zone, the first such window opens the next zone and takes every
+ *      later window without a zone that runs together with it.
+ *   6. more than max_zones zones: no usable structure, every window gets zone 0
+ *      (details: gave_up = 1, n_zones = 1).
+ *   7. merge: rates taken while the process was still starting up can read a
+ *      few per cent low, which makes windows of zone 0 look foreign in step 2
+ *      and open a zone of their own in step 5.  So the zones' first windows are
+ *      compared once more, each pair with again = 1: going through the zones in
+ *      order, a zone whose first window runs together (rate >= cut) with the
+ *      first window of an earlier zone that is still on its own joins the
+ *      earliest such zone.
+ * Zone ids are numbered in order of first appearance.
+ *
+ * rr_zones_from_pair_rates applies the rule to rates the caller supplies through
+ * `rate` (it must write a finite, non-negative value and return RR_OK; any other
+ * return value ends the call and is passed on).  rr_detect_zones measures them:
+ * rate(a, b) is the fastest of `launches` launches of the ticketed read kernel
+ * (128-byte lines, every wave slot occupied, iters_per_wave reads per logical
+ * wave, even compute units on window a, odd ones on window b), again = 1 runs
+ * twice as many; `warmup` untimed launches come first.
+ *   region        device, 128-byte aligned; region_bytes a multiple of n_windows * 128
+ *   n_windows     1 .. RR_MAX_ZONE_WINDOWS
+ *   opts          host or NULL; zero fields take the defaults given below
+ *   zone_of_window_out  host [n_windows]; usable as rr_launch_opts_t.zone_of_window
+ *                 when a window holds a power-of-two number of lines
+ *   details_out   host or NULL
+ * Outputs are written on success only.  The device's even and odd compute
+ * units must both exist (RR_EPLACE otherwise).
+ */
+#define RR_MAX_ZONE_WINDOWS 64u
+#define RR_MAX_ZONES 16u
+typedef int (*rr_pair_rate_fn)(uint32_t a, uint32_t b, int again, void *user, double *rate_out);
+typedef struct {
+    double min_gap;          /* default 0.02                                                   */
+    uint32_t max_zones;      /* default (and at most) RR_MAX_ZONES                             */
+    uint32_t launches;       /* timed launches per rate, the fastest counts (default 3)        */
+    uint32_t iters_per_wave; /* default 4096                                                   */
+    uint32_t warmup;         /* untimed launches before the first rate (default 32); pass
+                                RR_ZONE_NO_WARMUP for none                                     */
+    uint32_t unroll;         /* ring depth of the probe launches (default 8, which keeps them
+                                apart from a caller's own launches in a kernel trace)          */
+    uint32_t reserved;       /* must be 0                                                      */
+} rr_zone_probe_opts_t;
+#define RR_ZONE_NO_WARMUP 0xFFFFFFFFu
+typedef struct {
+    double same, cut, band;          /* steps 1 and 3, in the unit of the rates (rr_detect_zones: GB/s) */
+    double row[RR_MAX_ZONE_WINDOWS]; /* step 2; row[0] is 0                                             */
+    uint32_t n_zones;
+    uint32_t pair_rates;             /* rates consulted, those taken again not counted                  */
+    uint32_t retakes;                /* rates taken again (step 4)                                      */
+    uint32_t gave_up;                /* step 6                                                          */
+    uint32_t launches;               /* rr_detect_zones: kernel launches made, warm-up included         */
+    uint32_t merge_rates;            /* rates taken in step 7                                           */
+    double seconds;                  /* rr_detect_zones: wall time of the call                          */
+    uint8_t before_merging[RR_MAX_ZONE_WINDOWS]; /* the zones as step 5 left them                      */
+} rr_zone_probe_t;
+int rr_zones_from_pair_rates(rr_pair_rate_fn rate, void *user, uint32_t n_windows, double min_gap,
+                             uint32_t max_zones, uint8_t *zone_of_window_out, rr_zone_probe_t *details_out);
+int rr_detect_zones(const void *region, uint64_t region_bytes, uint32_t n_windows,
+                    const rr_zone_probe_opts_t *opts, void *hip_stream, uint8_t *zone_of_window_out,
+                    rr_zone_probe_t *details_out);
+
 /* Release the per-GPU scratch and cached CU tables.  Safe to call when nothing was created. */
 int rr_shutdown(void);
 

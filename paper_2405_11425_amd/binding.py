@@ -56,13 +56,30 @@ class _Opts(C.Structure):
                 ("cu_waves_out", C.POINTER(C.c_uint32))]
 
 
+class _ZoneProbeOpts(C.Structure):
+    _fields_ = [("min_gap", C.c_double), ("max_zones", C.c_uint32), ("launches", C.c_uint32),
+                ("iters_per_wave", C.c_uint32), ("warmup", C.c_uint32), ("unroll", C.c_uint32),
+                ("reserved", C.c_uint32)]
+
+
+class _ZoneProbe(C.Structure):
+    _fields_ = [("same", C.c_double), ("cut", C.c_double), ("band", C.c_double), ("row", C.c_double * 64),
+                ("n_zones", C.c_uint32), ("pair_rates", C.c_uint32), ("retakes", C.c_uint32),
+                ("gave_up", C.c_uint32), ("launches", C.c_uint32), ("merge_rates", C.c_uint32),
+                ("seconds", C.c_double), ("before_merging", C.c_uint8 * 64)]
+
+
+PAIR_RATE_FN = C.CFUNCTYPE(C.c_int, C.c_uint32, C.c_uint32, C.c_int, C.c_void_p, C.POINTER(C.c_double))
+ZONE_NO_WARMUP = 0xFFFFFFFF
+
+
 class _ReadItem(C.Structure):
     _fields_ = [("region_bytes", C.c_uint64), ("read_seed", C.c_uint64), ("opts", C.POINTER(_Opts))]
 
 
 EXPORTS = ["rr_enumerate_cus", "rr_fill", "rr_rand_read", "rr_rand_read_noalloc", "rr_rand_read_batch", "rr_probe_pair", "rr_probe_cus", "rr_seq_read", "rr_copy", "rr_chase", "rr_rand_update",
            "rr_region_granularity", "rr_region_create", "rr_region_destroy",
-           "rr_groups_from_heatmap", "rr_shutdown", "rr_strerror", "rr_last_error"]
+           "rr_groups_from_heatmap", "rr_zones_from_pair_rates", "rr_detect_zones", "rr_shutdown", "rr_strerror", "rr_last_error"]
 
 _lib = None
 
@@ -120,6 +137,12 @@ def lib():
         L.rr_groups_from_heatmap.argtypes = [C.POINTER(C.c_double), u32, C.POINTER(C.c_double), C.c_double,
                                              C.POINTER(C.c_uint16), C.POINTER(u32), C.POINTER(u32),
                                              C.POINTER(C.c_double)]
+        L.rr_zones_from_pair_rates.restype = C.c_int
+        L.rr_zones_from_pair_rates.argtypes = [PAIR_RATE_FN, vp, u32, C.c_double, u32, C.POINTER(C.c_uint8),
+                                               C.POINTER(_ZoneProbe)]
+        L.rr_detect_zones.restype = C.c_int
+        L.rr_detect_zones.argtypes = [vp, u64, u32, C.POINTER(_ZoneProbeOpts), vp, C.POINTER(C.c_uint8),
+                                      C.POINTER(_ZoneProbe)]
         L.rr_shutdown.restype = C.c_int
         L.rr_shutdown.argtypes = []
         L.rr_strerror.restype = C.c_char_p
@@ -432,6 +455,51 @@ def groups_from_heatmap(T: np.ndarray, singles: Optional[np.ndarray] = None, min
                                       order.ctypes.data_as(C.POINTER(C.c_uint32)), C.byref(ng), C.byref(thr))
     _check(rc)
     return group, order, float(thr.value)
+
+
+def _zone_details(d: _ZoneProbe, n: int) -> dict:
+    return {"same": d.same, "cut": d.cut, "band": d.band, "row": [d.row[b] for b in range(1, n)],
+            "n_zones": int(d.n_zones), "pair_rates": int(d.pair_rates), "retakes": int(d.retakes),
+            "gave_up": bool(d.gave_up), "launches": int(d.launches), "seconds": d.seconds,
+            "merge_rates": int(d.merge_rates), "zones_before_merging": [int(d.before_merging[b]) for b in range(n)]}
+
+
+def zones_from_pair_rates(rate, n_windows: int, min_gap: float = 0.02, max_zones: int = 16,
+                          details: Optional[dict] = None):
+    """zone_of_window[n_windows] by the library's rule from rates the caller supplies: rate(a, b, again) -> float
+    (see rr_zones_from_pair_rates).  An exception raised by `rate` ends the call and is raised again."""
+    raised = []
+
+    def trampoline(a, b, again, _user, out):
+        try:
+            out[0] = float(rate(a, b, bool(again)))
+            return RR_OK
+        except BaseException as e:   # must not propagate through the C frames
+            raised.append(e)
+            return RR_EINVAL
+    zone = (C.c_uint8 * max(n_windows, 1))()
+    d = _ZoneProbe()
+    rc = lib().rr_zones_from_pair_rates(PAIR_RATE_FN(trampoline), None, n_windows, min_gap, max_zones, zone, C.byref(d))
+    if raised:
+        raise raised[0]
+    _check(rc)
+    if details is not None:
+        details.update(_zone_details(d, n_windows))
+    return [int(z) for z in zone[:n_windows]]
+
+
+def detect_zones(region, n_windows: int = 32, region_bytes: Optional[int] = None, stream=None,
+                 details: Optional[dict] = None, min_gap: float = 0.0, max_zones: int = 0, launches: int = 0,
+                 iters_per_wave: int = 0, warmup: int = 0, unroll: int = 0):
+    """zone_of_window[n_windows] of the region, measured by the library (see rr_detect_zones); rates in GB/s."""
+    ptr, nbytes = _region(region, region_bytes)
+    o = _ZoneProbeOpts(min_gap, max_zones, launches, iters_per_wave, warmup, unroll, 0)
+    zone = (C.c_uint8 * max(n_windows, 1))()
+    d = _ZoneProbe()
+    _check(lib().rr_detect_zones(ptr, nbytes, n_windows, C.byref(o), _stream(stream), zone, C.byref(d)))
+    if details is not None:
+        details.update(_zone_details(d, n_windows))
+    return [int(z) for z in zone[:n_windows]]
 
 
 def shutdown() -> None:

@@ -3,6 +3,7 @@
 // (rr_rand_read, rr_probe_cus, rr_probe_pair, rr_rand_update).  The kernels are in rr_read_kernel.hpp,
 // rr_phased_kernel.hpp and rr_update_kernel.hpp and are instantiated in the rr_inst_*.hip files.
 #include <algorithm>
+#include <chrono>
 #include <cstring>
 #include <vector>
 
@@ -11,6 +12,7 @@
 #include "rr_host.hpp"
 #include "rr_phased_kernel.hpp"
 #include "rr_update_kernel.hpp"
+#include "rr_zones.hpp"
 
 using namespace rr;
 
@@ -483,9 +485,119 @@ int run_plan(const Plan &pl, const void *region, uint32_t iters, const rr_window
     return rc;
 }
 
+// ------------------------------------------------------------------ zone probe
+
+// What the measuring rate function of rr_detect_zones works with.  g_mutex is held for the whole probe.
+struct ZoneProbe {
+    DeviceState *st;
+    const void *region;
+    u64 region_bytes;
+    u32 n_windows, iters, launches, unroll;
+    hipStream_t stream;
+    u64 next_seed;
+    u32 launches_made;
+    uint16_t parity[kMaxCus];  // group of a compute unit: its dense id modulo 2
+};
+
+// One launch of the probe: even compute units read window a, odd ones window b; every wave slot is occupied.
+int zone_probe_launch(ZoneProbe &zp, u32 a, u32 b, double *gbps) {
+    const uint16_t window_of_group[2] = {(uint16_t)a, (uint16_t)b};
+    const rr_window_map_t wm = {2, zp.n_windows, zp.st->n_cus, zp.parity, window_of_group};
+    rr_launch_opts_t opts;
+    memset(&opts, 0, sizeof opts);
+    opts.unroll = zp.unroll;
+    const u64 W = (u64)zp.st->n_cus * 64;  // 32 wave slots per compute unit, two logical waves per wavefront
+    const u64 n_reads = W * zp.iters;
+    rr_result_t res;
+    Plan pl;
+    int rc = make_plan(zp.region, zp.region_bytes, 128, 32, n_reads, zp.iters, &wm, &opts, &res, pl);
+    if (rc != RR_OK) return rc;
+    rc = run_plan_locked(*zp.st, pl, zp.region, zp.iters, &wm, zp.next_seed++, zp.stream, &opts, &res);
+    if (rc != RR_OK) return rc;
+    zp.launches_made += res.launches;
+    if (!(res.kernel_ms_event > 0.0)) return fail(RR_EHIP, "a probe launch reported no time");
+    if (gbps) *gbps = (double)n_reads * 128.0 / res.kernel_ms_event / 1e6;
+    return RR_OK;
+}
+
+// rate(a, b): the fastest of the pair's launches (what disturbs a launch only ever makes it slower).
+int zone_probe_rate(uint32_t a, uint32_t b, int again, void *user, double *rate_out) {
+    ZoneProbe &zp = *(ZoneProbe *)user;
+    const u32 n = again ? 2 * zp.launches : zp.launches;
+    double best = 0.0;
+    for (u32 i = 0; i < n; ++i) {
+        double r = 0.0;
+        int rc = zone_probe_launch(zp, a, b, &r);
+        if (rc != RR_OK) return rc;
+        best = std::max(best, r);
+    }
+    *rate_out = best;
+    return RR_OK;
+}
+
 }  // namespace
 
 // ------------------------------------------------------------------ C ABI
+
+extern "C" int rr_detect_zones(const void *region, uint64_t region_bytes, uint32_t n_windows,
+                               const rr_zone_probe_opts_t *opts, void *hip_stream, uint8_t *zone_of_window_out,
+                               rr_zone_probe_t *details_out) {
+    const auto t_begin = std::chrono::steady_clock::now();
+    rr_zone_probe_opts_t o;
+    memset(&o, 0, sizeof o);
+    if (opts) o = *opts;
+    if (o.min_gap == 0.0) o.min_gap = 0.02;
+    if (o.max_zones == 0) o.max_zones = RR_MAX_ZONES;
+    if (o.launches == 0) o.launches = 3;
+    if (o.iters_per_wave == 0) o.iters_per_wave = 4096;
+    if (o.warmup == 0) o.warmup = 32;
+    if (o.warmup == RR_ZONE_NO_WARMUP) o.warmup = 0;
+    if (o.unroll == 0) o.unroll = 8;
+    if (!region) return fail(RR_EINVAL, "region is NULL");
+    int rc = check_zone_rule_args(n_windows, o.min_gap, o.max_zones, zone_of_window_out);
+    if (rc != RR_OK) return rc;
+    if (o.reserved != 0) return fail(RR_EINVAL, "reserved must be 0");
+    if (o.launches > 64) return fail(RR_EINVAL, "at most 64 launches per rate");
+    if (o.warmup > 4096) return fail(RR_EINVAL, "at most 4096 warm-up launches");
+    if ((uintptr_t)region % 128 != 0) return fail(RR_EINVAL, "region is not aligned to 128 bytes");
+    if (region_bytes == 0 || region_bytes % ((u64)n_windows * 128) != 0)
+        return fail(RR_EINVAL, "region_bytes must be a positive multiple of n_windows lines of 128 bytes");
+    if (region_bytes / 128 > (1ull << 32)) return fail(RR_EINVAL, "region has more than 2^32 lines");
+    if (!find_read_kernel_32_1(o.unroll, RR_BCAST_DPP, 1))
+        return fail(RR_EINVAL, "unroll %u is not built for 128-byte lines", o.unroll);
+
+    hipStream_t stream = (hipStream_t)hip_stream;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    static ZoneProbe zp;  // guarded by g_mutex; static so that the call does not put 2 KB of table on the stack
+    rc = get_state(stream, &zp.st);
+    if (rc != RR_OK) return rc;
+    if (zp.st->n_cus < 2) return fail(RR_EPLACE, "the probe needs at least two compute units");
+    zp.region = region;
+    zp.region_bytes = region_bytes;
+    zp.n_windows = n_windows;
+    zp.iters = o.iters_per_wave;
+    zp.launches = o.launches;
+    zp.unroll = o.unroll;
+    zp.stream = stream;
+    zp.next_seed = 1000;
+    zp.launches_made = 0;
+    for (u32 c = 0; c < zp.st->n_cus; ++c) zp.parity[c] = (uint16_t)(c & 1u);
+    for (u32 i = 0; i < o.warmup; ++i) {
+        rc = zone_probe_launch(zp, 0, 0, nullptr);
+        if (rc != RR_OK) return rc;
+    }
+    uint8_t zone[RR_MAX_ZONE_WINDOWS];
+    rr_zone_probe_t d;
+    rc = zones_rule(zone_probe_rate, &zp, n_windows, o.min_gap, o.max_zones, zone, &d);
+    if (rc != RR_OK) return rc;
+    memcpy(zone_of_window_out, zone, n_windows);
+    if (details_out) {
+        d.launches = zp.launches_made;
+        d.seconds = std::chrono::duration<double>(std::chrono::steady_clock::now() - t_begin).count();
+        *details_out = d;
+    }
+    return RR_OK;
+}
 
 extern "C" int rr_rand_read(const void *region, uint64_t region_bytes, uint32_t line_bytes,
                             uint32_t lanes_per_line, uint64_t n_reads, uint32_t iters_per_wave,

@@ -136,8 +136,7 @@ class Runner:
         if not whole or region_bytes > whole or region_bytes % (whole // 32) != 0:
             return 1, None
         if self._zone_of_window is None:
-            from . import zonemap
-            self._zone_of_window = zonemap.detect_zone_map(self.region, whole, len(self.cus))
+            self._zone_of_window = self.rl.detect_zones(self.region, 32, region_bytes=whole)
         zm = self._zone_of_window[:region_bytes // (whole // 32)]
         ids = {z: i for i, z in enumerate(dict.fromkeys(zm))}
         return len(ids), [ids[z] for z in zm]

@@ -160,13 +160,14 @@ def test_chase_closed_cycle_over_pages(region, dist, n):
 def test_detected_zone_map_drives_the_phased_read(region):
     """The quick zone probe returns a usable map (one id per window, ids numbered by first appearance), and a read
     ordered by that map returns the checksum of the plain read."""
-    from paper_2405_11425_amd import zonemap
-    n_cus = len(rl.enumerate_cus())
     R = (region.numel() // (32 * GiB)) * 32 * GiB
     if R == 0:
         pytest.skip("region too small for 32 windows of whole GiB")
-    zm = zonemap.detect_zone_map(region, R, n_cus)
-    assert len(zm) == 32 and zm[0] == 0 and max(zm) < 16
+    d = {}
+    zm = rl.detect_zones(region, 32, region_bytes=R, details=d)
+    print(f"\n[zones] {zm}\n[zones] " + str({k: v for k, v in d.items() if k != "row"}), flush=True)
+    assert len(zm) == 32 and zm[0] == 0 and max(zm) < 16 and d["n_zones"] == max(zm) + 1
+    assert d["launches"] >= 3 * d["pair_rates"] and d["cut"] < d["same"] and len(d["row"]) == 31
     assert all(z <= max(zm[:i]) + 1 for i, z in enumerate(zm) if i)          # numbered by first appearance
     W, I = 4096, 512
     plain = rl.rand_read(region, 128, W * I, I, 21, region_bytes=R)
@@ -670,8 +671,7 @@ def zone_map(region):
     """zone_of_window for the whole allocation in 32 windows, from the quick probe (what bench.py orders its
     largest regions by)."""
     need(region, 256)
-    from paper_2405_11425_amd import zonemap
-    zm = zonemap.detect_zone_map(region, 256 * GiB, len(rl.enumerate_cus()))
+    zm = rl.detect_zones(region, 32, region_bytes=256 * GiB)
     print(f"\n[zone map] {zm}", flush=True)
     return zm
 

@@ -41,7 +41,8 @@ def test_header_is_plain_c(tmp_path):
     inc = os.path.join(os.path.dirname(os.path.abspath(__file__)), "..", "include")
     b = rl.binding
     mirrors = {"rr_launch_opts_t": b._Opts, "rr_result_t": b._Result, "rr_window_map_t": b._WindowMap,
-               "rr_chase_result_t": b._ChaseResult, "rr_read_item_t": b._ReadItem}
+               "rr_chase_result_t": b._ChaseResult, "rr_read_item_t": b._ReadItem,
+               "rr_zone_probe_opts_t": b._ZoneProbeOpts, "rr_zone_probe_t": b._ZoneProbe}
     prints = []
     for cname, mirror in mirrors.items():
         prints.append(f'printf("%zu\\n", sizeof({cname}));')
@@ -240,53 +241,6 @@ def test_chase_validation():
         with pytest.raises(rl.RandlineError) as e:
             rl.chase(*args)
         assert e.value.code == rl.RR_EINVAL and needle in str(e.value)
-
-
-@pytest.mark.parametrize("planted", [
-    [0] * 12 + [1] * 12 + [2] * 8,                                   # three contiguous zones (96, 96, 64 GiB)
-    [0] * 8 + [1] * 8 + [2] * 4 + [0] * 4 + [2] * 6 + [1] * 2,      # interleaved pieces
-    [0] * 32,                                                         # one zone
-    [0, 1] * 16,                                                      # alternating
-])
-def test_zone_probe_recovers_a_planted_map(monkeypatch, planted):
-    """The zone probe's logic against a stand-in for the library: pairs of windows in one planted zone run 4 % faster
-    than pairs across zones.  Two kinds of noise, both worse than measured on the GPU: launches that scatter by 0.8 %,
-    one in 50 of them 5 % slow and one in 100 2 % fast; and a busy box, where launches scatter by 0.6 % and every
-    third one is slower by 1-8 %.  In every third stream the process also starts slow, as seen on the GPU: the first
-    150 launches lose 2.5 %.  The probe must return the planted partition for every noise stream."""
-    from paper_2405_11425_amd import zonemap
-    for stream in range(24):
-        rng = np.random.default_rng(1000 + stream)
-        busy = stream % 2 == 1
-        slow_start = [150 if stream % 3 == 0 else 0]
-
-        def fake_read(region, line_bytes, n_reads, iters, seed, wm, region_bytes=None, **kw):
-            a, b = (int(x) for x in wm.window_of_group)
-            rate = 6800.0 if planted[a] == planted[b] else 6540.0
-            if slow_start[0] > 0:
-                slow_start[0] -= 1
-                rate *= 0.975
-            if busy:
-                rate *= 1.0 + rng.normal(0.0, 0.006)
-                if rng.integers(3) == 0:
-                    rate *= 1.0 - rng.uniform(0.01, 0.08)
-            else:
-                rate *= 1.0 + rng.normal(0.0, 0.008)
-                if rng.integers(50) == 0:
-                    rate *= 0.95
-                if rng.integers(100) == 0:
-                    rate *= 1.02
-            return rl.ReadResult(0, n_reads * line_bytes / rate / 1e6, 0.0, 0, 1)
-
-        monkeypatch.setattr(zonemap.rl, "rand_read", fake_read)
-        got = zonemap.detect_zone_map(None, 256 << 30, 256)
-        relabel = {}
-        for g, p in zip(got, planted):
-            assert relabel.setdefault(g, p) == p, (stream, got)   # every found zone lies inside one planted zone ...
-        assert len(relabel) == len(set(planted)), (stream, got)   # ... and there are exactly as many
-        assert got[0] == 0 and all(z <= max(got[:i]) + 1 for i, z in enumerate(got) if i)
-    with pytest.raises(ValueError):
-        zonemap.detect_zone_map(None, (256 << 30) + 128, 256)
 
 
 def test_verify_sweep_tool(tmp_path, worked):
