@@ -105,6 +105,12 @@ typedef struct {
 #define RR_MODE_AUTO 0
 #define RR_MODE_FLAT 1   /* one hardware wave per 64 lanes of logical waves, fixed by block index */
 #define RR_MODE_TICKET 2 /* resident waves claim logical waves of their CU's group from counters  */
+#define RR_MODE_STREAM 3 /* no window map only: a few workgroups per CU, each with a range of the
+                            work of its own that its waves take in chunks from a counter in LDS; a
+                            wave keeps its loads in flight from one chunk to the next.  The default
+                            where it applies (whole wavefronts of logical waves, chunks of a
+                            multiple of 16 iterations that divide iters_per_wave, DPP broadcast,
+                            256 threads, no placement outputs); otherwise AUTO means FLAT.          */
 
 /*
  * Optional launch controls.  NULL or a zeroed struct = defaults.  None of them
@@ -112,14 +118,18 @@ typedef struct {
  */
 typedef struct {
     uint32_t block_threads;  /* 64, 128 or 256 (default 256)                                      */
-    uint32_t grid_blocks;    /* ticket mode: workgroups per launch (default: the resident capacity;
-                                pinned runs: 64 x that).  Flat mode ignores it.                   */
+    uint32_t grid_blocks;    /* ticket mode: workgroups per launch (default: eight wavefronts per
+                                CU, zone-phased reads the resident capacity; pinned runs: 64 x the
+                                wave slots).  Stream mode: the same (default: two workgroups per
+                                CU).  Flat mode ignores it.                                       */
     uint32_t unroll;         /* loads kept in flight per wave: 2, 4, 8 or 16 (default by line width) */
     uint32_t mode;           /* RR_MODE_*                                                          */
     uint32_t bcast;          /* RR_BCAST_*                                                         */
     uint32_t nontemporal;    /* RR_NT_*                                                            */
     uint32_t chunk_iters;    /* iterations of a logical wave executed per ticket / hardware wave: a
-                                multiple of 64; 0 = default (flat: all of them; ticketed: 1024)    */
+                                multiple of 64; 0 = default (flat: all of them; ticketed: 1024;
+                                stream: 256, or the largest of 128 ... 16 that divides
+                                iters_per_wave)                                                    */
     uint32_t reserved;       /* must be 0                                                          */
     uint64_t first_wave;     /* id of the first logical wave (default 0); multiple of n_groups     */
     uint64_t zone_bytes;     /* 0 = off.  Otherwise the region is cut into zones of this many bytes
@@ -427,11 +437,10 @@ typedef struct {
     double min_gap;          /* default 0.02                                                   */
     uint32_t max_zones;      /* default (and at most) RR_MAX_ZONES                             */
     uint32_t launches;       /* timed launches per rate, the fastest counts (default 3)        */
-    uint32_t iters_per_wave; /* default 4096                                                   */
+    uint32_t iters_per_wave; /* default 2048                                                   */
     uint32_t warmup;         /* untimed launches before the first rate (default 32); pass
                                 RR_ZONE_NO_WARMUP for none                                     */
-    uint32_t unroll;         /* ring depth of the probe launches (default 8, which keeps them
-                                apart from a caller's own launches in a kernel trace)          */
+    uint32_t unroll;         /* ring depth of the probe launches (default 16)                  */
     uint32_t reserved;       /* must be 0                                                      */
 } rr_zone_probe_opts_t;
 #define RR_ZONE_NO_WARMUP 0xFFFFFFFFu

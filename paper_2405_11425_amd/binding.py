@@ -17,7 +17,7 @@ from . import build as _build
 RR_OK, RR_EINVAL, RR_EHIP, RR_EPLACE = 0, -1, -2, -3
 RR_CU_EXCLUDED = 0xFFFF
 BCAST_DEFAULT, BCAST_LDS, BCAST_DPP, BCAST_READLANE = 0, 1, 2, 3
-MODE_AUTO, MODE_FLAT, MODE_TICKET = 0, 1, 2
+MODE_AUTO, MODE_FLAT, MODE_TICKET, MODE_STREAM = 0, 1, 2, 3
 NT_DEFAULT, NT_ON, NT_OFF = 0, 1, 2
 OP_WRITE, OP_ADD = 1, 2
 

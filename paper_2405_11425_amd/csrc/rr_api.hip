@@ -35,6 +35,9 @@ const Family *find_family(u32 lanes, u32 wdw) {
     return nullptr;
 }
 
+constexpr u32 kTicketWavesPerCu = 8;   // default grid of the plain ticketed kernel, in wavefronts per compute unit
+constexpr u32 kStreamBlocksPerCu = 2;  // default grid of the stream kernel: workgroups (of four wavefronts) per compute unit
+
 // Validated description of one read call.
 struct Plan {
     u64 n_lines = 0, W = 0, first_wave = 0;
@@ -104,7 +107,7 @@ int make_plan(const void *region, uint64_t region_bytes, uint32_t line_bytes, ui
         if (opts->bcast) pl.bcast = opts->bcast;
         if (opts->nontemporal > RR_NT_OFF) return fail(RR_EINVAL, "nontemporal must be 0, 1 or 2");
         if (opts->nontemporal) pl.nt = opts->nontemporal == RR_NT_ON ? 1u : 0u;
-        if (opts->mode > RR_MODE_TICKET) return fail(RR_EINVAL, "unknown mode value");
+        if (opts->mode > RR_MODE_STREAM) return fail(RR_EINVAL, "unknown mode value");
         pl.mode = opts->mode;
         pl.grid_blocks = opts->grid_blocks;
         if (opts->chunk_iters % 64 != 0) return fail(RR_EINVAL, "chunk_iters must be a multiple of 64");
@@ -151,13 +154,7 @@ int make_plan(const void *region, uint64_t region_bytes, uint32_t line_bytes, ui
             while ((1ull << pl.zone_shift) < window_lines) pl.zone_shift++;
         }
     }
-    pl.kernel = pl.family->find(pl.unroll, pl.bcast, pl.nt);
-    if (!pl.kernel) return fail(RR_EINVAL, "unroll %u is not built for this line shape", pl.unroll);
-    if (pl.n_zones) {
-        pl.kernel = find_phased_kernel(pl.lanes, pl.wdw, pl.nt);
-        if (!pl.kernel) return fail(RR_EINVAL, "no zone-phased kernel for this line shape");
-        pl.block = 256;  // its LDS lists are laid out for four waves per workgroup
-    }
+    if (pl.n_zones) pl.block = 256;  // the phased kernel's LDS lists are laid out for four waves per workgroup
     bool needs_tickets = false;
     if (wm) {
         if (wm->n_groups > 1) needs_tickets = true;
@@ -169,8 +166,37 @@ int make_plan(const void *region, uint64_t region_bytes, uint32_t line_bytes, ui
     }
     if (pl.mode == RR_MODE_FLAT && needs_tickets)
         return fail(RR_EINVAL, "flat mode cannot honour a window map with several groups or excluded CUs");
+    // The stream kernel serves launches without a map, in whole units, whose chunks are a multiple of 16 iterations
+    // that divides the iterations of a wave.
+    const u32 lpw = 64 / pl.lanes;
+    const char *no_stream = nullptr;
+    u32 stream_chunk = pl.chunk_iters;
+    if (!stream_chunk)
+        for (stream_chunk = 256; stream_chunk > 16 && iters % stream_chunk != 0;) stream_chunk /= 2;
+    if (wm) no_stream = "a window map";
+    else if (pl.n_zones) no_stream = "zones";
+    else if (opts && (opts->placement_out || opts->cu_waves_out)) no_stream = "a placement log or per-CU counts";
+    else if (pl.bcast != RR_BCAST_DPP) no_stream = "a broadcast other than DPP";
+    else if (pl.W % lpw != 0) no_stream = "an odd number of 32-lane logical waves";
+    else if (iters % stream_chunk != 0 || stream_chunk % 16 != 0) no_stream = "chunks that are not a multiple of 16 iterations dividing iters_per_wave";
+    else if (pl.block != 256) no_stream = "workgroups of other than 256 threads";
+    else if (!find_stream_kernel(pl.lanes, pl.wdw, pl.unroll, pl.nt)) no_stream = "this ring depth";
+    else if ((pl.W / lpw) * (u64)(iters / stream_chunk) >= (1ull << 31)) no_stream = "2^31 tickets or more";
+    if (pl.mode == RR_MODE_STREAM && no_stream) return fail(RR_EINVAL, "stream mode does not work with %s", no_stream);
     // zone-phased reads line their phases up only when the work is handed out zone-major by tickets
-    if (pl.mode == RR_MODE_AUTO) pl.mode = (needs_tickets || pl.n_zones) ? RR_MODE_TICKET : RR_MODE_FLAT;
+    if (pl.mode == RR_MODE_AUTO)
+        pl.mode = (needs_tickets || pl.n_zones) ? RR_MODE_TICKET : no_stream ? RR_MODE_FLAT : RR_MODE_STREAM;
+    if (pl.mode == RR_MODE_STREAM) {
+        pl.chunk_iters = stream_chunk;
+        pl.kernel = find_stream_kernel(pl.lanes, pl.wdw, pl.unroll, pl.nt);
+    } else if (pl.n_zones) {
+        if (!pl.family->find(pl.unroll, pl.bcast, pl.nt)) return fail(RR_EINVAL, "unroll %u is not built for this line shape", pl.unroll);
+        pl.kernel = find_phased_kernel(pl.lanes, pl.wdw, pl.nt);
+        if (!pl.kernel) return fail(RR_EINVAL, "no zone-phased kernel for this line shape");
+    } else {
+        pl.kernel = pl.family->find(pl.unroll, pl.bcast, pl.nt);
+        if (!pl.kernel) return fail(RR_EINVAL, "unroll %u is not built for this line shape", pl.unroll);
+    }
     return RR_OK;
 }
 
@@ -245,8 +271,9 @@ struct Launch {
     u32 reset_bits = 0;  // what reset_kernel has to clear first, the result cells aside
 };
 
-int make_launch(const Plan &pl, DeviceState &st, const void *region, uint32_t iters, bool has_map, uint64_t read_seed,
-                const rr_launch_opts_t *opts, u16 *placement, Launch &ln) {
+int make_launch(const Plan &pl, DeviceState &st, const void *region, uint32_t iters, const rr_window_map_t *wm,
+                uint64_t read_seed, const rr_launch_opts_t *opts, u16 *placement, Launch &ln) {
+    const bool has_map = wm != nullptr;
     const u32 n_cus = st.n_cus;
     const u32 lpw = 64 / pl.lanes;
     const u64 L_win = pl.n_lines / pl.n_windows;
@@ -282,11 +309,19 @@ int make_launch(const Plan &pl, DeviceState &st, const void *region, uint32_t it
 
     const u32 waves_per_block = pl.block / 64;
     u64 grid;
-    if (p.ticket_mode) {
+    if (pl.mode == RR_MODE_STREAM) {
+        // a few wavefronts per SIMD that never stop keep the memory system as busy as a full house (measured)
+        grid = pl.grid_blocks ? pl.grid_blocks : (u64)kStreamBlocksPerCu * n_cus;
+    } else if (p.ticket_mode) {
         // As many workgroups as are resident at once: work-stealing finishes the job whatever the placement, and
         // every workgroup beyond that only starts when the work is done, scans all shares and leaves -- which
         // lengthens the kernel (measured 1-2 %).  Pinned runs need many more, most land on CUs that take no part.
         u32 blocks_per_cu = resident_blocks_per_cu(pl.kernel, pl.block);
+        // The plain ticketed kernel does best with few waves: eight per compute unit keep the memory system as busy
+        // as thirty-two do and finish more evenly (measured at 64 GiB: 6.85 TB/s with 8 waves per CU, 6.81 with 16,
+        // 6.72 with 32; windowed launches at 256 GiB +2 %).  The zone-phased kernel drains its loads at every
+        // item's end and needs what fits (16 waves per CU; with 8 it loses 6 %).
+        if (!phased) blocks_per_cu = std::min(blocks_per_cu, std::max(1u, kTicketWavesPerCu / waves_per_block));
         if (pl.pinned) blocks_per_cu = (32 / waves_per_block) * 64u;
         grid = pl.grid_blocks ? pl.grid_blocks : (u64)blocks_per_cu * n_cus;
     } else {
@@ -304,7 +339,7 @@ int make_launch(const Plan &pl, DeviceState &st, const void *region, uint32_t it
     ln.reset_bits = (p.ticket_mode ? 2u : 0u) | ((p.ticket_mode || p.locate) ? 4u : 0u);
     // the plain flat launch has a kernel of its own (fewer registers, 8 resident waves per SIMD instead of 7)
     ln.kernel = pl.kernel;
-    if (!p.ticket_mode && !phased && !has_map && !p.locate) {
+    if (pl.mode == RR_MODE_FLAT && !phased && !has_map && !p.locate) {
         kernel_handle flat = find_flat_kernel(pl.lanes, pl.wdw, pl.unroll, pl.bcast, pl.nt);
         if (flat) ln.kernel = flat;
     }
@@ -384,7 +419,7 @@ int run_plan_locked(DeviceState &st, const Plan &pl, const void *region, uint32_
     const u64 quota = pl.W / pl.G;
     const u64 units = (quota + lpw - 1) / lpw;  // per group
     // a flat launch without a map reads none of the per-call table fields: reuse what is there
-    const bool flat_no_map = !wm && pl.mode == RR_MODE_FLAT;
+    const bool flat_no_map = !wm && (pl.mode == RR_MODE_FLAT || pl.mode == RR_MODE_STREAM);
     if (!(flat_no_map && st.flat_tables_ready)) {
         rc = prepare_tables(st, pl, wm, units, L_win, stream);
         if (rc != RR_OK) return rc;
@@ -407,7 +442,7 @@ int run_plan_locked(DeviceState &st, const Plan &pl, const void *region, uint32_
     }
 
     Launch ln;
-    rc = make_launch(pl, st, region, iters, wm != nullptr, read_seed, opts, want_placement ? st.placement : nullptr, ln);
+    rc = make_launch(pl, st, region, iters, wm, read_seed, opts, want_placement ? st.placement : nullptr, ln);
     if (rc != RR_OK) return rc;
     const ReadParams &p = ln.p;
     const bool want_cu_waves = opts && opts->cu_waves_out;
@@ -549,10 +584,10 @@ extern "C" int rr_detect_zones(const void *region, uint64_t region_bytes, uint32
     if (o.min_gap == 0.0) o.min_gap = 0.02;
     if (o.max_zones == 0) o.max_zones = RR_MAX_ZONES;
     if (o.launches == 0) o.launches = 3;
-    if (o.iters_per_wave == 0) o.iters_per_wave = 4096;
+    if (o.iters_per_wave == 0) o.iters_per_wave = 2048;
     if (o.warmup == 0) o.warmup = 32;
     if (o.warmup == RR_ZONE_NO_WARMUP) o.warmup = 0;
-    if (o.unroll == 0) o.unroll = 8;
+    if (o.unroll == 0) o.unroll = 16;
     if (!region) return fail(RR_EINVAL, "region is NULL");
     int rc = check_zone_rule_args(n_windows, o.min_gap, o.max_zones, zone_of_window_out);
     if (rc != RR_OK) return rc;
@@ -664,7 +699,7 @@ extern "C" int rr_rand_read_batch(const void *region, const rr_read_item_t *item
     if (rc != RR_OK) return rc;
     std::vector<Launch> launches(n_items);
     for (u32 i = 0; i < n_items; ++i) {
-        rc = make_launch(plans[i], st, region, iters_per_wave, false, items[i].read_seed, items[i].opts, nullptr,
+        rc = make_launch(plans[i], st, region, iters_per_wave, nullptr, items[i].read_seed, items[i].opts, nullptr,
                          launches[i]);
         if (rc != RR_OK) return rc;
     }
@@ -728,7 +763,13 @@ extern "C" int rr_probe_cus(const void *region, uint64_t region_bytes, const uin
     // the zone-phased kernel knows no excluded compute units: its waves would run everywhere and steal the targets' work
     if (opts && (opts->zone_bytes || opts->zone_of_window || opts->phase_ticks))
         return fail(RR_EINVAL, "a pinned run cannot be zone-phased");
-    // validate everything else before touching the device (map filled in below)
+    // validate everything else before touching the device (map filled in below); a pinned run is a ticketed one
+    rr_launch_opts_t ticketed;
+    memset(&ticketed, 0, sizeof ticketed);
+    if (opts) ticketed = *opts;
+    ticketed.mode = RR_MODE_TICKET;
+    if (opts && opts->mode == RR_MODE_STREAM) return fail(RR_EINVAL, "a pinned run cannot use stream mode");
+    opts = &ticketed;
     Plan pl;
     int rc = make_plan(region, region_bytes, 128, 32, n_reads, iters_per_wave, nullptr, opts, out, pl);
     if (rc != RR_OK) return rc;

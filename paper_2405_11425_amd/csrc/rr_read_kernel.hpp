@@ -157,7 +157,7 @@ __device__ __forceinline__ u64 read_logical_wave(const char *region, u64 wave_se
 //                 per CU, ballot) and drains whatever shares are still open, so
 //                 every ticket is executed even if some CU received no wave.
 template <int LANES, int WDW, int U, int BC, int NT>
-__global__ void __launch_bounds__(256) rand_read_kernel(const ReadParams p) {
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_num_sgpr(80))) rand_read_kernel(const ReadParams p) {
     constexpr u32 LPW = 64 / LANES;  // logical waves per hardware wave
     constexpr u32 kNone = 0xFFFFFFFFu;
     const u32 lane = threadIdx.x & 63;
@@ -181,22 +181,15 @@ __global__ void __launch_bounds__(256) rand_read_kernel(const ReadParams p) {
         if (lane == 0) t = atomicAdd(&s->tickets[cu * kTicketStride], 1u);
         return __builtin_amdgcn_readfirstlane(t);
     };
-    // scan state for stealing: candidates of the current 64-CU window, one per lane
-    const u32 g_begin = tb->group_begin[group];
-    const u32 g_count = tb->group_begin[group + 1] - g_begin;
-    const u32 my_pos = tb->cu_pos[dense];
-    u32 scan_base = 0, cand = 0;
-    unsigned long long open_mask = 0;
+    // stealing: scan the group's other CUs, 64 at a time (one per lane), starting behind this CU
     auto next_victim = [&]() -> u32 {
-        for (;;) {
-            if (open_mask) {
-                const u32 l = (u32)__builtin_ctzll(open_mask);
-                open_mask &= open_mask - 1;
-                return __builtin_amdgcn_readlane(cand, l);
-            }
-            if (scan_base + 1 >= g_count) return kNone;  // the ring minus this CU has g_count-1 entries
+        const u32 g_begin = tb->group_begin[group];
+        const u32 g_count = tb->group_begin[group + 1] - g_begin;
+        const u32 my_pos = tb->cu_pos[dense];
+        for (u32 scan_base = 0; scan_base + 1 < g_count; scan_base += 64) {  // the ring minus this CU has g_count-1 entries
             const u32 pos = scan_base + lane;
             bool open = false;
+            u32 cand = 0;
             if (pos + 1 < g_count) {
                 u32 ring = my_pos + 1 + pos;
                 if (ring >= g_count) ring -= g_count;
@@ -205,9 +198,10 @@ __global__ void __launch_bounds__(256) rand_read_kernel(const ReadParams p) {
                                                     __HIP_MEMORY_SCOPE_AGENT);
                 open = taken < tb->cu_unit_count[cand] * cpw;
             }
-            open_mask = __ballot(open);
-            scan_base += 64;
+            const unsigned long long open_mask = __ballot(open);
+            if (open_mask) return __builtin_amdgcn_readlane(cand, (u32)__builtin_ctzll(open_mask));
         }
+        return kNone;
     };
 
     u32 cur = dense;          // CU whose share is being drained
@@ -222,7 +216,6 @@ __global__ void __launch_bounds__(256) rand_read_kernel(const ReadParams p) {
         ticket = launch_index;
     }
     u64 acc = 0;
-    u64 t0 = 0;
     bool worked = false;
     for (;;) {
         if (ticket >= limit) {
@@ -239,9 +232,10 @@ __global__ void __launch_bounds__(256) rand_read_kernel(const ReadParams p) {
         else ticket = kNone;
         const u32 unit = this_ticket / cpw;
         const u32 chunk = this_ticket - unit * cpw;
-        if (!worked) {
+        if (!worked) {  // the start time goes to the wave's cell at once, so that it need not be kept
             worked = true;
-            t0 = clock_ticks();
+            const u64 t0 = clock_ticks();
+            if (lane == 0) atomicMin(&s->cells[launch_index & (kNumCells - 1)].t_min, t0);
         }
         const u64 j0 = (u64)(unit_begin + unit) * LPW;  // index, within the group, of the lower logical wave
         u64 j = j0 + half;
@@ -262,7 +256,6 @@ __global__ void __launch_bounds__(256) rand_read_kernel(const ReadParams p) {
     if (lane == 0) {
         Cell *c = &s->cells[launch_index & (kNumCells - 1)];
         atomicAdd(&c->sum, total);
-        atomicMin(&c->t_min, t0);
         atomicMax(&c->t_max, t1);
         atomicAdd(&c->waves, 1u);
         if (p.ticket_mode || p.locate) atomicAdd(&s->cu_waves[dense], 1u);
@@ -304,6 +297,109 @@ __global__ void __launch_bounds__(256) rand_read_flat_kernel(const ReadParams p)
     }
 }
 
+// The launch without a window map as one uninterrupted stream of loads per wave.
+//
+// Measured on the MI355X: a few wavefronts per SIMD keep the memory system as busy as a full house does (two
+// per SIMD with 16 loads each in flight reach the rate of eight), provided that they never stop -- and a launch
+// that gives every wave slot one unit and lets it run loses a few per cent at its end, because the hardware
+// serves the oldest waves first and the slots of those that have finished stay empty.  So this kernel starts few
+// workgroups (a multiple of the number of compute units) and lets their waves take work in small pieces:
+//   * every workgroup owns a contiguous range of tickets (ticket = unit * chunks_per_wave + chunk) and hands them
+//     out to its waves from a counter in LDS.  An LDS atomic returns through the LDS counter of the wave, not
+//     through the one the global loads use, so that asking for the next ticket does not wait for the loads in
+//     flight;
+//   * the ring of U loads is never drained between tickets: the batch loop is one loop, in which the addresses
+//     of the next batch come either from the same ticket or, at a ticket's end, from the next one.
+// A ticket therefore costs a few dozen instructions and can be short (256 iterations), which makes the waves of
+// a workgroup finish within microseconds of each other; the workgroups have equal ranges.  Needs whole units
+// (an even number of logical waves when two share a wavefront) and chunks of a multiple of 16 iterations that
+// divide the iterations of a wave; the host falls back to rand_read_flat_kernel otherwise.
+template <int LANES, int WDW, int U, int NT>
+__global__ void __launch_bounds__(256) rand_read_stream_kernel(const ReadParams p) {
+    typedef typename Vec<WDW>::type V;
+    constexpr u32 LPW = 64 / LANES;
+    constexpr int ITB = 16;  // iterations per batch: DPP row broadcast
+    static_assert(ITB % U == 0, "ring must divide the batch");
+    __shared__ u32 next_ticket;
+    const u32 lane = threadIdx.x & 63;
+    const u32 half = (LANES == 32) ? (lane >> 5) : 0;
+    const u32 itl = lane & (ITB - 1);
+    const u32 sub_bytes = (lane & (LANES - 1)) * (WDW * 4);
+    const u32 launch_index = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    const u32 cpw = p.chunks_per_wave;
+    const u64 total = (p.quota / LPW) * cpw;  // tickets of the launch (the host keeps this below 2^31)
+    const u32 t_begin = (u32)(total * blockIdx.x / gridDim.x);
+    const u32 t_end = (u32)(total * (blockIdx.x + 1) / gridDim.x);
+    if (threadIdx.x == 0) next_ticket = t_begin;
+    __syncthreads();
+    auto claim = [&]() -> u32 {
+        u32 t = 0;
+        if (lane == 0) t = atomicAdd(&next_ticket, 1u);
+        return __builtin_amdgcn_readfirstlane(t);
+    };
+    u32 ticket = claim();
+    if (ticket >= t_end) return;
+    const u64 t0 = clock_ticks();
+    // SplitMix64 state of this lane's first iteration of a ticket: iteration chunk * chunk_iters + itl of the
+    // logical wave unit * LPW + half
+    auto ticket_ctr = [&](u32 t) -> u64 {
+        const u32 unit = t / cpw;
+        const u32 chunk = t - unit * cpw;
+        const u64 w = p.first_wave + (u64)unit * LPW + half;
+        const u64 wave_seed = mix64(p.read_seed + (w + 1) * kGamma);
+        return wave_seed + ((u64)chunk * p.chunk_iters + itl + 1) * kGamma;
+    };
+    u64 ctr = ticket_ctr(ticket);
+    const u64 step = (u64)ITB * kGamma;
+    auto gen = [&]() -> u64 {
+        const u32 idx = reduce_to_line(mix64(ctr), p.red);
+        ctr += step;
+        return (u64)p.region + ((u64)idx << p.log2_line);
+    };
+    V ring[U];
+#pragma unroll
+    for (int j = 0; j < U; ++j) ring[j] = V(0);
+    Acc acc{0u, 0u};
+    const u32 batches_per_ticket = p.chunk_iters / ITB;
+    u32 left = batches_per_ticket;  // batches of the current ticket whose loads are still to be issued
+    u64 cur = gen();
+    bool more = true;
+    while (more) {
+        // the batch after this one: same ticket, the next ticket, or none
+        if (--left == 0) {
+            ticket = claim();
+            if (ticket >= t_end) {
+                more = false;
+            } else {
+                ctr = ticket_ctr(ticket);
+                left = batches_per_ticket;
+            }
+        }
+        const u64 nxt = gen();
+        const u32 clo = (u32)cur, chi = (u32)(cur >> 32);
+        __builtin_amdgcn_sched_barrier(0);
+        static_for<0, ITB>([&](auto kc) {
+            constexpr int K = decltype(kc)::value;
+            acc.add(ring[K % U]);  // oldest load of the ring: waits until only U-1 are outstanding
+            const u64 line = bcast_addr<LANES, BC_DPP, K>(clo, chi, lane, 0u);
+            ring[K % U] = load_line_part<NT, V>(line | sub_bytes);
+            __builtin_amdgcn_sched_barrier(0);  // keep issue order: consume slot, refill slot
+        });
+        cur = nxt;
+    }
+#pragma unroll
+    for (int j = 0; j < U; ++j) acc.add(ring[j]);
+    const u64 total_sum = wave_sum(acc.value());
+    const u64 t1 = clock_ticks();
+    if (lane == 0) {
+        Cell *c = &p.scratch->cells[launch_index & (kNumCells - 1)];
+        atomicAdd(&c->sum, total_sum);
+        atomicMin(&c->t_min, t0);
+        atomicMax(&c->t_max, t1);
+        atomicAdd(&c->waves, 1u);
+    }
+}
+
 // Each (LANES, WDW) family lives in its own translation unit and exposes a
 // finder that returns the kernel's host-side handle for (unroll, bcast,
 // nontemporal), or null if that combination is not built.
@@ -315,5 +411,7 @@ kernel_handle find_read_kernel_64_1(u32 unroll, u32 bcast, u32 nt);
 kernel_handle find_read_kernel_64_2(u32 unroll, u32 bcast, u32 nt);
 // The flat-only kernel is built for the DPP broadcast and each family's default ring depth; null otherwise.
 kernel_handle find_flat_kernel(u32 lanes, u32 wdw, u32 unroll, u32 bcast, u32 nt);
+// The stream kernel (DPP broadcast) for a line shape and ring depth; null if not built.
+kernel_handle find_stream_kernel(u32 lanes, u32 wdw, u32 unroll, u32 nt);
 
 }  // namespace rr

@@ -333,9 +333,22 @@ SMALL = [
 @pytest.mark.parametrize("R,B,lanes,W,I", SMALL)
 def test_rand_read_small(region, R, B, lanes, W, I):
     want = oracle(R, B, W, I)
-    got = rl.rand_read(region, B, W * I, I, wl.READ_SEED, lanes_per_line=lanes, region_bytes=R)
+    got = rl.rand_read(region, B, W * I, I, wl.READ_SEED, lanes_per_line=lanes, region_bytes=R, mode=rl.MODE_FLAT)
     assert got.checksum == want
     assert got.launches == 1 and got.waves_run == (W * lanes + 63) // 64
+    # the default: the stream kernel where it applies (whole wavefronts, iterations a multiple of 16), else the flat one
+    auto = rl.rand_read(region, B, W * I, I, wl.READ_SEED, lanes_per_line=lanes, region_bytes=R)
+    assert auto.checksum == want and auto.launches == 1
+    streams = (W * lanes) % 64 == 0 and I % 16 == 0
+    if streams:
+        tickets = (W * lanes // 64) * (I // next(c for c in (256, 128, 64, 32, 16) if I % c == 0))
+        assert 1 <= auto.waves_run <= min(tickets, 8 * len(rl.enumerate_cus()))
+        explicit = rl.rand_read(region, B, W * I, I, wl.READ_SEED, lanes_per_line=lanes, region_bytes=R, mode=rl.MODE_STREAM)
+        assert explicit.checksum == want
+    else:
+        assert auto.waves_run == got.waves_run
+        with pytest.raises(rl.RandlineError, match="stream mode does not work with"):
+            rl.rand_read(region, B, W * I, I, wl.READ_SEED, lanes_per_line=lanes, region_bytes=R, mode=rl.MODE_STREAM)
 
 
 def test_reference_configuration_value(region, worked):
@@ -366,6 +379,30 @@ def test_launch_geometry_does_not_change_checksum(region, B, lanes, unrolls):
             got = rl.rand_read(region, B, W * I, I, wl.READ_SEED, lanes_per_line=lanes, region_bytes=R,
                                block_threads=block, mode=mode, grid_blocks=grid)
             assert got.checksum == want, (block, mode, grid)
+
+
+@pytest.mark.parametrize("B,lanes", wl.LINE_SHAPES)
+def test_stream_geometry_does_not_change_checksum(region, B, lanes):
+    """The stream kernel (ranges of tickets per workgroup, chunks handed out from LDS, loads kept in flight across
+    chunks): ring depth, cache hint, chunk size, grid size from one workgroup to more workgroups than tickets, a
+    first wave other than 0, a region that is not a power of two."""
+    R, W, I = 3 << 24, 300, 192
+    want = oracle(R, B, W, I)
+    for unroll in (8, 16):
+        for nt in (rl.NT_ON, rl.NT_OFF):
+            for chunk, grid in ((0, 0), (64, 1), (64, 7), (192, 3), (64, 1000), (64, 5000)):
+                got = rl.rand_read(region, B, W * I, I, wl.READ_SEED, lanes_per_line=lanes, region_bytes=R,
+                                   mode=rl.MODE_STREAM, unroll=unroll, nontemporal=nt, chunk_iters=chunk, grid_blocks=grid)
+                assert got.checksum == want, (unroll, nt, chunk, grid)
+    first = 64
+    got = rl.rand_read(region, B, W * I, I, 5, lanes_per_line=lanes, region_bytes=R, mode=rl.MODE_STREAM, first_wave=first)
+    assert got.checksum == oracle(R, B, W, I, read_seed=5, first_wave=first)
+    # iterations that only 16 divides; one ticket per unit
+    got = rl.rand_read(region, B, 64 * 48, 48, 5, lanes_per_line=lanes, region_bytes=1 << 20, mode=rl.MODE_STREAM)
+    assert got.checksum == oracle(1 << 20, B, 64, 48, read_seed=5)
+    for kw in (dict(bcast=rl.BCAST_LDS), dict(block_threads=128), dict(chunk_iters=128), dict(want_cu_waves=True)):
+        with pytest.raises(rl.RandlineError, match="stream mode does not work with"):
+            rl.rand_read(region, B, W * I, I, 5, lanes_per_line=lanes, region_bytes=R, mode=rl.MODE_STREAM, **kw)
 
 
 def test_additivity_over_wave_ranges(region):
@@ -601,11 +638,17 @@ def test_region_sweep_full_size(region, cu_table):
     """Every point of the region-size sweep (all wave slots occupied, 4096 reads per logical
     wave, default launch options -- what bench.py times) against the oracle."""
     for cfg in wl.region_sweep(region.numel(), len(cu_table)):
+        want = oracle(cfg.region_bytes, cfg.line_bytes, cfg.logical_waves, cfg.iters_per_wave)
+        # the default launch: the stream kernel, two workgroups of four wavefronts per compute unit
         got = rl.rand_read(region, cfg.line_bytes, cfg.n_reads, cfg.iters_per_wave, cfg.read_seed,
                            lanes_per_line=cfg.lanes_per_line, region_bytes=cfg.region_bytes)
-        want = oracle(cfg.region_bytes, cfg.line_bytes, cfg.logical_waves, cfg.iters_per_wave)
         assert got.checksum == want, cfg.name
-        assert got.waves_run == cfg.logical_waves // 2
+        assert got.waves_run == 8 * len(cu_table)
+        # one wavefront per pair of logical waves, every wave slot of the device occupied
+        flat = rl.rand_read(region, cfg.line_bytes, cfg.n_reads, cfg.iters_per_wave, cfg.read_seed,
+                            lanes_per_line=cfg.lanes_per_line, region_bytes=cfg.region_bytes, mode=rl.MODE_FLAT)
+        assert flat.checksum == want, cfg.name
+        assert flat.waves_run == cfg.logical_waves // 2
 
 
 def test_batch_equals_single_calls(region):

@@ -33,7 +33,8 @@ def same(a, b):
 
 
 def test_two_calls_in_a_row_second_smaller(region):
-    """Flat launches: 8192 logical waves x 512 over 1 GiB, then 96 x 100 over 12 KiB (96 lines: exact remainder)."""
+    """Launches without a map: 8192 logical waves x 512 over 1 GiB (stream kernel by default, flat on request), then
+    96 x 100 over 12 KiB (96 lines: exact remainder; 100 iterations: the flat kernel)."""
     big = dict(line_bytes=128, n_reads=8192 * 512, iters_per_wave=512, read_seed=7)
     small = dict(line_bytes=128, n_reads=96 * 100, iters_per_wave=100, read_seed=11, region_bytes=12288)
     got_big = rl.rand_read_noalloc(region, **big)
@@ -42,7 +43,10 @@ def test_two_calls_in_a_row_second_smaller(region):
     want_small = rl.rand_read(region, **small)
     same(got_big, want_big)
     same(got_small, want_small)
-    assert got_big.waves_run == want_big.waves_run == 4096
+    assert got_big.waves_run == want_big.waves_run == 8 * len(rl.enumerate_cus())     # the stream kernel: 8 waves per CU
+    flat_big = rl.rand_read_noalloc(region, mode=rl.MODE_FLAT, **big)                   # one wavefront per pair
+    same(flat_big, want_big)
+    assert flat_big.waves_run == rl.rand_read(region, mode=rl.MODE_FLAT, **big).waves_run == 4096
     assert got_small.waves_run == want_small.waves_run == 48
     assert got_big.kernel_ms_device > 0 and got_big.kernel_ms_event == 0.0
     # and both equal the oracle
