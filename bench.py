@@ -12,8 +12,11 @@ timed region (the region is resident in HBM when timing starts).  Prints ONE JSO
 
 `value` is whole-job throughput: bytes read in the K timed steps / wall time between two device
 synchronisations, i.e. it includes launch, the 8-byte result read-back and host overhead.
-`roofline` is for the read kernel alone: algorithmic bytes per launch / average launch duration
-measured by the library with HIP events on the launch stream, against the 8 TB/s HBM3E peak.
+`roofline` is for the read kernels alone: algorithmic bytes per launch / average launch duration
+measured by the library with HIP events on the launch stream, against the 8 TB/s HBM3E peak; its
+top-level figures are those of the dominant kernel (the plain-order read) over regions of 4 GiB and
+more, `kernels` lists every kernel of the timed steps with its own figures, `all_timed_launches`
+is all of them together.
 `cpu_baseline` times the CPU oracle (recompute mode) on one sweep point on the host's cores and
 checks that its checksum equals the GPU's for the same arguments.
 """
@@ -31,11 +34,12 @@ HBM_PEAK_GBPS = 8000.0
 
 
 def read_traffic_file(path):
-    """HBM bytes per launch from the committed rocprofv3 --pmc summary, or None."""
+    """Bytes per launch that the L2 fetched from the fabric plus those it wrote back, from the committed rocprofv3
+    --pmc summary (FETCH_SIZE and WRITE_SIZE, each scaled by a copy of known size), or None."""
     try:
         with open(path) as f:
             for line in f:
-                if line.startswith("hbm_read_bytes_per_launch:"):
+                if line.startswith("fabric_traffic_bytes_per_launch:"):
                     return float(line.split(":", 1)[1].split()[0])
     except OSError:
         pass
@@ -132,6 +136,30 @@ def main():
             order = {cfg.name: None for cfg in configs}
             zone_info = {"error": f"{type(e).__name__}: {e}"}
 
+    # What the timed launches are, from one untimed launch of each kind: the kernel's name as a trace shows it, and
+    # how its working wavefronts spread over the XCDs.  And, as context, the same reads as one wavefront per pair of
+    # logical waves with every wave slot of the device occupied (RR_MODE_FLAT), three launches per region.
+    xcd_of_cu = cu_table[:, 0]
+    kinds = {}
+    for cfg in configs:
+        kind = "plain" if order[cfg.name] is None else "zone-by-zone"
+        if kind in kinds:
+            continue
+        kw = {"zone_of_window": order[cfg.name]} if order[cfg.name] is not None else {}
+        r = rl.rand_read(region, cfg.line_bytes, cfg.n_reads, cfg.iters_per_wave, 999, lanes_per_line=cfg.lanes_per_line,
+                         region_bytes=cfg.region_bytes, want_cu_waves=True, **kw)
+        per_xcd = [int(r.cu_waves[:n_cus][xcd_of_cu == x].sum()) for x in sorted(set(xcd_of_cu.tolist()))]
+        per_cu = r.cu_waves[:n_cus]
+        kinds[kind] = {"kernel": rl.last_kernel(), "wavefronts": int(r.waves_run), "wavefronts_per_xcd": per_xcd,
+                       "wavefronts_per_cu_min_max": [int(per_cu.min()), int(per_cu.max())]}
+    full_occupancy = []
+    for cfg in configs:
+        ms = sorted(rl.rand_read(region, cfg.line_bytes, cfg.n_reads, cfg.iters_per_wave, 3000 + i,
+                                 lanes_per_line=cfg.lanes_per_line, region_bytes=cfg.region_bytes,
+                                 mode=rl.MODE_FLAT).kernel_ms_event for i in range(3))[1]
+        full_occupancy.append({"region_gib": cfg.region_bytes // GiB, "gbps": round(cfg.bytes_read / ms / 1e6, 1)})
+    flat_kernel = rl.last_kernel()
+
     c0 = configs[0]   # the points differ in region size (and read order) only
 
     # the same calls as one by one, queued back to back with one wait at the end of the step; the arguments are
@@ -162,30 +190,51 @@ def main():
     bytes_per_step = sum(c.bytes_read for c in configs)
     value = bytes_per_step * args.steps / wall_s / 1e9
     curve = []
-    all_ms = []     # launches of the dominant kernel (the flat read kernel: most launches, most of the time)
+    groups = {}     # launches of the timed steps by kernel and region class
     for cfg in configs:
         ms = [r.kernel_ms_event for r in records[cfg.name]]
-        if order[cfg.name] is None:
-            all_ms += ms
+        ms_dev = [r.kernel_ms_device for r in records[cfg.name]]
+        kind = "plain" if order[cfg.name] is None else "zone-by-zone"
+        gib = cfg.region_bytes // GiB
+        # The device has a 256 MB memory-side cache that no counter on this machine shows: a region of 1-2 GiB may be
+        # served from it to 12-25 %, so those launches are not counted as HBM rates (4 GiB: at most 6 %).
+        cls = kind if gib >= 4 else kind + ", regions below 4 GiB"
+        groups.setdefault(cls, {"kind": kind, "regions_gib": [], "ms": []})
+        groups[cls]["regions_gib"].append(gib)
+        groups[cls]["ms"] += ms
         med = statistics.median(ms)
-        curve.append({"region_gib": cfg.region_bytes // GiB,
-                      "order": "plain" if order[cfg.name] is None else "zone-by-zone",
+        curve.append({"region_gib": gib, "order": kind,
                       "gbps": round(cfg.bytes_read / med / 1e6, 1),
                       "gbps_min": round(cfg.bytes_read / max(ms) / 1e6, 1),
                       "gbps_max": round(cfg.bytes_read / min(ms) / 1e6, 1),
                       "pct_of_hbm_peak": round(cfg.bytes_read / med / 1e6 / HBM_PEAK_GBPS * 100, 1),
-                      "kernel_ms": round(med, 4)})
+                      "kernel_ms": round(med, 4), "kernel_ms_in_kernel_clock": round(statistics.median(ms_dev), 4)})
     bytes_per_launch = configs[0].bytes_read
-    avg_ms = sum(all_ms) / len(all_ms)
-    achieved = bytes_per_launch / avg_ms / 1e6
-    roofline = {"bound": "hbm", "kernel": "rand_read_flat_kernel<32 lanes, 1 dword, ring 16, DPP broadcast, non-temporal>",
-                "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBPS, 4),
+    per_kernel = []
+    for cls, g in groups.items():
+        avg = sum(g["ms"]) / len(g["ms"])
+        per_kernel.append({"launches_of": cls, "kernel": kinds[g["kind"]]["kernel"], "regions_gib": g["regions_gib"],
+                           "launches_timed": len(g["ms"]), "avg_launch_ms": round(avg, 4),
+                           "achieved": round(bytes_per_launch / avg / 1e6, 1),
+                           "frac": round(bytes_per_launch / avg / 1e6 / HBM_PEAK_GBPS, 4),
+                           "wavefronts": kinds[g["kind"]]["wavefronts"],
+                           "wavefronts_per_xcd": kinds[g["kind"]]["wavefronts_per_xcd"],
+                           "wavefronts_per_cu_min_max": kinds[g["kind"]]["wavefronts_per_cu_min_max"]})
+    dominant = max((k for k in per_kernel if "below" not in k["launches_of"]), key=lambda k: k["launches_timed"])
+    all_ms = [m for g in groups.values() for m in g["ms"]]
+    avg_all = sum(all_ms) / len(all_ms)
+    roofline = {"bound": "hbm", "kernel": dominant["kernel"], "achieved": dominant["achieved"], "peak": HBM_PEAK_GBPS,
+                "unit": "GB/s", "frac": dominant["frac"],
                 "traffic": read_traffic_file(os.path.join(ROOT, "profiles", "rand_read_region_sweep_pmc.txt")),
-                "bytes_per_launch": bytes_per_launch, "avg_launch_ms": round(avg_ms, 4),
-                "launches_timed": len(all_ms),
-                "note": "launches in plain order only; regions read zone by zone run rand_read_phased_kernel "
-                        "(see curve[].order)"}
+                "traffic_is": "bytes per launch between the L2 and the fabric (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled "
+                              "by a copy of known size), from the committed profile of this command, not of this run; "
+                              "reads served by the 256 MB memory-side cache are included in it",
+                "bytes_per_launch": bytes_per_launch, "avg_launch_ms": dominant["avg_launch_ms"],
+                "launches_timed": dominant["launches_timed"], "regions_gib": dominant["regions_gib"],
+                "kernels": per_kernel,
+                "all_timed_launches": {"launches": len(all_ms), "avg_launch_ms": round(avg_all, 4),
+                                       "achieved": round(bytes_per_launch / avg_all / 1e6, 1),
+                                       "frac": round(bytes_per_launch / avg_all / 1e6 / HBM_PEAK_GBPS, 4)}}
 
     out = {
         "metric": "random-line read GB/s vs region size (1-256 GiB); % of 8 TB/s HBM peak",
@@ -193,8 +242,12 @@ def main():
         "ms_per_step": round(wall_s / args.steps * 1e3, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "u32", "data": "synthetic",
         "config": {"workload": "region-size sweep (configs[1]): per region size one launch with all "
-                               f"{n_cus * wl.WAVES_PER_CU} wave slots occupied, each 32-lane logical wave reading "
-                               "4096 uniformly random 128-B lines; regions are prefixes of one filled allocation; "
+                               f"{configs[0].logical_waves} 32-lane logical waves (two for each of the device's "
+                               f"{n_cus * wl.WAVES_PER_CU} wave slots), each reading "
+                               "4096 uniformly random 128-B lines, executed by 8 wavefronts per compute unit that take "
+                               "the logical waves' iterations in chunks and never let their loads run dry (measured "
+                               "faster than one wavefront per pair with every slot occupied: see full_occupancy_flat); "
+                               "regions are prefixes of one filled allocation; "
                                "regions that span several memory zones are read in whichever order was faster "
                                "before the timed steps, plain or zone by zone (same lines, same checksums); "
                                + ("one call and one wait per launch" if args.one_by_one else
@@ -210,6 +263,8 @@ def main():
         "gbps_at_largest_region": curve[-1]["gbps"],
         "fill_gbps": round(max_gib * GiB / fill_s / 1e9, 1),
         "roofline": roofline,
+        # context: the same launches as one wavefront per pair of logical waves, every wave slot occupied
+        "full_occupancy_flat": {"kernel": flat_kernel, "launches_per_region": 3, "curve": full_occupancy},
         # the paper's own figures (A100 SXM4-80GB, Sec. 2.1): context, not a target, hence vs_baseline is null
         "paper_context_a100": {"theoretical_hbm_gbps": 1900, "random_256B_lines_gbps": 1400,
                                "random_512B_lines_gbps": 1600, "throughput_collapses_above_gb": 64},

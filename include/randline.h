@@ -107,10 +107,12 @@ typedef struct {
 #define RR_MODE_TICKET 2 /* resident waves claim logical waves of their CU's group from counters  */
 #define RR_MODE_STREAM 3 /* no window map only: a few workgroups per CU, each with a range of the
                             work of its own that its waves take in chunks from a counter in LDS; a
-                            wave keeps its loads in flight from one chunk to the next.  The default
-                            where it applies (whole wavefronts of logical waves, chunks of a
-                            multiple of 16 iterations that divide iters_per_wave, DPP broadcast,
-                            256 threads, no placement outputs); otherwise AUTO means FLAT.          */
+                            wave keeps its loads in flight from one chunk to the next (and, in a
+                            zone-phased read, from one zone to the next).  The default where it
+                            applies (whole wavefronts of logical waves, chunks of a multiple of 16
+                            iterations -- zone-phased: 64 -- that divide iters_per_wave, DPP
+                            broadcast, 256 threads, no placement outputs, no phase_ticks);
+                            otherwise AUTO means FLAT, or TICKET for a zone-phased read.            */
 
 /*
  * Optional launch controls.  NULL or a zeroed struct = defaults.  None of them
@@ -137,7 +139,7 @@ typedef struct {
                                 of a power-of-two number of lines) and the lines are read zone by
                                 zone: all lines in zone 0 first, then zone 1, ...  Same
                                 lines, same checksum, different order (see "Zone-phased reads").
-                                Not with a window map.  Default mode: ticketed, zone-major order.  */
+                                Not with a window map.  Default mode: stream, else ticketed.       */
     const uint8_t *zone_of_window; /* host [n_zone_windows] or NULL: instead of zone_bytes, a zone id (< 16) for   */
     uint32_t n_zone_windows;       /* each of n_zone_windows (<= 64) equal windows of the region, each a power of
                                       two lines long -- for zones that are not contiguous (the "zones" experiment
@@ -166,6 +168,11 @@ typedef struct {
  * together inside one locality domain -- transposed from space (a window per
  * group) to time (a window per phase).  zone_bytes describes contiguous zones
  * of equal size, zone_of_window any assignment of up to 64 windows to zones.
+ * In stream mode (the default where it applies) every workgroup goes through
+ * its own share of the work zone-major; a wave collects the lines of the
+ * current zone in a small queue in LDS and reads them without ever letting
+ * its loads run dry, across tickets and zones; the workgroups stay together
+ * because their shares are statistically alike.
  */
 
 /*
@@ -420,7 +427,7 @@ int rr_groups_from_heatmap(const double *T, uint32_t n, const double *singles, d
  * rate(a, b) is the fastest of `launches` launches of the ticketed read kernel
  * (128-byte lines, every wave slot occupied, iters_per_wave reads per logical
  * wave, even compute units on window a, odd ones on window b), again = 1 runs
- * twice as many; `warmup` untimed launches come first.
+ * twice as many; a warm-up comes first (see rr_zone_probe_opts_t).
  *   region        device, 128-byte aligned; region_bytes a multiple of n_windows * 128
  *   n_windows     1 .. RR_MAX_ZONE_WINDOWS
  *   opts          host or NULL; zero fields take the defaults given below
@@ -438,8 +445,10 @@ typedef struct {
     uint32_t max_zones;      /* default (and at most) RR_MAX_ZONES                             */
     uint32_t launches;       /* timed launches per rate, the fastest counts (default 3)        */
     uint32_t iters_per_wave; /* default 2048                                                   */
-    uint32_t warmup;         /* untimed launches before the first rate (default 32); pass
-                                RR_ZONE_NO_WARMUP for none                                     */
+    uint32_t warmup;         /* untimed launches before the first rate (default 8), followed by
+                                groups of eight until the best rate of a group is within 0.5 % of
+                                the group before (a process' first launches can run slow); pass
+                                RR_ZONE_NO_WARMUP for neither                                  */
     uint32_t unroll;         /* ring depth of the probe launches (default 16)                  */
     uint32_t reserved;       /* must be 0                                                      */
 } rr_zone_probe_opts_t;
@@ -465,6 +474,10 @@ int rr_detect_zones(const void *region, uint64_t region_bytes, uint32_t n_window
 /* Release the per-GPU scratch and cached CU tables.  Safe to call when nothing was created. */
 int rr_shutdown(void);
 
+/* Name (with template arguments) of the read kernel that the calling thread's most recent rr_rand_read,
+   rr_rand_read_noalloc, rr_rand_read_batch (its last item) or probe call chose -- the name a kernel trace
+   shows; "" before the first such call. */
+const char *rr_last_kernel(void);
 /* Static description of a return code; never NULL. */
 const char *rr_strerror(int code);
 /* Message of the calling thread's most recent failure ("" if none). */

@@ -79,7 +79,7 @@ class _ReadItem(C.Structure):
 
 EXPORTS = ["rr_enumerate_cus", "rr_fill", "rr_rand_read", "rr_rand_read_noalloc", "rr_rand_read_batch", "rr_probe_pair", "rr_probe_cus", "rr_seq_read", "rr_copy", "rr_chase", "rr_rand_update",
            "rr_region_granularity", "rr_region_create", "rr_region_destroy",
-           "rr_groups_from_heatmap", "rr_zones_from_pair_rates", "rr_detect_zones", "rr_shutdown", "rr_strerror", "rr_last_error"]
+           "rr_groups_from_heatmap", "rr_zones_from_pair_rates", "rr_detect_zones", "rr_shutdown", "rr_strerror", "rr_last_error", "rr_last_kernel"]
 
 _lib = None
 
@@ -149,6 +149,8 @@ def lib():
         L.rr_strerror.argtypes = [C.c_int]
         L.rr_last_error.restype = C.c_char_p
         L.rr_last_error.argtypes = []
+        L.rr_last_kernel.restype = C.c_char_p
+        L.rr_last_kernel.argtypes = []
         _lib = L
     return _lib
 
@@ -500,6 +502,11 @@ def detect_zones(region, n_windows: int = 32, region_bytes: Optional[int] = None
     if details is not None:
         details.update(_zone_details(d, n_windows))
     return [int(z) for z in zone[:n_windows]]
+
+
+def last_kernel() -> str:
+    """Name of the read kernel this thread's last read call launched (see rr_last_kernel)."""
+    return lib().rr_last_kernel().decode()
 
 
 def shutdown() -> None:

@@ -4,6 +4,7 @@
 // rr_phased_kernel.hpp and rr_update_kernel.hpp and are instantiated in the rr_inst_*.hip files.
 #include <algorithm>
 #include <chrono>
+#include <cstdio>
 #include <cstring>
 #include <vector>
 
@@ -36,7 +37,11 @@ const Family *find_family(u32 lanes, u32 wdw) {
 }
 
 constexpr u32 kTicketWavesPerCu = 8;   // default grid of the plain ticketed kernel, in wavefronts per compute unit
+constexpr u32 kZoneStreamBlocksPerCu = 2;
 constexpr u32 kStreamBlocksPerCu = 2;  // default grid of the stream kernel: workgroups (of four wavefronts) per compute unit
+
+// Name of the kernel the calling thread's last read call launched (rr_last_kernel).
+thread_local char g_last_kernel[96] = "";
 
 // Validated description of one read call.
 struct Plan {
@@ -123,9 +128,10 @@ int make_plan(const void *region, uint64_t region_bytes, uint32_t line_bytes, ui
             if (opts->zone_bytes && opts->zone_of_window)
                 return fail(RR_EINVAL, "give either zone_bytes or zone_of_window, not both");
             if (wm) return fail(RR_EINVAL, "zone-phased reads cannot be combined with a window map");
-            if (opts->chunk_iters) return fail(RR_EINVAL, "zone-phased reads do not take chunk_iters");
-            if (opts->placement_out || opts->cu_waves_out)
-                return fail(RR_EINVAL, "zone-phased reads do not record placement");
+            if (opts->chunk_iters && opts->mode != RR_MODE_STREAM)
+                return fail(RR_EINVAL, "zone-phased reads take chunk_iters in stream mode only");
+            if (opts->placement_out || (opts->cu_waves_out && opts->mode != RR_MODE_AUTO && opts->mode != RR_MODE_STREAM))
+                return fail(RR_EINVAL, "zone-phased reads do not record placement (per-CU counts: in stream mode)");
             u64 window_lines;  // a power of two; the region has at most 64 such windows
             if (opts->zone_bytes) {
                 if (opts->zone_bytes % line_bytes != 0) return fail(RR_EINVAL, "zone_bytes must be a multiple of line_bytes");
@@ -168,27 +174,37 @@ int make_plan(const void *region, uint64_t region_bytes, uint32_t line_bytes, ui
         return fail(RR_EINVAL, "flat mode cannot honour a window map with several groups or excluded CUs");
     // The stream kernel serves launches without a map, in whole units, whose chunks are a multiple of 16 iterations
     // that divides the iterations of a wave.
+    // (zone by zone: a multiple of 64, since a producer step evaluates 64 iterations of one logical wave).
     const u32 lpw = 64 / pl.lanes;
+    const u32 chunk_unit = pl.n_zones ? 64u : 16u;
     const char *no_stream = nullptr;
     u32 stream_chunk = pl.chunk_iters;
     if (!stream_chunk)
-        for (stream_chunk = 256; stream_chunk > 16 && iters % stream_chunk != 0;) stream_chunk /= 2;
+        for (stream_chunk = 256; stream_chunk > chunk_unit && iters % stream_chunk != 0;) stream_chunk /= 2;
+    kernel_handle stream_kernel = pl.n_zones ? find_zone_stream_kernel(pl.lanes, pl.wdw, pl.nt)
+                                             : find_stream_kernel(pl.lanes, pl.wdw, pl.unroll, pl.nt);
     if (wm) no_stream = "a window map";
-    else if (pl.n_zones) no_stream = "zones";
-    else if (opts && (opts->placement_out || opts->cu_waves_out)) no_stream = "a placement log or per-CU counts";
+    else if (opts && opts->phase_ticks) no_stream = "phase_ticks";
+    else if (opts && opts->placement_out) no_stream = "a placement log";
     else if (pl.bcast != RR_BCAST_DPP) no_stream = "a broadcast other than DPP";
     else if (pl.W % lpw != 0) no_stream = "an odd number of 32-lane logical waves";
-    else if (iters % stream_chunk != 0 || stream_chunk % 16 != 0) no_stream = "chunks that are not a multiple of 16 iterations dividing iters_per_wave";
+    else if (iters % stream_chunk != 0 || stream_chunk % chunk_unit != 0)
+        no_stream = pl.n_zones ? "chunks that are not a multiple of 64 iterations dividing iters_per_wave"
+                               : "chunks that are not a multiple of 16 iterations dividing iters_per_wave";
     else if (pl.block != 256) no_stream = "workgroups of other than 256 threads";
-    else if (!find_stream_kernel(pl.lanes, pl.wdw, pl.unroll, pl.nt)) no_stream = "this ring depth";
-    else if ((pl.W / lpw) * (u64)(iters / stream_chunk) >= (1ull << 31)) no_stream = "2^31 tickets or more";
+    else if (!stream_kernel) no_stream = "this ring depth";
+    else if ((pl.W / lpw) * (u64)(iters / stream_chunk) * (pl.n_zones ? pl.n_zones : 1u) >= (1ull << 31))
+        no_stream = "2^31 tickets or more";
     if (pl.mode == RR_MODE_STREAM && no_stream) return fail(RR_EINVAL, "stream mode does not work with %s", no_stream);
-    // zone-phased reads line their phases up only when the work is handed out zone-major by tickets
+    // without the stream kernel, zone-phased reads line their phases up only when the work is handed out zone-major
+    // by tickets
     if (pl.mode == RR_MODE_AUTO)
-        pl.mode = (needs_tickets || pl.n_zones) ? RR_MODE_TICKET : no_stream ? RR_MODE_FLAT : RR_MODE_STREAM;
+        pl.mode = needs_tickets ? RR_MODE_TICKET : !no_stream ? RR_MODE_STREAM : pl.n_zones ? RR_MODE_TICKET : RR_MODE_FLAT;
+    if (pl.n_zones && pl.mode != RR_MODE_STREAM && opts && opts->cu_waves_out)
+        return fail(RR_EINVAL, "per-CU counts of a zone-phased read need stream mode, which does not work with %s", no_stream);
     if (pl.mode == RR_MODE_STREAM) {
         pl.chunk_iters = stream_chunk;
-        pl.kernel = find_stream_kernel(pl.lanes, pl.wdw, pl.unroll, pl.nt);
+        pl.kernel = stream_kernel;
     } else if (pl.n_zones) {
         if (!pl.family->find(pl.unroll, pl.bcast, pl.nt)) return fail(RR_EINVAL, "unroll %u is not built for this line shape", pl.unroll);
         pl.kernel = find_phased_kernel(pl.lanes, pl.wdw, pl.nt);
@@ -288,7 +304,7 @@ int make_launch(const Plan &pl, DeviceState &st, const void *region, uint32_t it
     p.iters = iters;
     // flat launches default to one hardware wave per whole logical wave (pair); ticketed ones to
     // chunks of 1024 iterations (shorter ones pay for draining the load ring at every chunk end)
-    const bool phased = pl.n_zones > 0;  // its chunks are what one pass through the LDS lists holds
+    const bool phased = pl.n_zones > 0 && pl.mode != RR_MODE_STREAM;  // its chunks are what one pass through the LDS lists holds
     u32 chunk = phased ? kPhaseChunk : pl.chunk_iters ? pl.chunk_iters : (pl.mode == RR_MODE_TICKET ? 1024u : iters);
     if (chunk > iters) chunk = iters;
     p.chunk_iters = chunk;
@@ -311,7 +327,7 @@ int make_launch(const Plan &pl, DeviceState &st, const void *region, uint32_t it
     u64 grid;
     if (pl.mode == RR_MODE_STREAM) {
         // a few wavefronts per SIMD that never stop keep the memory system as busy as a full house (measured)
-        grid = pl.grid_blocks ? pl.grid_blocks : (u64)kStreamBlocksPerCu * n_cus;
+        grid = pl.grid_blocks ? pl.grid_blocks : (u64)(pl.n_zones ? kZoneStreamBlocksPerCu : kStreamBlocksPerCu) * n_cus;
     } else if (p.ticket_mode) {
         // As many workgroups as are resident at once: work-stealing finishes the job whatever the placement, and
         // every workgroup beyond that only starts when the work is done, scans all shares and leaves -- which
@@ -339,10 +355,22 @@ int make_launch(const Plan &pl, DeviceState &st, const void *region, uint32_t it
     ln.reset_bits = (p.ticket_mode ? 2u : 0u) | ((p.ticket_mode || p.locate) ? 4u : 0u);
     // the plain flat launch has a kernel of its own (fewer registers, 8 resident waves per SIMD instead of 7)
     ln.kernel = pl.kernel;
+    const char *name = pl.mode == RR_MODE_STREAM ? (pl.n_zones ? "rand_read_zone_stream_kernel" : "rand_read_stream_kernel")
+                       : phased                   ? "rand_read_phased_kernel"
+                                                  : "rand_read_kernel";
     if (pl.mode == RR_MODE_FLAT && !phased && !has_map && !p.locate) {
         kernel_handle flat = find_flat_kernel(pl.lanes, pl.wdw, pl.unroll, pl.bcast, pl.nt);
-        if (flat) ln.kernel = flat;
+        if (flat) {
+            ln.kernel = flat;
+            name = "rand_read_flat_kernel";
+        }
     }
+    // template arguments as the kernels declare them: lanes per line, dwords per lane, ring depth, [broadcast,] cache hint
+    const u32 ring = pl.n_zones ? (pl.mode == RR_MODE_STREAM ? (pl.wdw == 4 ? 8u : 16u) : 32u / pl.wdw) : pl.unroll;
+    if (pl.mode == RR_MODE_STREAM || phased)
+        snprintf(g_last_kernel, sizeof g_last_kernel, "%s<%u, %u, %u, %u>", name, pl.lanes, pl.wdw, ring, pl.nt);
+    else
+        snprintf(g_last_kernel, sizeof g_last_kernel, "%s<%u, %u, %u, %u, %u>", name, pl.lanes, pl.wdw, ring, pl.bcast, pl.nt);
     return RR_OK;
 }
 
@@ -585,7 +613,7 @@ extern "C" int rr_detect_zones(const void *region, uint64_t region_bytes, uint32
     if (o.max_zones == 0) o.max_zones = RR_MAX_ZONES;
     if (o.launches == 0) o.launches = 3;
     if (o.iters_per_wave == 0) o.iters_per_wave = 2048;
-    if (o.warmup == 0) o.warmup = 32;
+    if (o.warmup == 0) o.warmup = 8;
     if (o.warmup == RR_ZONE_NO_WARMUP) o.warmup = 0;
     if (o.unroll == 0) o.unroll = 16;
     if (!region) return fail(RR_EINVAL, "region is NULL");
@@ -621,6 +649,22 @@ extern "C" int rr_detect_zones(const void *region, uint64_t region_bytes, uint32
         rc = zone_probe_launch(zp, 0, 0, nullptr);
         if (rc != RR_OK) return rc;
     }
+    // A process' first launches can run a few per cent slow, for some tens of milliseconds (seen after a fill: 80
+    // launches).  Unless the caller asked for no warm-up, go on in groups of eight until the best of a group is no
+    // longer more than 0.5 % above the best of the group before it (at most 64 groups).
+    if (o.warmup) {
+        double before = 0.0;
+        for (u32 g = 0; g < 64; ++g) {
+            double best = 0.0, r = 0.0;
+            for (u32 i = 0; i < 8; ++i) {
+                rc = zone_probe_launch(zp, 0, 0, &r);
+                if (rc != RR_OK) return rc;
+                best = std::max(best, r);
+            }
+            if (g > 0 && best <= before * 1.005) break;
+            before = best;
+        }
+    }
     uint8_t zone[RR_MAX_ZONE_WINDOWS];
     rr_zone_probe_t d;
     rc = zones_rule(zone_probe_rate, &zp, n_windows, o.min_gap, o.max_zones, zone, &d);
@@ -633,6 +677,8 @@ extern "C" int rr_detect_zones(const void *region, uint64_t region_bytes, uint32
     }
     return RR_OK;
 }
+
+extern "C" const char *rr_last_kernel(void) { return g_last_kernel; }
 
 extern "C" int rr_rand_read(const void *region, uint64_t region_bytes, uint32_t line_bytes,
                             uint32_t lanes_per_line, uint64_t n_reads, uint32_t iters_per_wave,

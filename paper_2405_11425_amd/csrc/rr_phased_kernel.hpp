@@ -220,7 +220,151 @@ __global__ void __launch_bounds__(256) rand_read_phased_kernel(const ReadParams 
     }
 }
 
+// Zone by zone as one uninterrupted stream of loads per wave (the stream kernel's way of working, see
+// rand_read_stream_kernel, applied to the zone order).
+//
+// Every workgroup owns a contiguous range of units and goes through its tickets zone-major -- ticket = (zone *
+// units + unit) * chunks + chunk, handed to its waves from a counter in LDS.  The workgroups have equal ranges and
+// are not synchronised; they advance through the zones together because their work is statistically the same.
+// A wave is a producer and a consumer in one loop:
+//   * producing: 64 lanes evaluate 64 iterations of one logical wave of the ticket, those whose line lies in the
+//     ticket's zone are appended (ballot, mbcnt) to the wave's own circular queue in LDS;
+//   * consuming: as soon as the queue holds a batch (16 load instructions' worth: 32 lines when two logical
+//     waves share a wavefront), each lane pops the entry its 16-lane row will broadcast, and the usual 16 steps
+//     "add the oldest slot of the ring, refill it with a new load" follow.
+// Which logical wave a line came from does not matter once it is in the queue -- the checksum is a plain sum -- so
+// the two halves of a wavefront simply take alternate entries, and nothing is padded.  The ring is never drained
+// between tickets or zones.  At the very end a wave fills its last batch up with entries for line 0 and
+// afterwards subtracts what those extra reads added (every lane knows its own words of line 0).
+// Needs whole units and chunks of a multiple of 64 iterations that divide the iterations of a wave.
+constexpr u32 kZoneQueue = 128;  // queue entries per wave: a batch (32) plus one producer step (64), rounded up
+
+template <int LANES, int WDW, int U, int NT>
+__global__ void __launch_bounds__(256) rand_read_zone_stream_kernel(const ReadParams p) {
+    typedef typename Vec<WDW>::type V;
+    constexpr u32 LPW = 64 / LANES;
+    constexpr int ITB = 16;                 // load instructions per batch: DPP row broadcast
+    constexpr u32 kBatch = ITB * LPW;       // queue entries a batch consumes
+    static_assert(ITB % U == 0, "ring must divide the batch");
+    static_assert(kBatch + 64 <= kZoneQueue, "queue too small");
+    __shared__ u32 next_ticket;
+    __shared__ u32 queues[4][kZoneQueue];
+    const u32 lane = threadIdx.x & 63;
+    const u32 half = (LANES == 32) ? (lane >> 5) : 0;
+    const u32 sub_bytes = (lane & (LANES - 1)) * (WDW * 4);
+    const u32 launch_index = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    u32 *queue = queues[threadIdx.x >> 6];
+    const u32 cpw = p.chunks_per_wave;
+    const u64 units_total = p.quota / LPW;
+    const u32 u_begin = (u32)(units_total * blockIdx.x / gridDim.x);
+    const u32 n_units = (u32)(units_total * (blockIdx.x + 1) / gridDim.x) - u_begin;
+    const u32 per_zone = n_units * cpw;              // tickets of this workgroup per zone
+    const u32 n_tickets = per_zone * p.n_zones;
+    if (threadIdx.x == 0) next_ticket = 0;
+    __syncthreads();
+    auto claim = [&]() -> u32 {
+        u32 t = 0;
+        if (lane == 0) t = atomicAdd(&next_ticket, 1u);
+        return __builtin_amdgcn_readfirstlane(t);
+    };
+    if (n_tickets == 0) return;
+    const u32 steps_per_wave = p.chunk_iters / 64;   // producer steps per logical wave of a ticket
+    const u32 steps_per_ticket = steps_per_wave * LPW;
+    const u64 t0 = clock_ticks();
+
+    // producer state (all wave-uniform): the ticket's zone, the seeds of its logical waves, its first iteration
+    u64 zone_mask = 0, seed_lo = 0, seed_hi = 0;
+    u32 it_base = 0;
+    u32 step = steps_per_ticket;  // "ticket used up": the first refill claims one
+    u32 head = 0, tail = 0;       // queue positions (not wrapped)
+    bool more = true, worked = false;
+
+    V ring[U];
+#pragma unroll
+    for (int j = 0; j < U; ++j) ring[j] = V(0);
+    Acc acc{0u, 0u};
+    u32 pads = 0;  // entries for line 0 that this lane's half of the wavefront read at the end
+
+    for (;;) {
+        while (tail - head < kBatch && more) {
+            if (step == steps_per_ticket) {
+                const u32 t = claim();
+                if (t >= n_tickets) {
+                    more = false;
+                    break;
+                }
+                worked = true;
+                const u32 z = t / per_zone;
+                const u32 rest = t - z * per_zone;
+                const u32 unit = rest / cpw;
+                const u32 chunk = rest - unit * cpw;
+                zone_mask = p.zone_mask[z];
+                const u64 w = p.first_wave + (u64)(u_begin + unit) * LPW;
+                seed_lo = mix64(p.read_seed + (w + 1) * kGamma);
+                if (LPW == 2) seed_hi = mix64(p.read_seed + (w + 2) * kGamma);
+                it_base = chunk * p.chunk_iters;
+                step = 0;
+            }
+            // one producer step: 64 iterations of one logical wave
+            const bool upper = (LPW == 2) && step >= steps_per_wave;
+            const u64 seed = upper ? seed_hi : seed_lo;
+            const u32 it = it_base + (upper ? step - steps_per_wave : step) * 64 + lane;
+            const u32 line = reduce_to_line(mix64(seed + ((u64)it + 1) * kGamma), p.red);
+            const bool keep = (zone_mask >> (line >> p.zone_shift)) & 1ull;
+            const unsigned long long m = __ballot(keep);
+            const u32 below = __builtin_amdgcn_mbcnt_hi((u32)(m >> 32), __builtin_amdgcn_mbcnt_lo((u32)m, 0u));
+            if (keep) queue[(tail + below) & (kZoneQueue - 1)] = line;
+            tail += (u32)__builtin_popcountll(m);
+            ++step;
+        }
+        const u32 avail = tail - head;
+        if (avail < kBatch) {  // nothing more will come: fill the last batch up, or stop
+            if (avail == 0) break;
+            if (lane < kBatch - avail) queue[(tail + lane) & (kZoneQueue - 1)] = 0u;
+            // entry k of a batch is read by half k % LPW: count this lane's half among positions avail .. kBatch-1
+            const u32 upto = (kBatch + LPW - 1 - half) / LPW, before = (avail + LPW - 1 - half) / LPW;
+            pads += upto - before;
+            tail = head + kBatch;
+        }
+        __builtin_amdgcn_wave_barrier();
+        // pop a batch: the lane takes the entry that its row broadcasts from it
+        const u32 entry = queue[(head + LPW * (lane & (ITB - 1)) + half) & (kZoneQueue - 1)];
+        head += kBatch;
+        const u64 cur = (u64)p.region + ((u64)entry << p.log2_line);
+        const u32 clo = (u32)cur, chi = (u32)(cur >> 32);
+        __builtin_amdgcn_sched_barrier(0);
+        static_for<0, ITB>([&](auto kc) {
+            constexpr int K = decltype(kc)::value;
+            acc.add(ring[K % U]);  // oldest load of the ring: waits until only U-1 are outstanding
+            const u64 line_addr = bcast_addr<LANES, BC_DPP, K>(clo, chi, lane, 0u);
+            ring[K % U] = load_line_part<NT, V>(line_addr | sub_bytes);
+            __builtin_amdgcn_sched_barrier(0);  // keep issue order: consume slot, refill slot
+        });
+    }
+    if (!worked) return;
+#pragma unroll
+    for (int j = 0; j < U; ++j) acc.add(ring[j]);
+    u64 mine = acc.value();
+    if (pads) {  // take the extra reads of line 0 out again
+        Acc one{0u, 0u};
+        one.add(load_line_part<0, V>((u64)p.region + sub_bytes));
+        mine -= (u64)pads * one.value();
+    }
+    const u64 total = wave_sum(mine);
+    const u64 t1 = clock_ticks();
+    if (lane == 0) {
+        Cell *c = &p.scratch->cells[launch_index & (kNumCells - 1)];
+        atomicAdd(&c->sum, total);
+        atomicMin(&c->t_min, t0);
+        atomicMax(&c->t_max, t1);
+        atomicAdd(&c->waves, 1u);
+        if (p.locate) atomicAdd(&p.scratch->cu_waves[p.tables->dense_of_key[cu_key()]], 1u);  // per-CU counts wanted
+    }
+}
+
 // Host-side handle of the phased kernel for a line shape, or null.
 kernel_handle find_phased_kernel(u32 lanes, u32 wdw, u32 nt);
+// The same for the zone-by-zone stream kernel (ring depth 16, or 8 for 16-byte lanes).
+kernel_handle find_zone_stream_kernel(u32 lanes, u32 wdw, u32 nt);
 
 }  // namespace rr

@@ -397,6 +397,7 @@ __global__ void __launch_bounds__(256) rand_read_stream_kernel(const ReadParams 
         atomicMin(&c->t_min, t0);
         atomicMax(&c->t_max, t1);
         atomicAdd(&c->waves, 1u);
+        if (p.locate) atomicAdd(&p.scratch->cu_waves[p.tables->dense_of_key[cu_key()]], 1u);  // per-CU counts wanted
     }
 }
 

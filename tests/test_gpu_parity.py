@@ -400,7 +400,9 @@ def test_stream_geometry_does_not_change_checksum(region, B, lanes):
     # iterations that only 16 divides; one ticket per unit
     got = rl.rand_read(region, B, 64 * 48, 48, 5, lanes_per_line=lanes, region_bytes=1 << 20, mode=rl.MODE_STREAM)
     assert got.checksum == oracle(1 << 20, B, 64, 48, read_seed=5)
-    for kw in (dict(bcast=rl.BCAST_LDS), dict(block_threads=128), dict(chunk_iters=128), dict(want_cu_waves=True)):
+    got = rl.rand_read(region, B, W * I, I, 5, lanes_per_line=lanes, region_bytes=R, mode=rl.MODE_STREAM, want_cu_waves=True)
+    assert got.checksum == oracle(R, B, W, I, read_seed=5) and int(got.cu_waves.sum()) == got.waves_run > 0
+    for kw in (dict(bcast=rl.BCAST_LDS), dict(block_threads=128), dict(chunk_iters=128), dict(want_placement=True)):
         with pytest.raises(rl.RandlineError, match="stream mode does not work with"):
             rl.rand_read(region, B, W * I, I, 5, lanes_per_line=lanes, region_bytes=R, mode=rl.MODE_STREAM, **kw)
 
@@ -468,12 +470,45 @@ def test_zone_phased_reads_same_checksum(region, R, B, lanes, W, I, zone):
             assert got.checksum == want, grid
 
 
+@pytest.mark.parametrize("B,lanes", wl.LINE_SHAPES)
+def test_zone_stream_geometry_does_not_change_checksum(region, B, lanes):
+    """Zone by zone with the stream kernel (the default for zoned reads where it applies): per-wave queues in LDS
+    filled zone by zone, loads kept in flight across tickets and zones, the last batch filled up with line 0 and
+    corrected.  Contiguous and scattered zones, one zone, sixteen zones, chunk sizes, grids from one workgroup to more
+    workgroups than units, cache hints, a first wave other than 0, a region that is not a power of two."""
+    R, W, I = 3 << 24, 300, 192
+    want = oracle(R, B, W, I)
+    scattered = [0, 1, 2, 0, 2, 1]                       # six windows of 2^23 bytes
+    for kw in (dict(zone_bytes=1 << 24), dict(zone_of_window=scattered), dict(zone_of_window=[0] * 6),
+               dict(zone_bytes=3 << 20), dict(zone_of_window=[5, 0, 5, 0, 1, 1])):
+        for nt in (rl.NT_ON, rl.NT_OFF):
+            for chunk, grid in ((0, 0), (64, 1), (64, 7), (192, 3), (64, 1000)):
+                got = rl.rand_read(region, B, W * I, I, wl.READ_SEED, lanes_per_line=lanes, region_bytes=R,
+                                   mode=rl.MODE_STREAM, nontemporal=nt, chunk_iters=chunk, grid_blocks=grid, **kw)
+                assert got.checksum == want, (kw, nt, chunk, grid)
+        assert rl.rand_read(region, B, W * I, I, wl.READ_SEED, lanes_per_line=lanes, region_bytes=R,
+                            **kw).checksum == want, kw       # the default mode
+    got = rl.rand_read(region, B, W * I, I, 5, lanes_per_line=lanes, region_bytes=R, zone_bytes=1 << 24, first_wave=64)
+    assert got.checksum == oracle(R, B, W, I, read_seed=5, first_wave=64)
+    got = rl.rand_read(region, B, W * I, I, 5, lanes_per_line=lanes, region_bytes=R, zone_bytes=1 << 24, want_cu_waves=True)
+    assert got.checksum == oracle(R, B, W, I, read_seed=5) and int(got.cu_waves.sum()) == got.waves_run > 0
+    # a region whose last zone is short, and few enough reads that most waves end on a filled-up batch
+    got = rl.rand_read(region, B, 8 * 64, 64, 5, lanes_per_line=lanes, region_bytes=5 << 22, zone_bytes=1 << 23,
+                       mode=rl.MODE_STREAM)
+    assert got.checksum == oracle(5 << 22, B, 8, 64, read_seed=5)
+    # what the stream kernel does not take goes to the ticketed zone-phased kernel by default, and is refused on request
+    odd = rl.rand_read(region, B, W * 100, 100, 5, lanes_per_line=lanes, region_bytes=R, zone_bytes=1 << 24)
+    assert odd.checksum == oracle(R, B, W, 100, read_seed=5)
+    with pytest.raises(rl.RandlineError, match="stream mode does not work with"):
+        rl.rand_read(region, B, W * 100, 100, 5, lanes_per_line=lanes, region_bytes=R, zone_bytes=1 << 24, mode=rl.MODE_STREAM)
+
+
 def test_zone_map_with_scattered_zones(region):
     """Zones given window by window, not contiguous (the way physical zones show up in an allocation)."""
     R, W, I = 1 << 30, 200, 777
     want = oracle(R, 128, W, I)
     zmap = [0] * 8 + [1] * 8 + [2] * 4 + [0] * 4 + [2] * 6 + [1] * 2
-    for mode in (rl.MODE_FLAT, rl.MODE_TICKET):
+    for mode in (rl.MODE_FLAT, rl.MODE_TICKET, rl.MODE_AUTO):
         got = rl.rand_read(region, 128, W * I, I, wl.READ_SEED, region_bytes=R, zone_of_window=zmap, mode=mode)
         assert got.checksum == want, mode
     got = rl.rand_read(region, 256, W * I, I, wl.READ_SEED, lanes_per_line=64, region_bytes=R, zone_of_window=[3, 0])

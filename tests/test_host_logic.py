@@ -120,10 +120,17 @@ def _expected_to_pass(ptr, nbytes, B, lanes, iters, wm, kw):
             return False
     if kw.get("block_threads", 0) not in (0, 64, 128, 256) or kw.get("bcast", 0) > 3 or kw.get("nontemporal", 0) > 2:
         return False
-    if kw.get("mode", 0) > 2 or kw.get("chunk_iters", 0) % 64 or kw.get("first_wave", 0) % G:
+    mode = kw.get("mode", 0)
+    if mode > 3 or kw.get("chunk_iters", 0) % 64 or kw.get("first_wave", 0) % G:
         return False
     wdw = B // lanes // 4
-    if kw.get("unroll", 0) not in ((0, 2, 4, 8) if wdw == 4 else (0, 4, 8, 16)):
+    # the stream kernel: no map, DPP broadcast, 256 threads, ring of 8 or 16, chunks of a multiple of 16 that divide iters
+    chunk = kw.get("chunk_iters", 0) or next((c for c in (256, 128, 64, 32, 16) if iters % c == 0), 16)
+    streams = (wm is None and kw.get("bcast", 0) in (0, 2) and kw.get("block_threads", 0) in (0, 256)
+               and (kw.get("unroll", 0) or (8 if wdw == 4 else 16)) in (8, 16) and iters % chunk == 0 and chunk % 16 == 0)
+    if mode == rl.MODE_STREAM:
+        return streams
+    if not (mode == rl.MODE_AUTO and streams) and kw.get("unroll", 0) not in ((0, 2, 4, 8) if wdw == 4 else (0, 4, 8, 16)):
         return False
     if wm is not None and kw.get("mode", 0) == rl.MODE_FLAT and (G > 1 or (wm.group_of_cu == 0xFFFF).any()):
         return False
