@@ -339,6 +339,18 @@ typedef struct {
 } rr_chase_result_t;
 int rr_chase(const void *region, uint64_t region_bytes, uint32_t line_bytes, uint64_t start, uint64_t stride,
              uint32_t mask, uint64_t hops, void *hip_stream, rr_chase_result_t *out);
+/*
+ * The same walk on a chosen compute unit (dense id `cu`), pinned the way the
+ * paper pins its two-SM runs (Sec. 2.2): many one-wave workgroups are launched,
+ * those that land on another CU leave at once, the first on the target does
+ * the walk.  Same results as rr_chase (the walk does not depend on where it
+ * runs); ns_per_hop is then the latency as that CU -- that XCD's translation
+ * caches -- sees it.  out->kernel_ms_event includes the draining of the idle
+ * workgroups.  RR_EINVAL: cu not below the CU count; RR_EPLACE: no workgroup
+ * landed on the CU in 8 launches.
+ */
+int rr_chase_on_cu(const void *region, uint64_t region_bytes, uint32_t line_bytes, uint64_t start, uint64_t stride,
+                   uint32_t mask, uint64_t hops, uint32_t cu, void *hip_stream, rr_chase_result_t *out);
 
 /*
  * Plain device-to-device copy kernel of exactly known traffic (bytes read =

@@ -77,7 +77,7 @@ class _ReadItem(C.Structure):
     _fields_ = [("region_bytes", C.c_uint64), ("read_seed", C.c_uint64), ("opts", C.POINTER(_Opts))]
 
 
-EXPORTS = ["rr_enumerate_cus", "rr_fill", "rr_rand_read", "rr_rand_read_noalloc", "rr_rand_read_batch", "rr_probe_pair", "rr_probe_cus", "rr_seq_read", "rr_copy", "rr_chase", "rr_rand_update",
+EXPORTS = ["rr_enumerate_cus", "rr_fill", "rr_rand_read", "rr_rand_read_noalloc", "rr_rand_read_batch", "rr_probe_pair", "rr_probe_cus", "rr_seq_read", "rr_copy", "rr_chase", "rr_chase_on_cu", "rr_rand_update",
            "rr_region_granularity", "rr_region_create", "rr_region_destroy",
            "rr_groups_from_heatmap", "rr_zones_from_pair_rates", "rr_detect_zones", "rr_shutdown", "rr_strerror", "rr_last_error", "rr_last_kernel"]
 
@@ -127,6 +127,8 @@ def lib():
         L.rr_rand_update.argtypes = [vp, u64, u32, u32, u64, u32, u64, u32, u64, vp, C.POINTER(_Result)]
         L.rr_chase.restype = C.c_int
         L.rr_chase.argtypes = [vp, u64, u32, u64, u64, u32, u64, vp, C.POINTER(_ChaseResult)]
+        L.rr_chase_on_cu.restype = C.c_int
+        L.rr_chase_on_cu.argtypes = [vp, u64, u32, u64, u64, u32, u64, u32, vp, C.POINTER(_ChaseResult)]
         L.rr_region_granularity.restype = C.c_int
         L.rr_region_granularity.argtypes = [C.POINTER(u64), C.POINTER(u64)]
         L.rr_region_create.restype = C.c_int
@@ -430,11 +432,15 @@ class ChaseResult:
 
 
 def chase(region, line_bytes: int, start: int, stride: int, mask: int, hops: int,
-          region_bytes: Optional[int] = None, stream=None) -> ChaseResult:
-    """Dependent-load walk by one wavefront (latency probe); see rr_chase."""
+          region_bytes: Optional[int] = None, stream=None, cu: Optional[int] = None) -> ChaseResult:
+    """Dependent-load walk by one wavefront (latency probe); see rr_chase.  With cu: on that compute unit
+    (rr_chase_on_cu)."""
     ptr, nbytes = _region(region, region_bytes)
     res = _ChaseResult()
-    _check(lib().rr_chase(ptr, nbytes, line_bytes, start, stride, mask, hops, _stream(stream), C.byref(res)))
+    if cu is None:
+        _check(lib().rr_chase(ptr, nbytes, line_bytes, start, stride, mask, hops, _stream(stream), C.byref(res)))
+    else:
+        _check(lib().rr_chase_on_cu(ptr, nbytes, line_bytes, start, stride, mask, hops, cu, _stream(stream), C.byref(res)))
     return ChaseResult(int(res.final_line), int(res.word_sum), res.kernel_ms_event, res.ns_per_hop)
 
 

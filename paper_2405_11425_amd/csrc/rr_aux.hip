@@ -93,9 +93,11 @@ __global__ void __launch_bounds__(256) seq_read_kernel(const u32x4 *src, u64 n_v
 // (uniform address, broadcast load), lane 0 reports.
 struct ChaseOut {
     u64 final_line, word_sum, ticks;
+    u32 claimed;  // pinned walk: set by the wavefront that does the walk
+    u32 ran_key;  // ... and the key of the compute unit it ran on
 };
-__global__ void __launch_bounds__(64) chase_kernel(const char *region, Reducer red, u32 log2_line, u64 start,
-                                                   u64 stride, u32 mask, u64 hops, ChaseOut *out) {
+__device__ __forceinline__ void walk(const char *region, const Reducer &red, u32 log2_line, u64 start, u64 stride,
+                                     u32 mask, u64 hops, ChaseOut *out) {
     typedef const u32 __attribute__((address_space(1))) *gptr;
     u64 line = start, sum = 0;
     const u64 t0 = clock_ticks();
@@ -111,6 +113,23 @@ __global__ void __launch_bounds__(64) chase_kernel(const char *region, Reducer r
         out->word_sum = sum;
         out->ticks = t1 - t0;
     }
+}
+__global__ void __launch_bounds__(64) chase_kernel(const char *region, Reducer red, u32 log2_line, u64 start,
+                                                   u64 stride, u32 mask, u64 hops, ChaseOut *out) {
+    walk(region, red, log2_line, start, stride, mask, hops, out);
+}
+// The same walk on a chosen compute unit (the pinning of the paper's two-SM probe, Sec. 2.2): many one-wave
+// workgroups are launched, those that land elsewhere leave at once, and of those on the target the first to
+// claim the walk does it.
+__global__ void __launch_bounds__(64) chase_pinned_kernel(const char *region, Reducer red, u32 log2_line, u64 start,
+                                                          u64 stride, u32 mask, u64 hops, ChaseOut *out, u32 target_key) {
+    const u32 key = cu_key();
+    if (key != target_key) return;
+    u32 won = 0;
+    if (threadIdx.x == 0) won = atomicCAS(&out->claimed, 0u, 1u) == 0u ? 1u : 0u;
+    if (!__builtin_amdgcn_readfirstlane(won)) return;
+    if (threadIdx.x == 0) out->ran_key = key;
+    walk(region, red, log2_line, start, stride, mask, hops, out);
 }
 
 // Plain copy, 16 bytes per lane and step, grid-stride: a kernel of exactly known
@@ -194,8 +213,11 @@ extern "C" int rr_seq_read(const void *region, uint64_t region_bytes, void *hip_
     return RR_OK;
 }
 
-extern "C" int rr_chase(const void *region, uint64_t region_bytes, uint32_t line_bytes, uint64_t start,
-                        uint64_t stride, uint32_t mask, uint64_t hops, void *hip_stream, rr_chase_result_t *out) {
+namespace {
+// cu: dense id of the compute unit that is to do the walk, or kAnyCu
+constexpr u32 kAnyCu = 0xFFFFFFFFu;
+int chase_impl(const void *region, uint64_t region_bytes, uint32_t line_bytes, uint64_t start, uint64_t stride,
+               uint32_t mask, uint64_t hops, u32 cu, void *hip_stream, rr_chase_result_t *out) {
     if (!out) return fail(RR_EINVAL, "out is NULL");
     if (!region) return fail(RR_EINVAL, "region is NULL");
     if (line_bytes != 128 && line_bytes != 256 && line_bytes != 512)
@@ -212,24 +234,61 @@ extern "C" int rr_chase(const void *region, uint64_t region_bytes, uint32_t line
     DeviceState *st = nullptr;
     int rc = get_state(stream, &st);
     if (rc != RR_OK) return rc;
-    // the walk's three result words go through the (otherwise idle) key-mark area of the scratch
+    if (cu != kAnyCu && cu >= st->n_cus) return fail(RR_EINVAL, "compute unit id %u is not below %u", cu, st->n_cus);
+    // the walk's result words go through the (otherwise idle) key-mark area of the scratch
     ChaseOut *dev_out = (ChaseOut *)st->scratch->key_seen;
     const u32 log2_line = line_bytes == 128 ? 7 : line_bytes == 256 ? 8 : 9;
-    HIP_TRY(hipEventRecord(st->ev0, stream));
-    hipLaunchKernelGGL(chase_kernel, dim3(1), dim3(64), 0, stream, (const char *)region, make_reducer(n_lines),
-                       log2_line, (u64)start, (u64)(stride % n_lines), mask, (u64)hops, dev_out);
-    HIP_TRY(hipGetLastError());
-    HIP_TRY(hipEventRecord(st->ev1, stream));
     ChaseOut host;
-    HIP_TRY(hipMemcpyAsync(&host, dev_out, sizeof host, hipMemcpyDeviceToHost, stream));
-    HIP_TRY(hipStreamSynchronize(stream));
     float ms = 0.f;
+    if (cu == kAnyCu) {
+        HIP_TRY(hipEventRecord(st->ev0, stream));
+        hipLaunchKernelGGL(chase_kernel, dim3(1), dim3(64), 0, stream, (const char *)region, make_reducer(n_lines),
+                           log2_line, (u64)start, (u64)(stride % n_lines), mask, (u64)hops, dev_out);
+        HIP_TRY(hipGetLastError());
+        HIP_TRY(hipEventRecord(st->ev1, stream));
+        HIP_TRY(hipMemcpyAsync(&host, dev_out, sizeof host, hipMemcpyDeviceToHost, stream));
+        HIP_TRY(hipStreamSynchronize(stream));
+    } else {
+        // 64 one-wave workgroups per wave slot of the device, as the pinned read launches: most leave at once
+        const u32 target_key = key_of(st->cus[cu]);
+        const u32 grid = st->n_cus * 32u * 64u;
+        for (int launch = 0;; ++launch) {
+            rc = launch_reset(*st, 8u, stream);  // clears the key-mark area, the claim flag with it
+            if (rc != RR_OK) return rc;
+            HIP_TRY(hipEventRecord(st->ev0, stream));
+            hipLaunchKernelGGL(chase_pinned_kernel, dim3(grid), dim3(64), 0, stream, (const char *)region,
+                               make_reducer(n_lines), log2_line, (u64)start, (u64)(stride % n_lines), mask, (u64)hops,
+                               dev_out, target_key);
+            HIP_TRY(hipGetLastError());
+            HIP_TRY(hipEventRecord(st->ev1, stream));
+            HIP_TRY(hipMemcpyAsync(&host, dev_out, sizeof host, hipMemcpyDeviceToHost, stream));
+            HIP_TRY(hipStreamSynchronize(stream));
+            if (host.claimed) break;
+            if (launch + 1 >= 8)
+                return fail(RR_EPLACE, "in 8 launches no workgroup landed on compute unit %u", cu);
+        }
+        if (host.ran_key != target_key)
+            return fail(RR_EPLACE, "the walk ran on the compute unit with key %#x, not on %#x", host.ran_key, target_key);
+    }
     HIP_TRY(hipEventElapsedTime(&ms, st->ev0, st->ev1));
     out->final_line = host.final_line;
     out->word_sum = host.word_sum;
     out->kernel_ms_event = ms;
     out->ns_per_hop = (double)host.ticks * 1e6 / (double)st->wall_khz / (double)hops;
     return RR_OK;
+}
+}  // namespace
+
+extern "C" int rr_chase(const void *region, uint64_t region_bytes, uint32_t line_bytes, uint64_t start,
+                        uint64_t stride, uint32_t mask, uint64_t hops, void *hip_stream, rr_chase_result_t *out) {
+    return chase_impl(region, region_bytes, line_bytes, start, stride, mask, hops, kAnyCu, hip_stream, out);
+}
+
+extern "C" int rr_chase_on_cu(const void *region, uint64_t region_bytes, uint32_t line_bytes, uint64_t start,
+                              uint64_t stride, uint32_t mask, uint64_t hops, uint32_t cu, void *hip_stream,
+                              rr_chase_result_t *out) {
+    if (cu >= RR_MAX_CUS) return fail(RR_EINVAL, "compute unit id %u is out of range", cu);
+    return chase_impl(region, region_bytes, line_bytes, start, stride, mask, hops, cu, hip_stream, out);
 }
 
 extern "C" int rr_copy(void *dst, const void *src, uint64_t bytes, void *hip_stream, double *kernel_ms) {

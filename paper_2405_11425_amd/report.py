@@ -111,6 +111,10 @@ def report(rows):
         body = [[f"{r['footprint_mib']:g} MiB", r["ns_per_hop"]] for r in by["latency"]]
         out.append(table(["footprint", "ns per hop"], body))
 
+    for r in by["latency-per-xcd"]:
+        out.append(f"Pinned to one CU of each XCD (CUs {r['cus']}), {r['footprint_mib']:g} MiB: "
+                   + ", ".join(f"{v:.0f}" for v in r["ns_per_hop"]) + f" ns per hop; same walk on every CU: {r['all_cus_agree']}.\n")
+
     if by["pages"]:
         out.append("## Closed walk over N lines, one per stride (ns per hop)\n")
         dists = sorted({r["distance_bytes"] for r in by["pages"]})
@@ -137,6 +141,18 @@ def report(rows):
         out.append(f"Pair probe with blocks of {r['unit_cus']} CUs, every CU on its own window of {r['window_pieces']} pieces: ratios "
                    f"{r['ratio_min']:.3f}-{r['ratio_max']:.3f}, {r['n_groups']} groups of {r['group_sizes_in_cus']} CUs; the groups are the "
                    f"XCDs: {r['groups_are_xcds']}.\n")
+    for r in by["pieces-latency"]:
+        for cu, ns in r["ns_per_hop_by_cu"].items():
+            out.append(f"Dependent-load walk pinned to CU {cu}, footprint = the first w pieces (ns per hop): "
+                       + ", ".join(f"{w}: {v:.0f}" for w, v in zip(r["footprint_pieces"], ns)) + ".\n")
+    for r in by["pieces-flat-curve"]:
+        out.append("### Windows sized by the measured reach, groups as a probe found them (Sec. 2.4)\n")
+        for name, g in r["by_grouping"].items():
+            out.append(f"Grouping `{name}` ({g['groups']} groups): one group alone reads at "
+                       + ", ".join(f"{w}: {v:.0f}" for w, v in zip(g["alone_window_pieces"], g["alone_gbps"]))
+                       + f" GB/s on a window of w pieces -> reach {g['reach_pieces']} pieces.\n")
+            body = [[c["windows"], f"{c['region_mib']:g} MiB", f"{c['gbps_windowed']:.0f}", f"{c['gbps_uniform']:.0f}"] for c in g["curve"]]
+            out.append(table(["windows", "region", "group g on window g mod k", "uniform"], body))
     return "\n".join(out)
 
 

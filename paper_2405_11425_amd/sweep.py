@@ -437,6 +437,24 @@ class Runner:
                                 "ns_per_hop_max": round(max(ns), 1), "final_line": runs[0].final_line,
                                 "word_sum": runs[0].word_sum, **self.meta})
             mib *= 4 if mib < 1024 else 2
+        # the same walk pinned to one compute unit of each XCD: does every XCD see the same latency curve?
+        cus = np.asarray(self.cus)
+        firsts = [int(np.flatnonzero(cus[:, 0] == x)[0]) for x in sorted(set(cus[:, 0].tolist()))]
+        for mib in (1, 64, 4096, 65536, self.max_gib * 1024):
+            if mib > self.max_gib * 1024:
+                continue
+            key = f"latency-per-xcd/{mib}MiB"
+            R = mib * wl.MiB
+            if key not in self.seen:
+                ns, ends = [], []
+                for cu in firsts:
+                    rl.chase(self.region, 128, 0, 0, 0xFFFFFFFF, 2000, region_bytes=R, cu=cu)
+                    runs = [rl.chase(self.region, 128, 7 * i, 0, 0xFFFFFFFF, hops, region_bytes=R, cu=cu) for i in range(3)]
+                    ns.append(round(statistics.median(r.ns_per_hop for r in runs), 1))
+                    ends.append((runs[0].final_line, runs[0].word_sum))
+                self.emit(key, {"experiment": "latency-per-xcd", "footprint_mib": mib, "hops": hops, "cus": firsts,
+                                "ns_per_hop": ns, "final_line": ends[0][0], "word_sum": ends[0][1],
+                                "all_cus_agree": len(set(ends)) == 1, **self.meta})
 
     def pages(self):
         """Nanoseconds per dependent load over a closed cycle of N lines, one line per stride.  The stride is the
@@ -577,6 +595,59 @@ class Runner:
                                 "groups_are_xcds": bool(same_xcd and n_groups == len(per_xcd)),
                                 "group_of_unit": group.tolist(), "xcd_of_unit": xcd_of_unit,
                                 "seconds": round(time.perf_counter() - t0, 1), **meta})
+            # (E) reach by latency: the dependent-load walk pinned to one CU, footprint = the first w pieces
+            key = f"{tag}/latency"
+            if key not in self.seen:
+                widths = [w for w in (4, 8, 16, 24, 32, 40, 48, 64, 96, 128, 256, 1024, 4096, n_pieces) if w <= n_pieces]
+                walkers = sorted({0, per_xcd[-1][0]})
+                table = {}
+                for cu in walkers:
+                    ns = []
+                    for w in widths:
+                        rl.chase(reg, 128, 0, 0, 0xFFFFFFFF, 2000, region_bytes=w * piece, cu=cu)
+                        runs = [rl.chase(reg, 128, 7 * i, 0, 0xFFFFFFFF, 20000, region_bytes=w * piece, cu=cu) for i in range(3)]
+                        ns.append(round(statistics.median(r.ns_per_hop for r in runs), 1))
+                    table[str(cu)] = ns
+                self.emit(key, {"experiment": "pieces-latency", "footprint_pieces": widths, "ns_per_hop_by_cu": table,
+                                "hops": 20000, **meta})
+            # (F) the remedy of Sec. 2.4 with nothing picked by hand: the groups are what a probe found, the window is
+            # what one group was measured to reach, and a region of k windows is read with group g on window g mod k.
+            # Two groupings: the XCDs (what the block probe (D) finds) and the single CUs (what the single-CU probe
+            # finds: no two CUs interfere).  Reach = the window size after which the rate of a group alone takes its
+            # largest relative drop.
+            key = f"{tag}/flat-curve"
+            if key not in self.seen:
+                def reach_of(members, widths):
+                    rates = []
+                    for w in widths:
+                        g, wog = wl.window_map_for_selected_cus(n, members, [0] * len(members))
+                        gbps, _ = rate(w * piece, 64 * len(members), rl.WindowMap(1, g, wog))
+                        rates.append(gbps)
+                    # the reach ends where the rate takes its largest relative drop from one width to the next
+                    drops = [rates[i] / max(rates[i + 1], 1e-9) for i in range(len(rates) - 1)]
+                    return widths[int(np.argmax(drops))], rates
+                widths = [w for w in (4, 8, 16, 24, 32, 48, 64, 96, 128, 192, 256, 512, 1024) if w <= n_pieces]
+                rows = {}
+                for name, groups in (("xcd", [list(x) for x in per_xcd]), ("cu", [[c] for c in range(n)])):
+                    reach, rates = reach_of(groups[0], widths)
+                    group_of_cu = np.zeros(n, np.uint16)
+                    for gi, members in enumerate(groups):
+                        group_of_cu[members] = gi
+                    G = len(groups)
+                    curve = []
+                    k = 1
+                    while k <= G and k * reach <= n_pieces:
+                        wog = np.arange(G, dtype=np.uint16) % k
+                        size = k * reach * piece
+                        waves = (W + G - 1) // G * G
+                        windowed, _ = rate(size, waves, rl.WindowMap(k, group_of_cu, wog))
+                        uniform, _ = rate(size, W)
+                        curve.append({"windows": k, "region_mib": size / wl.MiB, "gbps_windowed": windowed,
+                                      "gbps_uniform": uniform})
+                        k *= 2
+                    rows[name] = {"groups": G, "reach_pieces": reach, "alone_window_pieces": widths,
+                                  "alone_gbps": rates, "curve": curve}
+                self.emit(key, {"experiment": "pieces-flat-curve", "by_grouping": rows, **meta})
         finally:
             reg.destroy()
 

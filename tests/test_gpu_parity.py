@@ -137,6 +137,23 @@ def test_chase_matches_oracle(region, R, B, start, stride, mask, hops):
     assert got.ns_per_hop > 0
 
 
+def test_chase_on_a_chosen_cu(region, cu_table):
+    """The walk pinned to a compute unit (Sec. 2.2's pinning applied to the latency probe): same result as the
+    oracle's walk whatever the CU, and it ran where it was told to (the library checks the CU's key and would
+    report RR_EPLACE); one CU of every XCD, the first and the last CU."""
+    n = len(cu_table)
+    one_per_xcd = [int(np.flatnonzero(cu_table[:, 0] == x)[0]) for x in sorted(set(cu_table[:, 0].tolist()))]
+    R, hops = 1 << 30, 3000
+    want = orc.chase(R, 128, wl.FILL_SEED, 5, 0, 0xFFFFFFFF, hops)
+    for cu in sorted(set(one_per_xcd + [0, n - 1])):
+        got = rl.chase(region, 128, 5, 0, 0xFFFFFFFF, hops, region_bytes=R, cu=cu)
+        assert (got.final_line, got.word_sum) == want, cu
+        assert 50 < got.ns_per_hop < 5000
+    with pytest.raises(rl.RandlineError) as e:
+        rl.chase(region, 128, 5, 0, 0xFFFFFFFF, hops, region_bytes=R, cu=n)
+    assert e.value.code == rl.RR_EINVAL
+
+
 def test_chase_full_region(region):
     R = region.numel()
     got = rl.chase(region, 128, 0, 0, 0xFFFFFFFF, 20000)

@@ -248,6 +248,11 @@ def test_chase_validation():
         with pytest.raises(rl.RandlineError) as e:
             rl.chase(*args)
         assert e.value.code == rl.RR_EINVAL and needle in str(e.value)
+    for args, kw, needle in (((FAKE, 128, 0, 0, 0, 1), {"cu": 1024}, "out of range"), ((FAKE, 128, 0, 0, 0, 0), {"cu": 3}, "hops"),
+                             (((0, 4096), 128, 0, 0, 0, 1), {"cu": 0}, "NULL")):
+        with pytest.raises(rl.RandlineError) as e:                      # the pinned walk checks the same, and its CU
+            rl.chase(*args, **kw)
+        assert e.value.code == rl.RR_EINVAL and needle in str(e.value)
 
 
 def test_verify_sweep_tool(tmp_path, worked):
@@ -303,11 +308,16 @@ def test_report_renders_every_kind_of_row():
          "cus_per_xcd_all_xcds": [4], "gbps_per_cu_all_xcds": [49.0]},
         {"experiment": "pieces-probe", "unit_cus": 4, "window_pieces": 48, "ratio_min": 0.18, "ratio_max": 1.01, "n_groups": 8,
          "group_sizes_in_cus": [32], "groups_are_xcds": True},
+        {"experiment": "latency-per-xcd", "footprint_mib": 64, "cus": [0, 32], "ns_per_hop": [401.0, 405.0], "all_cus_agree": True},
+        {"experiment": "pieces-latency", "footprint_pieces": [16, 64], "ns_per_hop_by_cu": {"0": [410.0, 733.0]}},
+        {"experiment": "pieces-flat-curve", "by_grouping": {"cu": {"groups": 256, "reach_pieces": 24, "alone_window_pieces": [16, 32],
+         "alone_gbps": [52.0, 17.0], "curve": [{"windows": 2, "region_mib": 6.0, "gbps_windowed": 6100.0, "gbps_uniform": 900.0}]}}},
     ]
     text = report.report(rows)
     for needle in ("Throughput vs region size", "| 256 GiB |  | 6700 (83.8 %) | 6400 (80.0 %) |", "64 x 4 B = 256 B", "xcd | 8",
                    "sequential read", "write | 16 GiB", "2 zones", "32 groups of [8] CUs", "1190-1200 GB/s", "| 1 MiB | 155.0 |",
-                   "| 33 | 200.0 |", "| 512 MiB | 4096 | 280 |", "96: 10", "6: 11.0", "the groups are the XCDs: True"):
+                   "| 33 | 200.0 |", "| 512 MiB | 4096 | 280 |", "96: 10", "6: 11.0", "the groups are the XCDs: True",
+                   "401, 405 ns per hop", "64: 733", "reach 24 pieces", "| 2 | 6 MiB | 6100 | 900 |"):
         assert needle in text, needle
     assert "Line width" not in report.report(rows[:1])
 

@@ -50,6 +50,11 @@ def expected(row, threads):
     if e == "latency":
         R = row["footprint_mib"] * MiB
         return (row["final_line"], row["word_sum"]), orc.chase(R, 128, FILL_SEED, 0, 0, 0xFFFFFFFF, row["hops"])
+    if e == "latency-per-xcd":
+        R = row["footprint_mib"] * MiB
+        if not row["all_cus_agree"]:
+            return "walks differ", "one walk"
+        return (row["final_line"], row["word_sum"]), orc.chase(R, 128, FILL_SEED, 0, 0, 0xFFFFFFFF, row["hops"])
     if e == "updates":
         if "value_seed" not in row:
             return "row does not give the value seed"
