@@ -122,8 +122,9 @@ typedef struct {
     uint32_t block_threads;  /* 64, 128 or 256 (default 256)                                      */
     uint32_t grid_blocks;    /* ticket mode: workgroups per launch (default: eight wavefronts per
                                 CU, zone-phased reads the resident capacity; pinned runs: 64 x the
-                                wave slots).  Stream mode: the same (default: two workgroups per
-                                CU).  Flat mode ignores it.                                       */
+                                wave slots).  Stream mode: the same (default: as many per CU as
+                                keep 32 KB of lines in flight: two for 128-byte lines, one for
+                                512-byte lines).  Flat mode ignores it.                           */
     uint32_t unroll;         /* loads kept in flight per wave: 2, 4, 8 or 16 (default by line width) */
     uint32_t mode;           /* RR_MODE_*                                                          */
     uint32_t bcast;          /* RR_BCAST_*                                                         */

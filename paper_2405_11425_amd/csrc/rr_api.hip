@@ -37,8 +37,7 @@ const Family *find_family(u32 lanes, u32 wdw) {
 }
 
 constexpr u32 kTicketWavesPerCu = 8;   // default grid of the plain ticketed kernel, in wavefronts per compute unit
-constexpr u32 kZoneStreamBlocksPerCu = 2;
-constexpr u32 kStreamBlocksPerCu = 2;  // default grid of the stream kernel: workgroups (of four wavefronts) per compute unit
+constexpr u32 kStreamBytesPerCu = 32768;  // default grid of the stream kernels: workgroups per compute unit so that this much is in flight
 
 // Name of the kernel the calling thread's last read call launched (rr_last_kernel).
 thread_local char g_last_kernel[96] = "";
@@ -327,7 +326,14 @@ int make_launch(const Plan &pl, DeviceState &st, const void *region, uint32_t it
     u64 grid;
     if (pl.mode == RR_MODE_STREAM) {
         // a few wavefronts per SIMD that never stop keep the memory system as busy as a full house (measured)
-        grid = pl.grid_blocks ? pl.grid_blocks : (u64)(pl.n_zones ? kZoneStreamBlocksPerCu : kStreamBlocksPerCu) * n_cus;
+        // What counts is the data in flight: 32 KB per compute unit -- for 128-byte lines two workgroups of four
+        // waves with 16 loads of two lines each -- is enough to keep the memory busy, and zone by zone more than that
+        // only blurs the zones (256- and 512-byte lines over 256 GiB: 6.86 TB/s with one workgroup per CU, 6.72 with
+        // two, 6.5-6.6 with four).
+        const u32 ring = pl.n_zones ? (pl.wdw == 4 ? 8u : 16u) : pl.unroll;
+        const u32 bytes_per_block = 4u * ring * lpw * (pl.lanes * pl.wdw * 4u);
+        const u32 blocks_per_cu = std::max(1u, kStreamBytesPerCu / bytes_per_block);
+        grid = pl.grid_blocks ? pl.grid_blocks : (u64)blocks_per_cu * n_cus;
     } else if (p.ticket_mode) {
         // As many workgroups as are resident at once: work-stealing finishes the job whatever the placement, and
         // every workgroup beyond that only starts when the work is done, scans all shares and leaves -- which

@@ -46,6 +46,7 @@ def report(rows):
         out.append("## Throughput vs region size (uniform random 128-byte lines)\n")
         sizes = sorted({r["region_gib"] for r in by["region"]})
         cols = [("uniform", None, "plain order"), ("uniform, zone by zone", None, "zone by zone"),
+                ("uniform, every wave slot occupied", None, "plain, one wavefront per pair of logical waves"),
                 ("uniform", "16x", "plain, 16x longer launches"), ("uniform, zone by zone", "16x", "zone by zone, 16x longer")]
         cell = {(r["scheme"], r.get("launch_size"), r["region_gib"]): r["gbps"] for r in by["region"]}
         body = []

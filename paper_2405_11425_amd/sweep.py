@@ -142,7 +142,7 @@ class Runner:
         return len(ids), [ids[z] for z in zm]
 
     def region_sweep(self):
-        wl = self.wl
+        wl, rl = self.wl, self.rl
         configs = wl.region_sweep(self.max_gib * wl.GiB, len(self.cus))
         for cfg in configs:
             key = f"region/{cfg.name}/{json.dumps(self.launch, sort_keys=True)}"
@@ -158,6 +158,12 @@ class Runner:
             if n_zones >= 2:
                 self.emit(key, {"experiment": "region", "scheme": "uniform, zone by zone", "zones": n_zones,
                                 "zone_of_window": zm, **self.timed_read(cfg, zone_of_window=zm), **self.meta})
+        # the same reads as one wavefront per pair of logical waves, every wave slot of the device occupied
+        for cfg in configs:
+            key = f"region-flat/{cfg.name}"
+            if key not in self.seen:
+                self.emit(key, {"experiment": "region", "scheme": "uniform, every wave slot occupied",
+                                **self.timed_read(cfg, mode=rl.MODE_FLAT), **self.meta})
         # and with 16 times as many logical waves per launch (2^30 reads): start, end and zone changes of a launch
         # then weigh 16 times less
         for cfg in configs:

@@ -314,7 +314,7 @@ def test_report_renders_every_kind_of_row():
          "alone_gbps": [52.0, 17.0], "curve": [{"windows": 2, "region_mib": 6.0, "gbps_windowed": 6100.0, "gbps_uniform": 900.0}]}}},
     ]
     text = report.report(rows)
-    for needle in ("Throughput vs region size", "| 256 GiB |  | 6700 (83.8 %) | 6400 (80.0 %) |", "64 x 4 B = 256 B", "xcd | 8",
+    for needle in ("Throughput vs region size", "| 256 GiB |  | 6700 (83.8 %) |  | 6400 (80.0 %) |", "64 x 4 B = 256 B", "xcd | 8",
                    "sequential read", "write | 16 GiB", "2 zones", "32 groups of [8] CUs", "1190-1200 GB/s", "| 1 MiB | 155.0 |",
                    "| 33 | 200.0 |", "| 512 MiB | 4096 | 280 |", "96: 10", "6: 11.0", "the groups are the XCDs: True",
                    "401, 405 ns per hop", "64: 733", "reach 24 pieces", "| 2 | 6 MiB | 6100 | 900 |"):
