@@ -192,6 +192,41 @@ def test_detected_zone_map_drives_the_phased_read(region):
     assert plain.checksum == phased.checksum == orc.checksum(R, 128, W, I, wl.FILL_SEED, 21, n_threads=ORACLE_THREADS)
 
 
+def test_measured_pair_rates_give_the_same_zones_through_library_and_oracle(region):
+    """Pair rates of eight 32 GiB windows, measured here the way rr_detect_zones measures them (even CUs on one window,
+    odd CUs on the other, the fastest of three launches; of six when taken again), recorded, and fed to the library's
+    rule and to the oracle's: same zones, same cut, same questions.  And rr_detect_zones itself finds the same
+    partition of the same windows."""
+    from oracle.zones import zones_from_pair_rates as oracle_zones
+    need(region, 256)
+    n, R, iters = 8, 256 * GiB, 2048
+    n_cus = len(rl.enumerate_cus())
+    W = n_cus * 64
+    parity = (np.arange(n_cus) % 2).astype(np.uint16)
+
+    def measure(a, b, launches):
+        wm = rl.WindowMap(n, parity, np.array([a, b], np.uint16))
+        ms = [rl.rand_read(region, 128, W * iters, iters, 100 + i, wm, region_bytes=R, unroll=16).kernel_ms_event
+              for i in range(launches)]
+        return W * iters * 128 / min(ms) / 1e6
+    for i in range(24):
+        measure(0, 0, 1)                                   # the process' first launches can run slow
+    table = {(a, b): (measure(a, b, 3), measure(a, b, 6)) for a in range(n) for b in range(a, n)}
+
+    def rate(a, b, again=False):
+        return table[(min(a, b), max(a, b))][1 if again else 0]
+    d_lib, d_orc = {}, {}
+    got = rl.zones_from_pair_rates(rate, n, details=d_lib)
+    want = oracle_zones(rate, n, details=d_orc)
+    print(f"\n[measured zones] {got}  same {d_lib['same']:.0f} cut {d_lib['cut']:.0f} GB/s, row {[round(x) for x in d_lib['row']]}",
+          flush=True)
+    assert got == want
+    for key in ("same", "cut", "band", "n_zones", "pair_rates", "merge_rates", "gave_up", "row", "zones_before_merging"):
+        assert d_lib[key] == d_orc[key], key
+    assert 2 <= d_lib["n_zones"] <= 4                      # a 256 GiB allocation spans the card's three zones
+    assert rl.detect_zones(region, n, region_bytes=R) == got
+
+
 def test_calls_on_a_side_stream():
     """Every entry point works on the stream it is given (explicitly, or torch's current one) and is ordered
     after what that stream already holds."""
