@@ -75,6 +75,21 @@ def test_anchor_is_the_largest_before_or_after_the_row():
     assert d["same"] == 100.0
 
 
+def test_anchor_is_the_largest_of_all_eight_measurements():
+    """The four anchor windows read 98, 100, 99, 98 before the row and 97 each after it: same = 100, the largest of the
+    eight (not the largest of the later round alone, not the smallest of the earlier one).  With cross-zone rates of 95
+    the cut is (100 + 95) / 2 = 97.5."""
+    calls = {"n": 0}
+    def rate(a, b, again=False):
+        if a == b:
+            calls["n"] += 1
+            return [98.0, 100.0, 99.0, 98.0][calls["n"] - 1] if calls["n"] <= 4 else 97.0
+        return {(0, 1): 100.0, (0, 2): 95.0, (0, 3): 95.0, (2, 3): 100.0}[(min(a, b), max(a, b))]
+    d = {}
+    assert zones_from_pair_rates(rate, 4, 0.02, details=d) == [0, 0, 1, 1]
+    assert d["same"] == 100.0 and d["cut"] == 97.5
+
+
 def test_rate_close_to_the_cut_is_taken_again_and_the_larger_counts():
     t = {(p, p): 100.0 for p in range(4)}
     t.update({(0, 1): (97.3, 99.8), (0, 2): 95.0, (0, 3): 95.2, (2, 3): (97.8, 94.0)})
