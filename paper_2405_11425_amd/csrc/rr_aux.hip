@@ -155,7 +155,7 @@ extern "C" int rr_fill(void *region, uint64_t region_bytes, uint64_t fill_seed, 
     HIP_TRY(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
     const u64 n_pairs = region_bytes / 16;
     u64 blocks = (n_pairs + 255) / 256;
-    const u64 cap = (u64)n_cu * 16;  // grid-stride beyond this
+    const u64 cap = (u64)n_cu * 32;  // grid-stride beyond this; stores want many waves (256 GiB: 7.1 TB/s, with 8 per CU 6.8)
     if (blocks > cap) blocks = cap;
     hipLaunchKernelGGL(fill_kernel, dim3((u32)blocks), dim3(256), 0, stream, (u64x2 *)region, n_pairs,
                        (u64)fill_seed);
@@ -182,12 +182,14 @@ extern "C" int rr_seq_read(const void *region, uint64_t region_bytes, void *hip_
     if (rc != RR_OK) return rc;
     const u64 n_vec = region_bytes / 16;
     u64 blocks = (n_vec + 255) / 256;
-    const u64 cap = 16ull * st->n_cus;  // two rounds of resident workgroups; each wave loops over its chunks
+    // One workgroup per compute unit, each wave looping over its chunks with 8 KiB in flight: 32 KB per CU, as for
+    // the random reads, is what reads fastest (64 GiB: 7.26 TB/s; with 4 workgroups per CU 7.03, with 16 7.05).
+    const u64 cap = st->n_cus;
     if (blocks > cap) blocks = cap;
     // Regions that may span several memory zones (more than 96 GiB) are swept front to back in blocks of 2 MiB
-    // from one counter: 6.82 / 6.91 / 6.89 TB/s over 128 / 192 / 256 GiB against 6.77 / 6.75 / 6.48 with the static
-    // assignment, which in turn is better inside one zone (7.0 against 6.7 TB/s at 64 GiB: no claims, no imbalance
-    // from the coarse blocks).
+    // from one counter, so that the device reads one zone after the other: 7.19 / 7.16 TB/s over 128 / 256 GiB.  Inside
+    // one zone the static assignment is used (7.40 / 7.37 TB/s at 16 / 64 GiB: no claims, no imbalance from the
+    // coarse blocks).
     const u32 block_chunks = region_bytes > (96ull << 30) ? 256u : 0u;
     rc = begin_cells(*st, stream);
     if (rc != RR_OK) return rc;
@@ -308,7 +310,7 @@ extern "C" int rr_copy(void *dst, const void *src, uint64_t bytes, void *hip_str
     if (rc != RR_OK) return rc;
     const u64 n_vec = bytes / 16;
     u64 blocks = (n_vec + 255) / 256;
-    const u64 cap = (u64)st->n_cus * 8;
+    const u64 cap = (u64)st->n_cus * 3;  // measured best (2-4 per CU within 5 %; 8 and more 10-15 % slower)
     if (blocks > cap) blocks = cap;
     HIP_TRY(hipEventRecord(st->ev0, stream));
     hipLaunchKernelGGL(copy_kernel, dim3((u32)blocks), dim3(256), 0, stream, (u32x4 *)dst, (const u32x4 *)src, n_vec);
