@@ -555,6 +555,40 @@ def test_zone_stream_geometry_does_not_change_checksum(region, B, lanes):
         rl.rand_read(region, B, W * 100, 100, 5, lanes_per_line=lanes, region_bytes=R, zone_bytes=1 << 24, mode=rl.MODE_STREAM)
 
 
+def test_stream_kernels_on_seeded_random_shapes(region):
+    """Sixty seeded random launches of the two stream kernels -- line shape, region size (powers of two and not),
+    logical waves, iterations, chunk, grid, first wave, and for the zoned ones a random assignment of 2-64 windows to
+    1-16 zones -- each against the oracle."""
+    rng = np.random.default_rng(20240511)
+    for case in range(60):
+        B, lanes = wl.LINE_SHAPES[int(rng.integers(len(wl.LINE_SHAPES)))]
+        lpw = 64 // lanes
+        W = lpw * int(rng.integers(1, 120))
+        zoned = case % 2 == 1
+        unit = 64 if zoned else 16
+        I = unit * int(rng.integers(1, 12))
+        chunks = [c for c in range(unit, I + 1, unit) if I % c == 0 and c % 64 == 0]      # chunk_iters must be a multiple of 64
+        chunk = int(rng.choice(chunks)) if chunks and rng.integers(2) else 0
+        grid = int(rng.choice([0, 1, 2, 5, 64, 511, 513, 2000]))
+        first = lpw * int(rng.integers(0, 50))
+        kw = {}
+        if zoned:
+            n_win = int(rng.choice([2, 3, 4, 6, 8, 16, 32, 64]))
+            win_lines = 1 << int(rng.integers(6, 14))
+            R = n_win * win_lines * B
+            n_zones = int(rng.integers(1, min(16, n_win) + 1))
+            zmap = rng.integers(0, n_zones, n_win).tolist()
+            zmap[:n_zones] = list(range(n_zones))                 # every zone id up to the largest is used
+            kw = dict(zone_of_window=zmap)
+        else:
+            R = B * int(rng.integers(1, 1 << 16)) if rng.integers(2) else B << int(rng.integers(0, 18))
+        seed = int(rng.integers(1, 1 << 40))
+        got = rl.rand_read(region, B, W * I, I, seed, lanes_per_line=lanes, region_bytes=R, mode=rl.MODE_STREAM,
+                           chunk_iters=chunk, grid_blocks=grid, first_wave=first, **kw)
+        want = oracle(R, B, W, I, read_seed=seed, first_wave=first)
+        assert got.checksum == want, (case, B, lanes, R, W, I, chunk, grid, first, kw)
+
+
 def test_zone_map_with_scattered_zones(region):
     """Zones given window by window, not contiguous (the way physical zones show up in an allocation)."""
     R, W, I = 1 << 30, 200, 777
