@@ -459,6 +459,26 @@ def test_stream_geometry_does_not_change_checksum(region, B, lanes):
             rl.rand_read(region, B, W * I, I, 5, lanes_per_line=lanes, region_bytes=R, mode=rl.MODE_STREAM, **kw)
 
 
+def test_last_kernel_names_what_was_launched(region):
+    """rr_last_kernel: the name a kernel trace shows for the kernel the last read call chose."""
+    R, W, I = 1 << 26, 64, 256
+    kw = dict(region_bytes=R)
+    rl.rand_read(region, 128, W * I, I, 7, **kw)
+    assert rl.last_kernel() == "rand_read_stream_kernel<32, 1, 16, 1>"
+    rl.rand_read(region, 128, W * I, I, 7, mode=rl.MODE_FLAT, nontemporal=rl.NT_OFF, **kw)
+    assert rl.last_kernel() == "rand_read_flat_kernel<32, 1, 16, 2, 0>"
+    rl.rand_read(region, 512, W * I, I, 7, mode=rl.MODE_TICKET, unroll=4, bcast=rl.BCAST_LDS, **kw)
+    assert rl.last_kernel() == "rand_read_kernel<32, 4, 4, 1, 1>"
+    rl.rand_read(region, 256, W * I, I, 7, lanes_per_line=64, zone_bytes=1 << 24, **kw)
+    assert rl.last_kernel() == "rand_read_zone_stream_kernel<64, 1, 16, 1>"
+    rl.rand_read(region, 512, W * I, I, 7, zone_bytes=1 << 24, **kw)
+    assert rl.last_kernel() == "rand_read_zone_stream_kernel<32, 4, 8, 1>"
+    rl.rand_read(region, 128, W * I, I, 7, zone_bytes=1 << 24, mode=rl.MODE_TICKET, **kw)
+    assert rl.last_kernel() == "rand_read_phased_kernel<32, 1, 32, 1>"
+    rl.probe_pair(region, 0, 1, W * I, I, 7, **kw)
+    assert rl.last_kernel() == "rand_read_kernel<32, 1, 16, 2, 1>"
+
+
 def test_additivity_over_wave_ranges(region):
     R, B, I = 1 << 26, 128, 64
     whole = rl.rand_read(region, B, 1000 * I, I, 9, region_bytes=R).checksum
