@@ -208,7 +208,9 @@ def main():
                       "gbps_min": round(cfg.bytes_read / max(ms) / 1e6, 1),
                       "gbps_max": round(cfg.bytes_read / min(ms) / 1e6, 1),
                       "pct_of_hbm_peak": round(cfg.bytes_read / med / 1e6 / HBM_PEAK_GBPS * 100, 1),
-                      "kernel_ms": round(med, 4), "kernel_ms_in_kernel_clock": round(statistics.median(ms_dev), 4)})
+                      "kernel_ms": round(med, 4), "kernel_ms_in_kernel_clock": round(statistics.median(ms_dev), 4),
+                      "n_reads": cfg.n_reads, "line_bytes": cfg.line_bytes, "lanes_per_line": cfg.lanes_per_line,
+                      "checksum_first_step": f"{records[cfg.name][0].checksum:#018x}"})
     bytes_per_launch = configs[0].bytes_read
     per_kernel = []
     for cls, g in groups.items():
@@ -279,12 +281,14 @@ def main():
         cores = len(os.sched_getaffinity(0))
         picks = list(configs)
         t_all, reads_all, used, match = 0.0, 0, 0, True
+        oracle_first = {}
         for cfg in picks:
             t0 = time.perf_counter()
             c_all, used = orc.checksum_ex(cfg.region_bytes, cfg.line_bytes, cfg.logical_waves, cfg.iters_per_wave,
                                           cfg.fill_seed, wl.READ_SEED, n_threads=cores)
             t_all += time.perf_counter() - t0
             reads_all += cfg.n_reads
+            oracle_first[cfg.name] = c_all
             match = match and c_all == records[cfg.name][0].checksum
         # the last timed step too (not timed: the rate above is from the first pass only)
         last_seed = wl.READ_SEED + args.steps - 1
@@ -304,6 +308,8 @@ def main():
         orc.checksum_materialised(host, cfg.line_bytes, mat_waves, 1024, wl.READ_SEED, n_threads=cores)
         t_mat = time.perf_counter() - t0
         del host
+        for c, cfg in zip(curve, configs):
+            c["oracle_checksum_first_step"] = f"{oracle_first[cfg.name]:#018x}"
         out["cpu_baseline"] = {
             "value": round(reads_all * cfg.line_bytes / t_all / 1e9, 3), "unit": "GB/s", "cores": used,
             "kind": "oracle",
