@@ -149,9 +149,9 @@ def report(rows):
     for r in by["pieces-flat-curve"]:
         out.append("### Windows sized by the measured reach, groups as a probe found them (Sec. 2.4)\n")
         for name, g in r["by_grouping"].items():
-            out.append(f"Grouping `{name}` ({g['groups']} groups): one group alone reads at "
-                       + ", ".join(f"{w}: {v:.0f}" for w, v in zip(g["alone_window_pieces"], g["alone_gbps"]))
-                       + f" GB/s on a window of w pieces -> reach {g['reach_pieces']} pieces.\n")
+            out.append(f"Grouping `{name}` ({g['groups']} groups): with every group on a window of w pieces of its own the device reads at "
+                       + ", ".join(f"{w}: {v:.0f}" for w, v in zip(g["own_window_pieces"], g["own_window_gbps"]))
+                       + f" GB/s -> reach {g['reach_pieces']} pieces.\n")
             body = [[c["windows"], f"{c['region_mib']:g} MiB", f"{c['gbps_windowed']:.0f}", f"{c['gbps_uniform']:.0f}"] for c in g["curve"]]
             out.append(table(["windows", "region", "group g on window g mod k", "uniform"], body))
     return "\n".join(out)

@@ -310,8 +310,8 @@ def test_report_renders_every_kind_of_row():
          "group_sizes_in_cus": [32], "groups_are_xcds": True},
         {"experiment": "latency-per-xcd", "footprint_mib": 64, "cus": [0, 32], "ns_per_hop": [401.0, 405.0], "all_cus_agree": True},
         {"experiment": "pieces-latency", "footprint_pieces": [16, 64], "ns_per_hop_by_cu": {"0": [410.0, 733.0]}},
-        {"experiment": "pieces-flat-curve", "by_grouping": {"cu": {"groups": 256, "reach_pieces": 24, "alone_window_pieces": [16, 32],
-         "alone_gbps": [52.0, 17.0], "curve": [{"windows": 2, "region_mib": 6.0, "gbps_windowed": 6100.0, "gbps_uniform": 900.0}]}}},
+        {"experiment": "pieces-flat-curve", "by_grouping": {"cu": {"groups": 256, "reach_pieces": 24, "own_window_pieces": [16, 32],
+         "own_window_gbps": [6900.0, 2800.0], "curve": [{"windows": 2, "region_mib": 6.0, "gbps_windowed": 6100.0, "gbps_uniform": 900.0}]}}},
     ]
     text = report.report(rows)
     for needle in ("Throughput vs region size", "| 256 GiB |  | 6700 (83.8 %) |  | 6400 (80.0 %) |", "64 x 4 B = 256 B", "xcd | 8",
