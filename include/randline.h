@@ -125,7 +125,8 @@ typedef struct {
                                 wave slots).  Stream mode: the same (default: as many per CU as
                                 keep 32 KB of lines in flight: two for 128-byte lines, one for
                                 512-byte lines).  Flat mode ignores it.                           */
-    uint32_t unroll;         /* loads kept in flight per wave: 2, 4, 8 or 16 (default by line width) */
+    uint32_t unroll;         /* loads kept in flight per wave: 2, 4, 8 or 16 (default by line width;
+                                the stream kernel is built for 8 and 16)                          */
     uint32_t mode;           /* RR_MODE_*                                                          */
     uint32_t bcast;          /* RR_BCAST_*                                                         */
     uint32_t nontemporal;    /* RR_NT_*                                                            */
@@ -143,20 +144,22 @@ typedef struct {
                                 Not with a window map.  Default mode: stream, else ticketed.       */
     const uint8_t *zone_of_window; /* host [n_zone_windows] or NULL: instead of zone_bytes, a zone id (< 16) for   */
     uint32_t n_zone_windows;       /* each of n_zone_windows (<= 64) equal windows of the region, each a power of
-                                      two lines long -- for zones that are not contiguous (the "zones" experiment
-                                      of the sweep driver produces such a map)                               */
+                                      two lines long -- for zones that are not contiguous (rr_detect_zones
+                                      produces such a map)                                                   */
     uint32_t reserved2;            /* must be 0                                                              */
     uint64_t *phase_ticks;   /* DEVICE [hardware waves x zones] or NULL (flat zone-phased reads only): the
                                 constant-rate clock (100 MHz) at which each wave finished each zone,
                                 for checking how well the phases line up                           */
-    uint16_t *placement_out; /* host [W] or NULL: dense CU id that executed each logical wave      */
+    uint16_t *placement_out; /* host [W] or NULL: dense CU id that executed each logical wave (flat and
+                                ticketed kernels; with it AUTO does not choose the stream kernel,
+                                whose waves share the iterations of a logical wave among them)     */
     uint32_t *cu_waves_out;  /* host [n_cus] or NULL: working hardware waves counted per CU        */
 } rr_launch_opts_t;
 
 /*
  * Zone-phased reads.  On the MI355X the random-read rate depends on how many
- * 96 GiB thirds of the HBM are being read at the same time by anyone (measure
- * it with the "zones" experiment of the sweep driver); restricting each compute
+ * 96 GiB thirds of the HBM are being read at the same time by anyone (find
+ * them with rr_detect_zones); restricting each compute
  * group to a window (paper Sec. 2.4) does not change that, but letting all
  * waves work on the same zone at the same time does.  With zone_bytes or
  * zone_of_window set, the work is cut into items (zone, pair of logical waves, chunk of iterations); an
