@@ -1,9 +1,12 @@
-// Zone-phased variant of the random line read.
+// Zone-phased variants of the random line read: rand_read_phased_kernel (items
+// binned into LDS lists, handed out by tickets or walked through flat) and, at
+// the end of this file, rand_read_zone_stream_kernel (the default: the stream
+// kernel's way of working with a filter in front of the loads).
 //
 // On the MI355X the read rate drops when lines from different 96 GiB thirds of
 // the memory are in flight at the same time, whoever issues them; a window per
 // compute group (the paper's remedy, Sec. 2.4) does not help, a window per
-// *phase* does.  This kernel reads exactly the lines of rand_read_kernel (same
+// *phase* does.  These kernels read exactly the lines of rand_read_kernel (same
 // draws, same checksum) in a different order: the region is cut into at most
 // 64 windows of a power-of-two number of lines, every window belongs to one
 // zone (the zones need not be contiguous: how the physical zones appear in an

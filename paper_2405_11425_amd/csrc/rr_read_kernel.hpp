@@ -14,6 +14,12 @@
 // broadcast or v_readlane) and every lane loads its WDW dwords of that line.
 // U loads stay in flight per wave: a ring of U result registers is consumed one
 // slot at a time, each slot refilled by the next load, across batch boundaries.
+//
+// Three kernels share this: rand_read_stream_kernel (the default without a
+// window map: few waves, tickets from LDS, the ring never drained),
+// rand_read_flat_kernel (one wave per pair of logical waves) and
+// rand_read_kernel (tickets from per-CU counters: window maps, pinned runs,
+// placement log).
 #pragma once
 #include <utility>
 #include "rr_common.hpp"
