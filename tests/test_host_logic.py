@@ -63,6 +63,14 @@ def test_header_is_plain_c(tmp_path):
     assert got == want
 
 
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU; asked for more it says so and exits before touching a device."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=60)
+    assert r.returncode == 2 and "single-GPU" in r.stderr and r.stdout == ""
+
+
 def test_strerror_and_codes():
     L = rl.lib()
     assert L.rr_strerror(0) == b"success"
