@@ -146,7 +146,11 @@ typedef struct {
     uint32_t n_zone_windows;       /* each of n_zone_windows (<= 64) equal windows of the region, each a power of
                                       two lines long -- for zones that are not contiguous (rr_detect_zones
                                       produces such a map)                                                   */
-    uint32_t reserved2;            /* must be 0                                                              */
+    uint32_t zone_descending;      /* 0: zones are read in ascending id order; 1: from the highest id down.
+                                      A caller that repeats a zone-phased read over a region larger than the
+                                      translation reach alternates the two, so that every launch starts in
+                                      the zone the one before ended in and finds its translations still
+                                      cached; other values are rejected                                      */
     uint64_t *phase_ticks;   /* DEVICE [hardware waves x zones] or NULL (flat zone-phased reads only): the
                                 constant-rate clock (100 MHz) at which each wave finished each zone,
                                 for checking how well the phases line up                           */

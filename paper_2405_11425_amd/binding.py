@@ -52,7 +52,7 @@ class _Opts(C.Structure):
                 ("mode", C.c_uint32), ("bcast", C.c_uint32), ("nontemporal", C.c_uint32),
                 ("chunk_iters", C.c_uint32), ("reserved", C.c_uint32), ("first_wave", C.c_uint64),
                 ("zone_bytes", C.c_uint64), ("zone_of_window", C.POINTER(C.c_uint8)), ("n_zone_windows", C.c_uint32),
-                ("reserved2", C.c_uint32), ("phase_ticks", C.c_void_p), ("placement_out", C.POINTER(C.c_uint16)),
+                ("zone_descending", C.c_uint32), ("phase_ticks", C.c_void_p), ("placement_out", C.POINTER(C.c_uint16)),
                 ("cu_waves_out", C.POINTER(C.c_uint32))]
 
 
@@ -223,7 +223,7 @@ class ReadResult:
 
 def _opts(W: int, n_cus_hint: int, block_threads=0, grid_blocks=0, unroll=0, mode=0, bcast=0,
           nontemporal=0, chunk_iters=0, first_wave=0, zone_bytes=0, zone_of_window=None, phase_ticks=None,
-          want_placement=False, want_cu_waves=False):
+          zone_descending=False, want_placement=False, want_cu_waves=False):
     ticks_ptr = None
     if phase_ticks is not None:   # a torch int64 device tensor of hardware waves x zones elements
         ticks_ptr = int(phase_ticks.data_ptr())
@@ -232,7 +232,7 @@ def _opts(W: int, n_cus_hint: int, block_threads=0, grid_blocks=0, unroll=0, mod
         zmap = np.ascontiguousarray(zone_of_window, dtype=np.uint8)
         zmap_ptr, zmap_len = zmap.ctypes.data_as(C.POINTER(C.c_uint8)), int(zmap.size)
     o = _Opts(block_threads, grid_blocks, unroll, mode, bcast, nontemporal, chunk_iters, 0, first_wave, zone_bytes,
-              zmap_ptr, zmap_len, 0, ticks_ptr, None, None)
+              zmap_ptr, zmap_len, int(zone_descending), ticks_ptr, None, None)
     o._keepalive = zone_of_window if zone_of_window is None else zmap
     placement = cu_waves = None
     if want_placement:

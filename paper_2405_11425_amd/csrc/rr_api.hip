@@ -120,7 +120,8 @@ int make_plan(const void *region, uint64_t region_bytes, uint32_t line_bytes, ui
         if (opts->first_wave % pl.G != 0) return fail(RR_EINVAL, "first_wave must be a multiple of n_groups");
         pl.first_wave = opts->first_wave;
         const bool zoned = opts->zone_bytes || opts->zone_of_window;
-        if (opts->reserved2 != 0) return fail(RR_EINVAL, "reserved2 must be 0");
+        if (opts->zone_descending > 1) return fail(RR_EINVAL, "zone_descending must be 0 or 1");
+        if (opts->zone_descending && !zoned) return fail(RR_EINVAL, "zone_descending needs zone_bytes or zone_of_window");
         if (opts->phase_ticks && (!zoned || opts->mode != RR_MODE_FLAT))
             return fail(RR_EINVAL, "phase_ticks needs zones and a flat launch");
         if (zoned) {
@@ -157,6 +158,7 @@ int make_plan(const void *region, uint64_t region_bytes, uint32_t line_bytes, ui
                 }
             }
             while ((1ull << pl.zone_shift) < window_lines) pl.zone_shift++;
+            if (opts->zone_descending) std::reverse(pl.zone_mask, pl.zone_mask + pl.n_zones);
         }
     }
     if (pl.n_zones) pl.block = 256;  // the phased kernel's LDS lists are laid out for four waves per workgroup

@@ -1,0 +1,123 @@
+"""GPU parity beyond 256 GiB: one allocation of nearly the whole memory of the card (280 GiB on an idle MI355X).
+
+What is new out here: line indices above 2^31 and word indices above 2^36, a region of 35 (not 32) zone windows, and a
+footprint larger than what the second-level translation cache of an XCD covers, where the paper's windows per group
+(Sec. 2.4) matter on this GPU.  Everything is integer work and is compared bit-exactly with the CPU oracle.  This module
+runs after test_gpu_parity.py and takes its memory over; it gives the memory back when it is done.
+"""
+import gc
+import os
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+import paper_2405_11425_amd as rl                      # noqa: E402
+from paper_2405_11425_amd import workloads as wl       # noqa: E402
+from oracle import randline as orc                     # noqa: E402
+
+GiB = 1 << 30
+ORACLE_THREADS = 16
+
+
+@pytest.fixture(scope="module")
+def whole():
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    assert os.path.exists(rl.library_path()), "librandline.so is not built"
+    gc.collect()
+    torch.cuda.empty_cache()
+    free, _ = torch.cuda.mem_get_info()
+    gib = min(280, int((free - 6 * GiB) // (8 * GiB)) * 8)
+    if gib < 264:
+        pytest.skip(f"needs one allocation well beyond 256 GiB; {free / GiB:.1f} GiB are free")
+    buf = torch.empty(gib * GiB, dtype=torch.uint8, device="cuda")
+    rl.fill(buf, wl.FILL_SEED)
+    print(f"\n[whole-memory fixture] {free / GiB:.1f} GiB free, allocated {gib} GiB", flush=True)
+    yield buf
+    del buf
+    gc.collect()
+    torch.cuda.empty_cache()
+
+
+def oracle(R, B, W, I, **kw):
+    return orc.checksum(R, B, W, I, wl.FILL_SEED, wl.READ_SEED, n_threads=ORACLE_THREADS, **kw)
+
+
+def test_fill_and_streaming_sum_at_the_top(whole):
+    n_words = whole.numel() // 4
+    assert n_words > 1 << 36
+    for off in ((1 << 36) - 2048, (1 << 36) + 4096 * 3, n_words - 4096):
+        got = whole[off * 4:(off + 4096) * 4].cpu().numpy().view(np.uint32)
+        assert np.array_equal(got, orc.fill_words(wl.FILL_SEED, off, 4096)), f"word offset {off}"
+    top = whole.numel() - GiB
+    assert rl.seq_read(whole[top:]).checksum == orc.sum_words(wl.FILL_SEED, top // 4, GiB // 4, n_threads=ORACLE_THREADS)
+
+
+def test_walk_over_the_whole_allocation(whole):
+    R = whole.numel()
+    assert R // 128 > 1 << 31
+    want = orc.chase(R, 128, wl.FILL_SEED, 0, 0, 0xFFFFFFFF, 20000)
+    for cu in (None, 0):
+        got = rl.chase(whole, 128, 0, 0, 0xFFFFFFFF, 20000, cu=cu)
+        assert (got.final_line, got.word_sum) == want, cu
+    # a closed walk over one line per 128 MiB: 2239 lines, more translations than the second level holds
+    stride = (128 << 20) + 128
+    n = min(2239, R // stride)
+    got = rl.chase(whole, 128, 0, stride // 128, 0, 3 * n + 5, region_bytes=n * stride, cu=0)
+    assert (got.final_line, got.word_sum) == orc.chase(n * stride, 128, wl.FILL_SEED, 0, stride // 128, 0, 3 * n + 5)
+    assert got.final_line == 5 * (stride // 128)     # three laps and five hops
+
+
+def test_every_scheme_over_the_whole_allocation(whole):
+    """Full occupancy, 4096 reads per logical wave, over all of the allocation: uniform reads by every kernel, in zone
+    order in both directions, one window per XCD and windows drawn per CU."""
+    R = whole.numel()
+    cus = rl.enumerate_cus()
+    n = len(cus)
+    W, I = wl.resident_logical_waves(n), wl.ITERS_PER_WAVE
+    want = oracle(R, 128, W, I)
+    read = lambda wm=None, **kw: rl.rand_read(whole, 128, W * I, I, wl.READ_SEED, wm, **kw)
+    rates = {}
+    for name, kw in (("stream", {}), ("flat", dict(mode=rl.MODE_FLAT)), ("ticketed", dict(mode=rl.MODE_TICKET))):
+        got = read(**kw)
+        assert got.checksum == want, name
+        rates[name] = W * I * 128 / got.kernel_ms_event / 1e6
+    assert "rand_read_kernel" in rl.last_kernel()
+    n_win = R // (8 * GiB)
+    zm = rl.detect_zones(whole, n_win)
+    assert len(zm) == n_win and max(zm) < 16
+    for name, kw in (("zone order", {}), ("zone order, descending", dict(zone_descending=True)),
+                     ("zone order, ticketed, descending", dict(zone_descending=True, mode=rl.MODE_TICKET))):
+        got = read(zone_of_window=zm, **kw)
+        assert got.checksum == want, name
+        rates[name] = W * I * 128 / got.kernel_ms_event / 1e6
+    for k, scheme in ((8, "xcd"), (2, "random")):
+        g_of_cu, w_of_g = (wl.window_map_by_xcd(cus, k) if scheme == "xcd" else wl.window_map_random_per_cu(n, k, seed=k))
+        got = read(rl.WindowMap(k, g_of_cu, w_of_g))
+        assert got.checksum == oracle(R, 128, W, I, n_windows=k, window_of_group=w_of_g), (k, scheme)
+        rates[f"windows 1/{k}, {scheme}"] = W * I * 128 / got.kernel_ms_event / 1e6
+    print(f"\n[{R // GiB} GiB, zones {zm}; one launch each, nothing warmed up] " + ", ".join(f"{k}: {v:.0f} GB/s" for k, v in rates.items()), flush=True)
+
+
+@pytest.mark.parametrize("R,B,lanes,W,I,zone", [
+    (3 << 24, 128, 32, 301, 1100, 1 << 24),         # odd wave count: the ticketed zone kernel
+    (3 << 24, 256, 32, 64, 1024, 5 << 22),          # the zone stream kernel, uneven zones
+    (5 << 22, 512, 32, 32, 512, 1 << 22),           # 16-byte lanes, 5 zones
+    (1 << 26, 256, 64, 32, 704, 1 << 25),           # 64-lane lines
+    (1 << 26, 128, 32, 10, 2100, 1 << 26),          # a single zone: both directions are the same launch
+])
+def test_zone_direction_does_not_change_the_checksum(whole, R, B, lanes, W, I, zone):
+    want = orc.checksum(R, B, W, I, wl.FILL_SEED, wl.READ_SEED, n_threads=ORACLE_THREADS)
+    for mode in (rl.MODE_AUTO, rl.MODE_TICKET, rl.MODE_FLAT):
+        for down in (False, True):
+            got = rl.rand_read(whole, B, W * I, I, wl.READ_SEED, lanes_per_line=lanes, region_bytes=R, zone_bytes=zone,
+                               mode=mode, zone_descending=down)
+            assert got.checksum == want, (mode, down)
+    # a scattered map, descending, equals the plain read too
+    if (R // B) % 8 == 0 and ((R // B // 8) & (R // B // 8 - 1)) == 0:
+        got = rl.rand_read(whole, B, W * I, I, wl.READ_SEED, lanes_per_line=lanes, region_bytes=R,
+                           zone_of_window=[2, 0, 1, 0, 2, 2, 1, 0], zone_descending=True)
+        assert got.checksum == want

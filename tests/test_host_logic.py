@@ -105,6 +105,8 @@ FAKE = (1 << 21, 1 << 20)  # an aligned, non-null "device pointer" that is never
     ((FAKE, 128, 8, 8, 7), {"zone_of_window": [0, 1, 2]}, "divide"),
     ((FAKE, 128, 8, 8, 7), {"zone_of_window": [0, 16]}, "below 16"),
     ((FAKE, 128, 8, 8, 7), {"zone_of_window": [0] * 65}, "n_zone_windows"),
+    ((FAKE, 128, 8, 8, 7), {"zone_of_window": [0, 1], "zone_descending": 2}, "zone_descending"),
+    ((FAKE, 128, 8, 8, 7), {"zone_descending": True}, "zone_descending needs"),
     (((1 << 21, 3 << 20), 128, 8, 8, 7), {"zone_of_window": [0, 1]}, "power-of-two"),
 ])
 def test_rand_read_rejects_bad_arguments_without_a_device(args, kw, needle):

@@ -24,11 +24,11 @@ FILL_SEED, READ_SEED = 1, 7          # the driver's fixed seeds (workloads.py)
 def expected(row, threads):
     """(value in the row, oracle's value) for a row that can be checked, else a string saying why not."""
     e = row.get("experiment")
-    if e in ("region", "lines", "windows"):
+    if e in ("region", "lines", "windows", "beyond"):
         R, B, I = int(row["region_gib"] * GiB), row["line_bytes"], row["iters_per_wave"]
         W = row["n_reads"] // I
         wog, nw = None, 1
-        if e == "windows" and row.get("scheme") != "none":
+        if (e == "windows" and row.get("scheme") != "none") or (e == "beyond" and row["scheme"].startswith("windows")):
             if "window_of_group" not in row:
                 return "row does not say which window each group reads"
             wog, nw = row["window_of_group"], row["n_windows"]
@@ -47,9 +47,13 @@ def expected(row, threads):
         return row["checksum"], orc.checksum(R, 128, row["n_reads"] // I, I, FILL_SEED, READ_SEED, n_threads=threads)
     if e == "stream" and "checksum" in row:
         return row["checksum"], orc.sum_words(FILL_SEED, 0, row["region_gib"] * GiB // 4, n_threads=threads)
-    if e == "latency":
+    if e in ("latency", "beyond-latency"):
         R = row["footprint_mib"] * MiB
         return (row["final_line"], row["word_sum"]), orc.chase(R, 128, FILL_SEED, 0, 0, 0xFFFFFFFF, row["hops"])
+    if e == "beyond-pages":
+        stride = row["distance_bytes"] + 128
+        return ((row["final_line"], row["word_sum"]),
+                orc.chase(row["n_lines"] * stride, 128, FILL_SEED, 0, stride // 128, 0, row["hops"]))
     if e == "latency-per-xcd":
         R = row["footprint_mib"] * MiB
         if not row["all_cus_agree"]:
