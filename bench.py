@@ -17,8 +17,11 @@ measured by the library with HIP events on the launch stream, against the 8 TB/s
 top-level figures are those of the dominant kernel (the plain-order read) over regions of 4 GiB and
 more, `kernels` lists every kernel of the timed steps with its own figures, `all_timed_launches`
 is all of them together.
-`cpu_baseline` times the CPU oracle (recompute mode) on one sweep point on the host's cores and
-checks that its checksum equals the GPU's for the same arguments.
+`cpu_baseline` times the CPU oracle (recompute mode) on one whole step on the host's cores and
+checks that its checksums equal the GPU's for the same arguments.
+`beyond_the_sweep` is context measured after the timed steps: if the card has the memory, the
+allocation is 280 GiB rather than 256, and the same launch is timed over 264, 272 and 280 GiB
+in plain order, zone by zone and with one window per XCD (paper Sec. 2.4).
 """
 import argparse
 import json
@@ -52,6 +55,9 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--max-region-gib", type=int, default=256)
+    ap.add_argument("--allocation-gib", type=int, default=280,
+                    help="allocate up to this much (a multiple of 8 GiB) if the card has it: what lies beyond "
+                         "--max-region-gib is measured after the timed steps, as context (beyond_the_sweep)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
     ap.add_argument("--one-by-one", action="store_true",
                     help="one rr_rand_read call (and one wait) per region size instead of one rr_rand_read_batch per step")
@@ -83,7 +89,16 @@ def main():
     max_gib = min(args.max_region_gib, int((free - 4 * GiB) // GiB))
     cu_table = rl.enumerate_cus()
     n_cus = len(cu_table)
-    region = torch.empty(max_gib * GiB, dtype=torch.uint8, device="cuda")
+    # the sweep's regions are prefixes of one allocation; if the card has more than the sweep needs, the allocation
+    # is larger still, for the context measurements beyond the sweep's largest region
+    alloc_gib = max(max_gib, min(args.allocation_gib, int((free - 6 * GiB) // (8 * GiB)) * 8))
+    try:
+        region = torch.empty(alloc_gib * GiB, dtype=torch.uint8, device="cuda")
+    except RuntimeError:
+        if alloc_gib == max_gib:
+            raise
+        alloc_gib = max_gib
+        region = torch.empty(alloc_gib * GiB, dtype=torch.uint8, device="cuda")
     t0 = time.perf_counter()
     rl.fill(region, wl.FILL_SEED)
     torch.cuda.synchronize()
@@ -187,6 +202,36 @@ def main():
     torch.cuda.synchronize()
     wall_s = time.perf_counter() - t0
 
+    # Context, after the timed steps: regions beyond the sweep, up to the whole allocation.  Above 256 GiB a region
+    # holds more translations than the second-level translation cache of an XCD; what that costs uniform reads in
+    # plain order, and what zone order (direction alternating from launch to launch) and one window per XCD (paper
+    # Sec. 2.4) make of it.
+    beyond = []
+    for gib in sorted({g for g in (264, 272, alloc_gib) if max_gib < g <= alloc_gib and g % 8 == 0}):
+        R = gib * GiB
+        row = {"region_gib": gib}
+        try:
+            rd = lambda seed, wm=None, **kw: rl.rand_read(region, c0.line_bytes, c0.n_reads, c0.iters_per_wave, seed, wm,
+                                                          lanes_per_line=c0.lanes_per_line, region_bytes=R, **kw)
+            rate = lambda rs: round(c0.bytes_read / sorted(r.kernel_ms_event for r in rs)[len(rs) // 2] / 1e6, 1)
+            rd(999)
+            plain = [rd(wl.READ_SEED + i) for i in range(4)]
+            row["gbps_plain"] = rate(plain)
+            zm = rl.detect_zones(region, gib // 8, region_bytes=R)
+            rd(999, zone_of_window=zm, zone_descending=True)
+            zoned = [rd(wl.READ_SEED + i, zone_of_window=zm, zone_descending=bool(i % 2)) for i in range(6)]
+            row["gbps_zone_by_zone_direction_alternating"] = rate(zoned)
+            g_of_cu, w_of_g = wl.window_map_by_xcd(cu_table, 8)
+            wm = rl.WindowMap(8, g_of_cu, w_of_g)
+            rd(999, wm)
+            row["gbps_one_window_of_8_per_xcd"] = rate([rd(wl.READ_SEED + i, wm) for i in range(4)])
+            row["zone_of_window_8gib"] = zm
+            row["zone_order_checksums_equal_plain"] = all(a.checksum == b.checksum for a, b in zip(plain, zoned))
+            row["checksum_plain_first_seed"] = f"{plain[0].checksum:#018x}"
+        except Exception as e:   # context only: say what went wrong and go on
+            row["error"] = f"{type(e).__name__}: {e}"
+        beyond.append(row)
+
     bytes_per_step = sum(c.bytes_read for c in configs)
     value = bytes_per_step * args.steps / wall_s / 1e9
     curve = []
@@ -257,13 +302,13 @@ def main():
                    "regions_gib": [c.region_bytes // GiB for c in configs], "line_bytes": 128,
                    "lanes_per_line": 32, "logical_waves": configs[0].logical_waves,
                    "iters_per_wave": configs[0].iters_per_wave, "reads_per_launch": configs[0].n_reads,
-                   "allocation_gib": max_gib, "fill_seed": wl.FILL_SEED, "first_read_seed": wl.READ_SEED,
+                   "allocation_gib": alloc_gib, "fill_seed": wl.FILL_SEED, "first_read_seed": wl.READ_SEED,
                    "n_cus": n_cus},
         "pct_of_hbm_peak": round(value / HBM_PEAK_GBPS * 100, 1),
         "curve": curve,
         "environment": env,
         "gbps_at_largest_region": curve[-1]["gbps"],
-        "fill_gbps": round(max_gib * GiB / fill_s / 1e9, 1),
+        "fill_gbps": round(alloc_gib * GiB / fill_s / 1e9, 1),
         "roofline": roofline,
         # context: the same launches as one wavefront per pair of logical waves, every wave slot occupied
         "full_occupancy_flat": {"kernel": flat_kernel, "launches_per_region": 3, "curve": full_occupancy},
@@ -272,6 +317,12 @@ def main():
                                "random_512B_lines_gbps": 1600, "throughput_collapses_above_gb": 64},
     }
 
+    if beyond:
+        out["beyond_the_sweep"] = {
+            "what": "context, measured after the timed steps and not part of value: the same launch over regions larger "
+                    "than the sweep's largest, up to the whole allocation; median of 4 launches (zone order: of 6, "
+                    "ascending and descending in turn)",
+            "curve": beyond}
     if zone_info is not None:
         out["zone_order"] = zone_info
 
@@ -310,6 +361,11 @@ def main():
         del host
         for c, cfg in zip(curve, configs):
             c["oracle_checksum_first_step"] = f"{oracle_first[cfg.name]:#018x}"
+        for row in beyond:      # not timed
+            if "checksum_plain_first_seed" in row:
+                want = orc.checksum(row["region_gib"] * GiB, c0.line_bytes, c0.logical_waves, c0.iters_per_wave,
+                                    c0.fill_seed, wl.READ_SEED, n_threads=cores)
+                row["oracle_checksum_plain_first_seed"] = f"{want:#018x}"
         out["cpu_baseline"] = {
             "value": round(reads_all * cfg.line_bytes / t_all / 1e9, 3), "unit": "GB/s", "cores": used,
             "kind": "oracle",
