@@ -174,6 +174,16 @@ def report(rows):
                    + "; ".join(f"one line per {d >> 20} MiB: " + ", ".join(f"{r['n_lines']} [{r['translations']}]: {r['ns_per_hop']:.0f}"
                                                                          for r in by["beyond-pages"] if r["distance_bytes"] == d)
                                for d in sorted({r["distance_bytes"] for r in by["beyond-pages"]}, reverse=True)) + ".\n")
+    if by["beyond-switch"]:
+        out.append("Launches over [0, 96), [96, 192) and [192, top) GiB in a cycle against each region repeated (microseconds per "
+                   "launch of 16384 logical waves, median):\n")
+        body = [[f"{r['top_gib']} GiB", r["iters_per_wave"], r["us_each_region_repeated"], r["us_regions_in_a_cycle"],
+                 f"{r['us_regions_in_a_cycle'] - r['us_each_region_repeated']:+.1f}",
+                 " / ".join(str(r[k]) for k in ("us_in_a_cycle_after_a_touch_of_32768_lines",
+                                                "us_in_a_cycle_after_a_touch_of_131072_lines") if k in r)]
+                for r in by["beyond-switch"]]
+        out.append(table(["top", "reads per wave", "repeated", "in a cycle", "difference",
+                          "in a cycle, a small launch over the region first (32768 / 131072 lines)"], body))
     return "\n".join(out)
 
 

@@ -26,7 +26,7 @@ measured point to a JSONL file (points already present are skipped, so a run can
            XCD can run out of their first level together, and the pair probe of 4-CU blocks on windows of their
            own, which finds the groups that share the second level (Sec. 2.2, 2.3)
   beyond   an allocation of nearly the whole memory (the largest multiple of 8 GiB that fits, 280 GiB on an idle card):
-           regions from 248 GiB to all of it, beyond the 256 GiB that this GPU's second-level translation cache covers:
+           regions from 248 GiB to all of it, beyond the 256 GiB that the second-level translation cache of an XCD covers:
            uniform reads in plain order, zone by zone (every launch in the same direction / direction alternating),
            one window per XCD against random windows per CU (the paper's remedy and its baseline, Sec. 2.4, Fig. 5),
            and the walk pinned to one CU.  Not part of `all` (it needs the memory to itself)
@@ -661,8 +661,8 @@ class Runner:
             reg.destroy()
 
     def beyond(self):
-        """Regions larger than what the second-level translation cache of an XCD covers (2048 translations of
-        128 MiB = 256 GiB): the paper's cliff (Sec. 2.1, Fig. 1) and its remedy (Sec. 2.4, Fig. 5) on this GPU."""
+        """Regions larger than what the second-level translation cache of an XCD covers (256 GiB): the paper's cliff
+        (Sec. 2.1, Fig. 1) and its remedy (Sec. 2.4, Fig. 5) on this GPU."""
         wl, rl = self.wl, self.rl
         n = len(self.cus)
         W = wl.resident_logical_waves(n)
@@ -720,8 +720,11 @@ class Runner:
         # how many translations the second level holds: a closed walk over N lines that lie one per 128 MiB (or two per
         # 128 MiB), pinned to one CU -- every hop misses the CU's 32 entries, and hits the second level as long as it
         # holds all N translations
+        # ... or one per 130 MiB: still every line in another 128 MiB, but no longer all in the same 1/64 of the 2 MiB
+        # pages -- which tells a cache of 2048 entries of 128 MiB from a set-indexed one of 131072 entries of 2 MiB
         for dist, counts in ((128 << 20, (512, 1024, 1536, 1920, 2032, 2040, 2048, 2056, 2064, 2080, 2112, 2176, 2239)),
-                             (64 << 20, (3840, 4064, 4096, 4128, 4224, 4400))):
+                             (64 << 20, (3840, 4064, 4096, 4128, 4224, 4400)),
+                             (130 << 20, (1024, 1920, 2048, 2112, 2176, 2200))):
             stride = dist + 128
             for n_lines in counts:
                 R = n_lines * stride
@@ -735,6 +738,37 @@ class Runner:
                                 "translations": len({(i * stride) >> 27 for i in range(n_lines)}), "span_gib": round(R / wl.GiB, 2), "hops": hops, "cu": 0,
                                 "ns_per_hop": round(statistics.median(r.ns_per_hop for r in walks), 1),
                                 "final_line": walks[0].final_line, "word_sum": walks[0].word_sum, **self.meta})
+
+        # What a change of zone costs: launches over [0, 96), [96, 192), [192, top) GiB in a cycle against the same
+        # launches with each region repeated, by top and by launch length; and with a small launch over the next
+        # region in front of each (does touching its translations ahead help?)
+        base = self.region.data_ptr()
+        def launch_us(regions, iters, touch=None, n=24):
+            f = lambda seed, r, w=W, i=iters: rl.rand_read((base + r[0] * wl.GiB, r[1] * wl.GiB), 128, w * i, i, seed)
+            for k in range(30):
+                f(100 + k, regions[k % len(regions)])
+            us = []
+            for k in range(n * len(regions)):
+                r = regions[k % len(regions)]
+                if touch:
+                    f(500 + k, r, touch[0], touch[1])
+                us.append(f(7 + k, r).kernel_ms_event * 1e3)
+            return round(statistics.median(us), 1)
+        for top in (256, 260, 264, 272, self.max_gib):
+            if top > self.max_gib or top <= 192:
+                continue
+            zones = [(0, 96), (96, 96), (192, top - 192)]
+            for iters in ((1024,) if top != self.max_gib else (64, 256, 1024, 4096)):
+                key = f"beyond-switch/{top}/{iters}"
+                if key in self.seen:
+                    continue
+                row = {"experiment": "beyond-switch", "top_gib": top, "iters_per_wave": iters, "logical_waves": W,
+                       "us_each_region_repeated": round(statistics.mean(launch_us([r], iters) for r in zones), 1),
+                       "us_regions_in_a_cycle": launch_us(zones, iters)}
+                if top == self.max_gib and iters == 1024:
+                    row["us_in_a_cycle_after_a_touch_of_32768_lines"] = launch_us(zones, iters, touch=(2048, 16))
+                    row["us_in_a_cycle_after_a_touch_of_131072_lines"] = launch_us(zones, iters, touch=(8192, 16))
+                self.emit(key, {**row, **self.meta})
 
     def calib(self):
         """Three kernels of exactly known traffic, 8 GiB each, for scaling FETCH_SIZE / WRITE_SIZE."""
