@@ -322,8 +322,20 @@ def test_report_renders_every_kind_of_row():
         {"experiment": "pieces-latency", "footprint_pieces": [16, 64], "ns_per_hop_by_cu": {"0": [410.0, 733.0]}},
         {"experiment": "pieces-flat-curve", "by_grouping": {"cu": {"groups": 256, "reach_pieces": 24, "own_window_pieces": [16, 32],
          "own_window_gbps": [6900.0, 2800.0], "curve": [{"windows": 2, "region_mib": 6.0, "gbps_windowed": 6100.0, "gbps_uniform": 900.0}]}}},
+        {"experiment": "beyond", "scheme": "uniform", "launch_size": "1x", "region_gib": 280.0, "gbps": 4006.0, "allocation_gib": 280},
+        {"experiment": "beyond", "scheme": "windows 1/8, xcd", "launch_size": "1x", "region_gib": 280.0, "gbps": 6200.0, "allocation_gib": 280},
+        {"experiment": "beyond", "scheme": "uniform, zone by zone", "launch_size": "16x", "region_gib": 264.0, "gbps": 6864.0, "allocation_gib": 280},
+        {"experiment": "beyond-latency", "footprint_mib": 286720, "ns_per_hop": 545.0},
+        {"experiment": "beyond-pages", "distance_bytes": 130 << 20, "n_lines": 2200, "translations": 2200, "ns_per_hop": 238.0},
+        {"experiment": "beyond-pages", "distance_bytes": 128 << 20, "n_lines": 2239, "translations": 2239, "ns_per_hop": 304.0},
+        {"experiment": "beyond-switch", "top_gib": 280, "iters_per_wave": 1024, "us_each_region_repeated": 317.9,
+         "us_regions_in_a_cycle": 381.4, "us_in_a_cycle_after_a_touch_of_32768_lines": 379.0},
     ]
     text = report.report(rows)
+    for needle in ("an allocation of 280 GiB", "| uniform |  | 4006 |", "| windows 1/8, xcd |  | 6200 |",
+                   "| uniform, zone by zone, 16x longer launches | 6864 |  |", "280 GiB: 545", "one line per 130 MiB: 2200 [2200]: 238",
+                   "one line per 128 MiB: 2239 [2239]: 304", "| 280 GiB | 1024 | 317.9 | 381.4 | +63.5 | 379.0 |"):
+        assert needle in text, needle
     for needle in ("Throughput vs region size", "| 256 GiB |  | 6700 (83.8 %) |  | 6400 (80.0 %) |", "64 x 4 B = 256 B", "xcd | 8",
                    "sequential read", "write | 16 GiB", "2 zones", "32 groups of [8] CUs", "1190-1200 GB/s", "| 1 MiB | 155.0 |",
                    "| 33 | 200.0 |", "| 512 MiB | 4096 | 280 |", "96: 10", "6: 11.0", "the groups are the XCDs: True",
