@@ -204,8 +204,8 @@ def main():
 
     # Context, after the timed steps: regions beyond the sweep, up to the whole allocation.  Above 256 GiB a region
     # holds more translations than the second-level translation cache of an XCD; what that costs uniform reads in
-    # plain order, and what zone order (direction alternating from launch to launch) and one window per XCD (paper
-    # Sec. 2.4) make of it.
+    # plain order, and what the library's division of the region between the halves of the XCDs, zone order (direction
+    # alternating from launch to launch) and one window per XCD (paper Sec. 2.4) make of it.
     beyond = []
     for gib in sorted({g for g in (264, 272, alloc_gib) if max_gib < g <= alloc_gib and g % 8 == 0}):
         R = gib * GiB
@@ -216,7 +216,10 @@ def main():
             rate = lambda rs: round(c0.bytes_read / sorted(r.kernel_ms_event for r in rs)[len(rs) // 2] / 1e6, 1)
             rd(999)
             plain = [rd(wl.READ_SEED + i) for i in range(4)]
-            row["gbps_plain"] = rate(plain)
+            row["gbps_plain"] = rate(plain)           # the library divides such a region between the halves of the XCDs
+            row["kernel_plain"] = rl.last_kernel()
+            rd(999, xcd_split=rl.SPLIT_OFF)
+            row["gbps_plain_not_divided_between_the_xcd_halves"] = rate([rd(wl.READ_SEED + i, xcd_split=rl.SPLIT_OFF) for i in range(4)])
             zm = rl.detect_zones(region, gib // 8, region_bytes=R)
             rd(999, zone_of_window=zm, zone_descending=True)
             zoned = [rd(wl.READ_SEED + i, zone_of_window=zm, zone_descending=bool(i % 2)) for i in range(6)]

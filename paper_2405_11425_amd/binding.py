@@ -18,6 +18,7 @@ RR_OK, RR_EINVAL, RR_EHIP, RR_EPLACE = 0, -1, -2, -3
 RR_CU_EXCLUDED = 0xFFFF
 BCAST_DEFAULT, BCAST_LDS, BCAST_DPP, BCAST_READLANE = 0, 1, 2, 3
 MODE_AUTO, MODE_FLAT, MODE_TICKET, MODE_STREAM = 0, 1, 2, 3
+SPLIT_DEFAULT, SPLIT_ON, SPLIT_OFF = 0, 1, 2
 NT_DEFAULT, NT_ON, NT_OFF = 0, 1, 2
 OP_WRITE, OP_ADD = 1, 2
 
@@ -50,7 +51,7 @@ class _ChaseResult(C.Structure):
 class _Opts(C.Structure):
     _fields_ = [("block_threads", C.c_uint32), ("grid_blocks", C.c_uint32), ("unroll", C.c_uint32),
                 ("mode", C.c_uint32), ("bcast", C.c_uint32), ("nontemporal", C.c_uint32),
-                ("chunk_iters", C.c_uint32), ("reserved", C.c_uint32), ("first_wave", C.c_uint64),
+                ("chunk_iters", C.c_uint32), ("xcd_split", C.c_uint32), ("first_wave", C.c_uint64),
                 ("zone_bytes", C.c_uint64), ("zone_of_window", C.POINTER(C.c_uint8)), ("n_zone_windows", C.c_uint32),
                 ("zone_descending", C.c_uint32), ("phase_ticks", C.c_void_p), ("placement_out", C.POINTER(C.c_uint16)),
                 ("cu_waves_out", C.POINTER(C.c_uint32))]
@@ -223,7 +224,7 @@ class ReadResult:
 
 def _opts(W: int, n_cus_hint: int, block_threads=0, grid_blocks=0, unroll=0, mode=0, bcast=0,
           nontemporal=0, chunk_iters=0, first_wave=0, zone_bytes=0, zone_of_window=None, phase_ticks=None,
-          zone_descending=False, want_placement=False, want_cu_waves=False):
+          zone_descending=False, xcd_split=0, want_placement=False, want_cu_waves=False):
     ticks_ptr = None
     if phase_ticks is not None:   # a torch int64 device tensor of hardware waves x zones elements
         ticks_ptr = int(phase_ticks.data_ptr())
@@ -231,7 +232,7 @@ def _opts(W: int, n_cus_hint: int, block_threads=0, grid_blocks=0, unroll=0, mod
     if zone_of_window is not None:
         zmap = np.ascontiguousarray(zone_of_window, dtype=np.uint8)
         zmap_ptr, zmap_len = zmap.ctypes.data_as(C.POINTER(C.c_uint8)), int(zmap.size)
-    o = _Opts(block_threads, grid_blocks, unroll, mode, bcast, nontemporal, chunk_iters, 0, first_wave, zone_bytes,
+    o = _Opts(block_threads, grid_blocks, unroll, mode, bcast, nontemporal, chunk_iters, xcd_split, first_wave, zone_bytes,
               zmap_ptr, zmap_len, int(zone_descending), ticks_ptr, None, None)
     o._keepalive = zone_of_window if zone_of_window is None else zmap
     placement = cu_waves = None

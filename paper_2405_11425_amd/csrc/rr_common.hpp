@@ -86,6 +86,9 @@ struct ReadParams {
     u32 n_zones;              // phased variant: number of zones; the region is cut into at most 64 windows of
     u32 zone_shift;           // 2^zone_shift lines, and bit v of zone_mask[z] says that window v belongs to zone z
     u64 zone_mask[16];
+    u32 split_half;           // zone stream kernel: 0, or half the number of XCDs: workgroup b belongs to half
+    u64 split_incl[2];        // (b / split_half) & 1, reads only windows in split_incl[that half] of its own units and
+                              // the other windows of the units of workgroup b ^ split_half
     Reducer red;              // L = lines per window
     Scratch *scratch;
     const Tables *tables;

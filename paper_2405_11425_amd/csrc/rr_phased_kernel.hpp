@@ -261,7 +261,20 @@ __global__ void __launch_bounds__(256) rand_read_zone_stream_kernel(const ReadPa
     const u64 units_total = p.quota / LPW;
     const u32 u_begin = (u32)(units_total * blockIdx.x / gridDim.x);
     const u32 n_units = (u32)(units_total * (blockIdx.x + 1) / gridDim.x) - u_begin;
-    const u32 per_zone = n_units * cpw;              // tickets of this workgroup per zone
+    // With the split on, the workgroup also goes through the units of its partner in the other half of the XCDs, and
+    // reads of its own units only what its half may read, of the partner's only what the partner's half may not.
+    u32 pu_begin = 0, pn_units = 0;
+    u64 incl = ~0ull, partner_incl = ~0ull;
+    if (p.split_half) {
+        const u32 partner = blockIdx.x ^ p.split_half;
+        pu_begin = (u32)(units_total * partner / gridDim.x);
+        pn_units = (u32)(units_total * (partner + 1) / gridDim.x) - pu_begin;
+        const u32 half = (blockIdx.x / p.split_half) & 1u;
+        incl = p.split_incl[half];
+        partner_incl = p.split_incl[half ^ 1u];  // what the partner leaves out lies inside incl
+    }
+    const u32 own_tickets = n_units * cpw;
+    const u32 per_zone = own_tickets + pn_units * cpw;  // tickets of this workgroup per zone
     const u32 n_tickets = per_zone * p.n_zones;
     if (threadIdx.x == 0) next_ticket = 0;
     __syncthreads();
@@ -298,11 +311,30 @@ __global__ void __launch_bounds__(256) rand_read_zone_stream_kernel(const ReadPa
                 }
                 worked = true;
                 const u32 z = t / per_zone;
-                const u32 rest = t - z * per_zone;
+                u32 rest = t - z * per_zone;
+                u32 first_unit = u_begin;
+                zone_mask = p.zone_mask[z];
+                // own tickets and the partner's in turn while both last: a partner's ticket yields few lines per
+                // draw, and the waves of a workgroup should not all be busy with such tickets at the same time
+                const u32 paired = 2 * (own_tickets < per_zone - own_tickets ? own_tickets : per_zone - own_tickets);
+                bool partners;
+                if (rest < paired) {
+                    partners = rest & 1u;
+                    rest >>= 1;
+                } else {
+                    partners = own_tickets < per_zone - own_tickets;
+                    rest -= paired / 2;
+                }
+                if (partners) {  // a ticket of the partner's units: what the partner leaves out
+                    first_unit = pu_begin;
+                    zone_mask &= ~partner_incl;
+                } else {
+                    zone_mask &= incl;
+                }
+                if (zone_mask == 0) continue;  // nothing of this zone is for this ticket: take the next one
                 const u32 unit = rest / cpw;
                 const u32 chunk = rest - unit * cpw;
-                zone_mask = p.zone_mask[z];
-                const u64 w = p.first_wave + (u64)(u_begin + unit) * LPW;
+                const u64 w = p.first_wave + (u64)(first_unit + unit) * LPW;
                 seed_lo = mix64(p.read_seed + (w + 1) * kGamma);
                 if (LPW == 2) seed_hi = mix64(p.read_seed + (w + 2) * kGamma);
                 it_base = chunk * p.chunk_iters;

@@ -674,13 +674,17 @@ class Runner:
             cfg = wl.ReadConfig(f"beyond-{gib}GiB", R, 128, 32, W, wl.ITERS_PER_WAVE)
             long_cfg = wl.ReadConfig(f"beyond-{gib}GiB-16x", R, 128, 32, 16 * W, wl.ITERS_PER_WAVE)
             zm = rl.detect_zones(self.region, gib // 8, region_bytes=R) if gib % 8 == 0 and gib // 8 <= 64 else None
-            runs = [("uniform", cfg, None, {}), ("uniform, every wave slot occupied", cfg, None, {"mode": rl.MODE_FLAT}),
+            # "uniform" is what a plain call does: above 256 GiB the library divides the region between the two halves
+            # of the XCDs by itself (RR_SPLIT_*); "not divided" is the same call with that switched off
+            runs = [("uniform", cfg, None, {}), ("uniform, not divided between the XCD halves", cfg, None, {"xcd_split": rl.SPLIT_OFF}),
+                    ("uniform, every wave slot occupied", cfg, None, {"mode": rl.MODE_FLAT}),
                     ("uniform, ticketed", cfg, None, {"mode": rl.MODE_TICKET})]
             if zm is not None and max(zm) > 0:
                 z = {"zone_of_window": zm}
                 runs += [("uniform, zone by zone", cfg, None, z),
                          ("uniform, zone by zone, direction alternating", cfg, None,
-                          {**z, "alternate": [{"zone_descending": False}, {"zone_descending": True}]})]
+                          {**z, "alternate": [{"zone_descending": False}, {"zone_descending": True}]}),
+                         ("uniform, zone by zone, divided between the XCD halves", cfg, None, {**z, "xcd_split": rl.SPLIT_ON})]
             for k in (2, 8):
                 for scheme in ("xcd", "random-per-cu"):
                     g, w = (wl.window_map_by_xcd(self.cus, k) if scheme == "xcd"
@@ -688,6 +692,7 @@ class Runner:
                     runs.append((f"windows 1/{k}, {scheme}", cfg, (k, g, w), {}))
             if not self.args.beyond_short:
                 runs.append(("uniform", long_cfg, None, {}))
+                runs.append(("uniform, not divided between the XCD halves", long_cfg, None, {"xcd_split": rl.SPLIT_OFF}))
                 if zm is not None and max(zm) > 0:
                     runs.append(("uniform, zone by zone", long_cfg, None, {"zone_of_window": zm}))
             for scheme, c, wmap, kw in runs:

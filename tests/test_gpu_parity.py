@@ -26,6 +26,7 @@ def region():
     """One device allocation, as large as fits (256 GiB on an idle MI355X), filled with seed 1."""
     assert torch.cuda.is_available(), "these tests need the GPU"
     assert os.path.exists(rl.library_path()), "librandline.so is not built"
+    torch.cuda.empty_cache()              # what an earlier test module may have left in torch's allocator
     free, _ = torch.cuda.mem_get_info()
     gib = min(256, int((free - 6 * GiB) // GiB))
     assert gib >= 2, "not enough free device memory"
@@ -573,6 +574,32 @@ def test_zone_stream_geometry_does_not_change_checksum(region, B, lanes):
     assert odd.checksum == oracle(R, B, W, 100, read_seed=5)
     with pytest.raises(rl.RandlineError, match="stream mode does not work with"):
         rl.rand_read(region, B, W * 100, 100, 5, lanes_per_line=lanes, region_bytes=R, zone_bytes=1 << 24, mode=rl.MODE_STREAM)
+
+
+@pytest.mark.parametrize("R,B,lanes,W,I", [
+    (1 << 28, 128, 32, 256, 4096),        # the small reference configuration: 64 windows, 8 pairs divided
+    (12288, 128, 32, 64, 128),            # 96 lines: 48 windows of 2 lines
+    (3 << 24, 256, 32, 130, 576),         # 8-byte lanes, a line count that is no power of two, 48 windows
+    ((1 << 26) + (1 << 20), 512, 32, 32, 192),   # 16-byte lanes; the last window is shorter than the others
+    (5 << 22, 256, 64, 33, 320),          # 64-lane lines, odd wave count
+])
+def test_plain_read_divided_between_the_xcd_halves(region, R, B, lanes, W, I):
+    """xcd_split on a read without a zone map: the zone stream kernel with the region as one zone of up to 64 windows, every
+    unit gone through by a workgroup of each half of the XCDs.  Same checksum as the plain kernels', whatever the grid."""
+    want = oracle(R, B, W, I)
+    plain = rl.rand_read(region, B, W * I, I, wl.READ_SEED, lanes_per_line=lanes, region_bytes=R)
+    assert plain.checksum == want and rl.last_kernel().startswith("rand_read_stream_kernel<")
+    for grid in (0, 8, 64, 1024):
+        got = rl.rand_read(region, B, W * I, I, wl.READ_SEED, lanes_per_line=lanes, region_bytes=R, xcd_split=rl.SPLIT_ON,
+                           grid_blocks=grid)
+        assert got.checksum == want, grid
+        assert rl.last_kernel().startswith("rand_read_zone_stream_kernel<")
+    for bad in (dict(grid_blocks=12), dict(mode=rl.MODE_FLAT), dict(mode=rl.MODE_TICKET), dict(chunk_iters=0, placement=True)):
+        want_placement = bad.pop("placement", False)
+        with pytest.raises(rl.RandlineError) as e:
+            rl.rand_read(region, B, W * I, I, wl.READ_SEED, lanes_per_line=lanes, region_bytes=R, xcd_split=rl.SPLIT_ON,
+                         want_placement=want_placement, **bad)
+        assert e.value.code == rl.RR_EINVAL and "xcd_split" in str(e.value), bad
 
 
 def test_stream_kernels_on_seeded_random_shapes(region):

@@ -37,6 +37,7 @@ def whole():
     rl.fill(buf, wl.FILL_SEED)
     print(f"\n[whole-memory fixture] {free / GiB:.1f} GiB free, allocated {gib} GiB", flush=True)
     yield buf
+    buf.untyped_storage().resize_(0)     # pytest still holds the tensor: let go of its memory, not of the object
     del buf
     gc.collect()
     torch.cuda.empty_cache()
@@ -72,8 +73,9 @@ def test_walk_over_the_whole_allocation(whole):
 
 
 def test_every_scheme_over_the_whole_allocation(whole):
-    """Full occupancy, 4096 reads per logical wave, over all of the allocation: uniform reads by every kernel, in zone
-    order in both directions, one window per XCD and windows drawn per CU."""
+    """Full occupancy, 4096 reads per logical wave, over all of the allocation: uniform reads by every kernel (by default
+    the zone stream kernel with the region divided between the halves of the XCDs), in zone order in both directions with
+    and without that division, one window per XCD and windows drawn per CU."""
     R = whole.numel()
     cus = rl.enumerate_cus()
     n = len(cus)
@@ -81,15 +83,20 @@ def test_every_scheme_over_the_whole_allocation(whole):
     want = oracle(R, 128, W, I)
     read = lambda wm=None, **kw: rl.rand_read(whole, 128, W * I, I, wl.READ_SEED, wm, **kw)
     rates = {}
-    for name, kw in (("stream", {}), ("flat", dict(mode=rl.MODE_FLAT)), ("ticketed", dict(mode=rl.MODE_TICKET))):
+    for name, kw, kernel in (("default (XCD halves split)", {}, "rand_read_zone_stream_kernel<"),
+                             ("stream", dict(xcd_split=rl.SPLIT_OFF), "rand_read_stream_kernel<"),
+                             ("flat", dict(mode=rl.MODE_FLAT), "rand_read_flat_kernel<"),
+                             ("ticketed", dict(mode=rl.MODE_TICKET), "rand_read_kernel<")):
         got = read(**kw)
         assert got.checksum == want, name
+        assert rl.last_kernel().startswith(kernel), (name, rl.last_kernel())
         rates[name] = W * I * 128 / got.kernel_ms_event / 1e6
-    assert "rand_read_kernel" in rl.last_kernel()
     n_win = R // (8 * GiB)
     zm = rl.detect_zones(whole, n_win)
     assert len(zm) == n_win and max(zm) < 16
     for name, kw in (("zone order", {}), ("zone order, descending", dict(zone_descending=True)),
+                     ("zone order, XCD halves split", dict(xcd_split=rl.SPLIT_ON)),
+                     ("zone order, XCD halves split, descending", dict(xcd_split=rl.SPLIT_ON, zone_descending=True)),
                      ("zone order, ticketed, descending", dict(zone_descending=True, mode=rl.MODE_TICKET))):
         got = read(zone_of_window=zm, **kw)
         assert got.checksum == want, name
@@ -111,6 +118,11 @@ def test_every_scheme_over_the_whole_allocation(whole):
 ])
 def test_zone_direction_does_not_change_the_checksum(whole, R, B, lanes, W, I, zone):
     want = orc.checksum(R, B, W, I, wl.FILL_SEED, wl.READ_SEED, n_threads=ORACLE_THREADS)
+    if W * lanes % 64 == 0 and I % 64 == 0 and R > zone:   # what the zone stream kernel takes: also split between the XCD halves
+        for down in (False, True):
+            got = rl.rand_read(whole, B, W * I, I, wl.READ_SEED, lanes_per_line=lanes, region_bytes=R, zone_bytes=zone,
+                               zone_descending=down, xcd_split=rl.SPLIT_ON)
+            assert got.checksum == want, ("split", down)
     for mode in (rl.MODE_AUTO, rl.MODE_TICKET, rl.MODE_FLAT):
         for down in (False, True):
             got = rl.rand_read(whole, B, W * I, I, wl.READ_SEED, lanes_per_line=lanes, region_bytes=R, zone_bytes=zone,

@@ -106,6 +106,10 @@ FAKE = (1 << 21, 1 << 20)  # an aligned, non-null "device pointer" that is never
     ((FAKE, 128, 8, 8, 7), {"zone_of_window": [0, 16]}, "below 16"),
     ((FAKE, 128, 8, 8, 7), {"zone_of_window": [0] * 65}, "n_zone_windows"),
     ((FAKE, 128, 8, 8, 7), {"zone_of_window": [0, 1], "zone_descending": 2}, "zone_descending"),
+    ((FAKE, 128, 8, 8, 7), {"xcd_split": 3}, "xcd_split"),
+    ((FAKE, 128, 8, 8, 7), {"xcd_split": 1}, "xcd_split"),                       # 8 reads per wave: no chunks of 64
+    ((FAKE, 128, 128, 64, 7), {"xcd_split": 1, "mode": 2}, "xcd_split"),
+    (((1 << 21, 128), 128, 128, 64, 7), {"xcd_split": 1}, "2 to 64 zone windows"),  # a single line
     ((FAKE, 128, 8, 8, 7), {"zone_descending": True}, "zone_descending needs"),
     (((1 << 21, 3 << 20), 128, 8, 8, 7), {"zone_of_window": [0, 1]}, "power-of-two"),
 ])
