@@ -231,6 +231,9 @@ int rr_fill(void *region, uint64_t region_bytes, uint64_t fill_seed, void *hip_s
  *   opts            NULL = defaults
  *   out             host; filled on success
  * Throughput in the paper's sense is n_reads * line_bytes / kernel time.
+ * A region of more than 256 GiB read without a window map is, by default, divided
+ * between the two halves of the XCDs (RR_SPLIT_*); rr_last_kernel() then names the
+ * zone stream kernel.
  */
 int rr_rand_read(const void *region, uint64_t region_bytes, uint32_t line_bytes,
                  uint32_t lanes_per_line, uint64_t n_reads, uint32_t iters_per_wave,
