@@ -109,6 +109,22 @@ def test_every_scheme_over_the_whole_allocation(whole):
     print(f"\n[{R // GiB} GiB, zones {zm}; one launch each, nothing warmed up] " + ", ".join(f"{k}: {v:.0f} GB/s" for k, v in rates.items()), flush=True)
 
 
+def test_other_entry_points_over_the_whole_allocation(whole):
+    """The entry point that allocates nothing and the batched one take the same path over more than 256 GiB (the region
+    divided between the XCD halves) and return the same checksums."""
+    R = whole.numel()
+    n = len(rl.enumerate_cus())
+    W, I = wl.resident_logical_waves(n) // 4, 1024
+    want = oracle(R, 128, W, I)
+    assert rl.rand_read(whole, 128, W * I, I, wl.READ_SEED).checksum == want
+    got = rl.rand_read_noalloc(whole, 128, W * I, I, wl.READ_SEED)
+    assert got.checksum == want and rl.last_kernel().startswith("rand_read_zone_stream_kernel<")
+    half = (R // (2 * GiB)) * GiB
+    items = [(R, wl.READ_SEED), (half, wl.READ_SEED), (R, wl.READ_SEED, dict(xcd_split=rl.SPLIT_OFF))]
+    res = rl.rand_read_batch(whole, items, 128, W * I, I)
+    assert [r.checksum for r in res] == [want, oracle(half, 128, W, I), want]
+
+
 @pytest.mark.parametrize("R,B,lanes,W,I,zone", [
     (3 << 24, 128, 32, 301, 1100, 1 << 24),         # odd wave count: the ticketed zone kernel
     (3 << 24, 256, 32, 64, 1024, 5 << 22),          # the zone stream kernel, uneven zones
