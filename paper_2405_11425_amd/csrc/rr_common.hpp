@@ -70,6 +70,9 @@ struct Reducer {
     u32 pow2;
 };
 
+// A kernel as the host launches it (the address of its host-side stub).
+typedef const void *kernel_handle;
+
 // Everything a read kernel needs, passed by value.
 struct ReadParams {
     const char *region;       // device base, aligned to the line size

@@ -1,0 +1,51 @@
+// What rr_plan.hip offers the entry points: the validated description of a read call, its lookup tables and its launch.
+#pragma once
+#include "rr_host.hpp"
+
+namespace rr {
+
+// The ticketed and flat read kernels of one line shape.
+struct Family {
+    u32 lanes, wdw;
+    kernel_handle (*find)(u32, u32, u32);
+    u32 default_unroll;
+};
+
+// Validated description of one read call.
+struct Plan {
+    u64 n_lines = 0, W = 0, first_wave = 0;
+    u32 log2_line = 0, lanes = 0, wdw = 0, G = 1, n_windows = 1;
+    u32 block = 256, unroll = 0, bcast = RR_BCAST_DPP, nt = 1, mode = RR_MODE_AUTO, grid_blocks = 0;
+    u32 chunk_iters = 0;
+    u32 n_zones = 0;     // > 0: zone-phased kernel
+    u32 zone_shift = 0;
+    u64 zone_mask[16] = {};
+    bool pinned = false;
+    u32 split = RR_SPLIT_OFF;     // RR_SPLIT_ON: asked for (fail if the launch cannot do it); RR_SPLIT_DEFAULT: do it if the launch can
+    u64 split_incl[2] = {0, 0};   // windows that the two halves of the XCDs may read
+    const Family *family = nullptr;
+    kernel_handle kernel = nullptr;
+};
+
+// One launch of a read kernel, ready to go: parameters, kernel, grid.
+struct Launch {
+    ReadParams p;
+    kernel_handle kernel = nullptr;
+    u32 grid = 0;
+    u32 tickets_per_unit = 0;
+    u32 reset_bits = 0;  // what reset_kernel has to clear first, the result cells aside
+};
+
+// Name of the kernel the calling thread's last read call launched (rr_last_kernel).
+extern thread_local char g_last_kernel[96];
+
+// Device-independent checks (everything that can be rejected without HIP) and the choice of kernel.
+int make_plan(const void *region, uint64_t region_bytes, uint32_t line_bytes, uint32_t lanes, uint64_t n_reads,
+              uint32_t iters, const rr_window_map_t *wm, const rr_launch_opts_t *opts, const void *out, Plan &pl);
+// Lookup tables of one call, uploaded only if they differ from what the device already holds.
+int prepare_tables(DeviceState &st, const Plan &pl, const rr_window_map_t *wm, u64 units, u64 L_win, hipStream_t stream);
+// Kernel, grid and parameters of one launch of a planned call.
+int make_launch(const Plan &pl, DeviceState &st, const void *region, uint32_t iters, const rr_window_map_t *wm,
+                uint64_t read_seed, const rr_launch_opts_t *opts, u16 *placement, Launch &ln);
+
+}  // namespace rr

@@ -410,7 +410,6 @@ __global__ void __launch_bounds__(256) rand_read_stream_kernel(const ReadParams 
 // Each (LANES, WDW) family lives in its own translation unit and exposes a
 // finder that returns the kernel's host-side handle for (unroll, bcast,
 // nontemporal), or null if that combination is not built.
-typedef const void *kernel_handle;
 kernel_handle find_read_kernel_32_1(u32 unroll, u32 bcast, u32 nt);
 kernel_handle find_read_kernel_32_2(u32 unroll, u32 bcast, u32 nt);
 kernel_handle find_read_kernel_32_4(u32 unroll, u32 bcast, u32 nt);
