@@ -516,6 +516,28 @@ int rr_detect_zones(const void *region, uint64_t region_bytes, uint32_t n_window
 /* Release the per-GPU scratch and cached CU tables.  Safe to call when nothing was created. */
 int rr_shutdown(void);
 
+/*
+ * What rr_rand_read would do with these arguments, without doing it: the same checks in the same order (RR_EINVAL
+ * with the same messages), then the plan instead of a launch.  Needs no device and touches none, so everything
+ * that depends on the device -- the grid, whether a planned division between the XCD halves fits it -- is left open.
+ */
+typedef struct {
+    uint32_t mode;              /* RR_MODE_FLAT, _TICKET or _STREAM: what RR_MODE_AUTO resolved to                    */
+    uint32_t zone_kernel;       /* 1: one of the zone-phased kernels (a zone map was given, or the region is
+                                   larger than 256 GiB and is read as a single zone of windows)                       */
+    uint32_t n_zones;           /* 0 if zone_kernel is 0                                                              */
+    uint32_t n_zone_windows;    /* windows the region is cut into for the zone masks (the last one may be shorter)    */
+    uint64_t zone_window_bytes; /* a power of two times line_bytes                                                    */
+    uint64_t zone_windows[16];  /* bit v of entry z: window v is read in phase z                                      */
+    uint32_t xcd_split;         /* 1: the launch divides the region between the halves of the XCDs if its grid allows */
+    uint32_t chunk_iters;       /* iterations per ticket / hardware wave                                              */
+    uint64_t split_windows[2];  /* bit v of entry h: half h of the XCDs may read window v                             */
+    uint32_t block_threads, unroll, bcast, nontemporal; /* as resolved from the defaults                             */
+} rr_read_plan_t;
+int rr_describe_read(const void *region, uint64_t region_bytes, uint32_t line_bytes, uint32_t lanes_per_line,
+                     uint64_t n_reads, uint32_t iters_per_wave, const rr_window_map_t *wm,
+                     const rr_launch_opts_t *opts, rr_read_plan_t *out);
+
 /* Name (with template arguments) of the read kernel that the calling thread's most recent rr_rand_read,
    rr_rand_read_noalloc, rr_rand_read_batch (its last item) or probe call chose -- the name a kernel trace
    shows; "" before the first such call. */

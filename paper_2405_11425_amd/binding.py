@@ -57,6 +57,13 @@ class _Opts(C.Structure):
                 ("cu_waves_out", C.POINTER(C.c_uint32))]
 
 
+class _ReadPlan(C.Structure):
+    _fields_ = [("mode", C.c_uint32), ("zone_kernel", C.c_uint32), ("n_zones", C.c_uint32), ("n_zone_windows", C.c_uint32),
+                ("zone_window_bytes", C.c_uint64), ("zone_windows", C.c_uint64 * 16), ("xcd_split", C.c_uint32),
+                ("chunk_iters", C.c_uint32), ("split_windows", C.c_uint64 * 2), ("block_threads", C.c_uint32),
+                ("unroll", C.c_uint32), ("bcast", C.c_uint32), ("nontemporal", C.c_uint32)]
+
+
 class _ZoneProbeOpts(C.Structure):
     _fields_ = [("min_gap", C.c_double), ("max_zones", C.c_uint32), ("launches", C.c_uint32),
                 ("iters_per_wave", C.c_uint32), ("warmup", C.c_uint32), ("unroll", C.c_uint32),
@@ -80,7 +87,7 @@ class _ReadItem(C.Structure):
 
 EXPORTS = ["rr_enumerate_cus", "rr_fill", "rr_rand_read", "rr_rand_read_noalloc", "rr_rand_read_batch", "rr_probe_pair", "rr_probe_cus", "rr_seq_read", "rr_copy", "rr_chase", "rr_chase_on_cu", "rr_rand_update",
            "rr_region_granularity", "rr_region_create", "rr_region_destroy",
-           "rr_groups_from_heatmap", "rr_zones_from_pair_rates", "rr_detect_zones", "rr_shutdown", "rr_strerror", "rr_last_error", "rr_last_kernel"]
+           "rr_groups_from_heatmap", "rr_zones_from_pair_rates", "rr_detect_zones", "rr_shutdown", "rr_strerror", "rr_last_error", "rr_last_kernel", "rr_describe_read"]
 
 _lib = None
 
@@ -154,6 +161,9 @@ def lib():
         L.rr_last_error.argtypes = []
         L.rr_last_kernel.restype = C.c_char_p
         L.rr_last_kernel.argtypes = []
+        L.rr_describe_read.restype = C.c_int
+        L.rr_describe_read.argtypes = [vp, u64, u32, u32, u64, u32, C.POINTER(_WindowMap), C.POINTER(_Opts),
+                                       C.POINTER(_ReadPlan)]
         _lib = L
     return _lib
 
@@ -509,6 +519,21 @@ def detect_zones(region, n_windows: int = 32, region_bytes: Optional[int] = None
     if details is not None:
         details.update(_zone_details(d, n_windows))
     return [int(z) for z in zone[:n_windows]]
+
+
+def describe_read(region, line_bytes: int, n_reads: int, iters_per_wave: int, window_map: Optional[WindowMap] = None,
+                  lanes_per_line: int = 32, region_bytes: Optional[int] = None, **launch) -> dict:
+    """What rand_read would do with these arguments (see rr_describe_read); needs no device."""
+    ptr, nbytes = _region(region, region_bytes)
+    o, _, _ = _opts(0, 1024, **launch)
+    wm = window_map._c() if window_map is not None else None
+    d = _ReadPlan()
+    _check(lib().rr_describe_read(ptr, nbytes, line_bytes, lanes_per_line, n_reads, iters_per_wave,
+                                  C.byref(wm) if wm is not None else None, C.byref(o), C.byref(d)))
+    out = {name: getattr(d, name) for name, _ in _ReadPlan._fields_}
+    out["zone_windows"] = [int(x) for x in d.zone_windows][:max(d.n_zones, 0)]
+    out["split_windows"] = [int(x) for x in d.split_windows]
+    return out
 
 
 def last_kernel() -> str:

@@ -326,6 +326,35 @@ extern "C" int rr_detect_zones(const void *region, uint64_t region_bytes, uint32
 
 extern "C" const char *rr_last_kernel(void) { return g_last_kernel; }
 
+extern "C" int rr_describe_read(const void *region, uint64_t region_bytes, uint32_t line_bytes, uint32_t lanes_per_line,
+                                uint64_t n_reads, uint32_t iters_per_wave, const rr_window_map_t *wm,
+                                const rr_launch_opts_t *opts, rr_read_plan_t *out) {
+    Plan pl;
+    const int rc = make_plan(region, region_bytes, line_bytes, lanes_per_line, n_reads, iters_per_wave, wm, opts, out, pl);
+    if (rc != RR_OK) return rc;
+    rr_read_plan_t d;
+    memset(&d, 0, sizeof d);
+    d.mode = pl.mode;
+    d.zone_kernel = pl.n_zones ? 1u : 0u;
+    d.n_zones = pl.n_zones;
+    if (pl.n_zones) {
+        d.n_zone_windows = (u32)((pl.n_lines + ((u64)1 << pl.zone_shift) - 1) >> pl.zone_shift);
+        d.zone_window_bytes = ((u64)1 << pl.zone_shift) * line_bytes;
+        memcpy(d.zone_windows, pl.zone_mask, sizeof d.zone_windows);
+    }
+    d.xcd_split = pl.split != RR_SPLIT_OFF ? 1u : 0u;
+    d.split_windows[0] = pl.split_incl[0];
+    d.split_windows[1] = pl.split_incl[1];
+    d.chunk_iters = pl.mode == RR_MODE_STREAM ? pl.chunk_iters : pl.n_zones ? kPhaseChunk : pl.chunk_iters ? pl.chunk_iters : pl.mode == RR_MODE_TICKET ? 1024u : iters_per_wave;
+    if (d.chunk_iters > iters_per_wave) d.chunk_iters = iters_per_wave;
+    d.block_threads = pl.block;
+    d.unroll = pl.n_zones ? (pl.mode == RR_MODE_STREAM ? (pl.wdw == 4 ? 8u : 16u) : 32u / pl.wdw) : pl.unroll;
+    d.bcast = pl.bcast;
+    d.nontemporal = pl.nt ? RR_NT_ON : RR_NT_OFF;
+    *out = d;
+    return RR_OK;
+}
+
 extern "C" int rr_rand_read(const void *region, uint64_t region_bytes, uint32_t line_bytes,
                             uint32_t lanes_per_line, uint64_t n_reads, uint32_t iters_per_wave,
                             const rr_window_map_t *wm, uint64_t read_seed, void *hip_stream,

@@ -42,7 +42,7 @@ def test_header_is_plain_c(tmp_path):
     b = rl.binding
     mirrors = {"rr_launch_opts_t": b._Opts, "rr_result_t": b._Result, "rr_window_map_t": b._WindowMap,
                "rr_chase_result_t": b._ChaseResult, "rr_read_item_t": b._ReadItem,
-               "rr_zone_probe_opts_t": b._ZoneProbeOpts, "rr_zone_probe_t": b._ZoneProbe}
+               "rr_zone_probe_opts_t": b._ZoneProbeOpts, "rr_zone_probe_t": b._ZoneProbe, "rr_read_plan_t": b._ReadPlan}
     prints = []
     for cname, mirror in mirrors.items():
         prints.append(f'printf("%zu\\n", sizeof({cname}));')
@@ -61,6 +61,57 @@ def test_header_is_plain_c(tmp_path):
         want.append(C.sizeof(mirror))
         want += [getattr(mirror, field).offset for field, _ in mirror._fields_]
     assert got == want
+
+
+def test_plans_of_reads_beyond_the_translation_reach():
+    """rr_describe_read: what a call would do, from the host alone.  Over more than 256 GiB a plain read becomes one zone
+    of at most 64 power-of-two windows, divided between the two halves of the XCDs so that of every pair of windows
+    256 GiB apart each half may read at most one; every window stays readable by somebody; windows without a partner
+    256 GiB away by both."""
+    GiB = 1 << 30
+    plan = lambda gib, B=128, **kw: rl.describe_read((1 << 21, gib * GiB), B, 16384 * 4096, 4096, **kw)
+    for gib in (1, 64, 255, 256):
+        d = plan(gib)
+        assert (d["mode"], d["zone_kernel"], d["xcd_split"]) == (rl.MODE_STREAM, 0, 0), gib
+    for gib in list(range(257, 300)) + [320, 384, 448, 511, 512]:
+        for B in (128, 512):
+            d = plan(gib, B)
+            n, w = d["n_zone_windows"], d["zone_window_bytes"]
+            assert (d["mode"], d["zone_kernel"], d["n_zones"], d["xcd_split"]) == (rl.MODE_STREAM, 1, 1, 1), gib
+            assert w & (w - 1) == 0 and n <= 64 and (n - 1) * w < gib * GiB <= n * w
+            assert 64 * (w // 2) < gib * GiB                                                    # the smallest such window
+            all_windows = (1 << n) - 1
+            assert d["zone_windows"] == [all_windows]
+            lo, hi = d["split_windows"]
+            reach = (256 * GiB) // w
+            assert lo | hi == all_windows
+            for k in range(n):
+                partner = k + reach
+                if partner < n:
+                    for half in (lo, hi):
+                        assert not ((half >> k) & 1 and (half >> partner) & 1), (gib, k)     # never both
+                    assert ((lo >> k) & 1) != ((hi >> k) & 1) and ((lo >> partner) & 1) != ((hi >> partner) & 1)
+                elif k - reach < 0:
+                    assert (lo >> k) & 1 and (hi >> k) & 1, (gib, k)                          # nobody displaces it
+            left_out = [bin(all_windows & ~half).count("1") for half in (lo, hi)]
+            assert abs(left_out[0] - left_out[1]) <= 1 and sum(left_out) == 2 * max(0, n - reach)
+    # switched off; asked for in vain; asked for on a small region (7/8 of it in place of 256 GiB); with a zone map
+    assert plan(280, xcd_split=rl.SPLIT_OFF)["zone_kernel"] == 0
+    assert plan(280, mode=rl.MODE_FLAT)["zone_kernel"] == 0 and plan(280, mode=rl.MODE_TICKET)["xcd_split"] == 0
+    d = rl.describe_read((1 << 21, 280 * GiB), 128, 16384 * 100, 100)              # 100 reads per wave: no chunks of 64
+    assert (d["zone_kernel"], d["xcd_split"], d["mode"]) == (0, 0, rl.MODE_FLAT)
+    d = plan(1, xcd_split=rl.SPLIT_ON)
+    assert d["xcd_split"] == 1 and d["n_zone_windows"] == 64 and bin(d["split_windows"][0]).count("1") == 56
+    zm = [0] * 12 + [1] * 12 + [2] * 11
+    d = plan(280, zone_of_window=zm)
+    assert (d["n_zones"], d["xcd_split"], d["n_zone_windows"]) == (3, 0, 35)
+    assert d["zone_windows"] == [0xFFF, 0xFFF000, 0x7FF000000]
+    assert plan(280, zone_of_window=zm, zone_descending=True)["zone_windows"] == [0x7FF000000, 0xFFF000, 0xFFF]
+    d = plan(280, zone_of_window=zm, xcd_split=rl.SPLIT_ON)
+    assert d["xcd_split"] == 1 and d["split_windows"] == plan(280)["split_windows"]
+    with pytest.raises(rl.RandlineError) as e:       # the same checks as the call itself
+        rl.describe_read((0, GiB), 128, 64, 64)
+    assert e.value.code == rl.RR_EINVAL and "NULL" in str(e.value)
 
 
 def test_bench_refuses_more_than_one_gpu():
