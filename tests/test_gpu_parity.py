@@ -634,6 +634,13 @@ def test_stream_kernels_on_seeded_random_shapes(region):
                            chunk_iters=chunk, grid_blocks=grid, first_wave=first, **kw)
         want = oracle(R, B, W, I, read_seed=seed, first_wave=first)
         assert got.checksum == want, (case, B, lanes, R, W, I, chunk, grid, first, kw)
+        if zoned:   # the same in descending zone order, and divided between the XCD halves where the grid allows it
+            kw["zone_descending"] = True
+            if grid % 8 == 0:
+                kw["xcd_split"] = rl.SPLIT_ON
+            got = rl.rand_read(region, B, W * I, I, seed, lanes_per_line=lanes, region_bytes=R, mode=rl.MODE_STREAM,
+                               chunk_iters=chunk, grid_blocks=grid, first_wave=first, **kw)
+            assert got.checksum == want, (case, B, lanes, R, W, I, chunk, grid, first, kw)
 
 
 def test_zone_map_with_scattered_zones(region):
