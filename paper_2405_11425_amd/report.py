@@ -27,6 +27,31 @@ def gib(x):
     return f"{x:g} GiB"
 
 
+def find_knee(sizes, rates, drop=0.05):
+    """Where a throughput curve leaves its plateau (paper Sec. 2.1, Fig. 1: flat, then a cliff once the region outgrows
+    the translation reach).  Points in order of size; the plateau at a point is the median rate of all smaller points.
+    Returns (size of the first point that lies more than `drop` below its plateau and is not followed by a recovery
+    to within `drop` of it, that plateau), or (None, median of all points) for a curve that stays flat."""
+    pts = sorted(zip(sizes, rates))
+    for i in range(1, len(pts)):
+        before = sorted(r for _, r in pts[:i])
+        plateau = before[len(before) // 2] if len(before) % 2 else 0.5 * (before[len(before) // 2 - 1] + before[len(before) // 2])
+        if pts[i][1] < (1.0 - drop) * plateau and all(r < (1.0 - drop) * plateau for _, r in pts[i:]):
+            return pts[i][0], plateau
+    allr = sorted(r for _, r in pts)
+    return None, (allr[len(allr) // 2] if len(allr) % 2 else 0.5 * (allr[len(allr) // 2 - 1] + allr[len(allr) // 2]))
+
+
+def knee_sentence(name, sizes, rates, drop):
+    knee, plateau = find_knee(sizes, rates, drop)
+    if knee is None:
+        low = min(rates)
+        return (f"{name}: no knee up to {gib(max(sizes))} (nowhere does the curve fall for good more than {drop * 100:g} % below the "
+                f"median of the smaller regions; lowest point {low:.0f} GB/s, {(1 - low / plateau) * 100:.1f} % below the median {plateau:.0f} "
+                "of all).")
+    return f"{name}: knee at {gib(knee)} (this region and all larger ones more than {drop * 100:g} % below the {plateau:.0f} GB/s of the smaller ones)."
+
+
 def report(rows):
     by = collections.defaultdict(list)
     for r in rows:
@@ -57,6 +82,13 @@ def report(rows):
                 row.append(f"{v:.0f} ({pct(v)})" if v else "")
             body.append(row)
         out.append(table(["region"] + [c[2] for c in cols], body))
+        for scheme, size, label in cols[:2]:
+            pts = [(s, cell[(scheme, size, s)]) for s in sizes if (scheme, size, s) in cell]
+            if scheme == "uniform, zone by zone":   # below several zones the zone order is the plain order
+                pts = [(s, cell.get((scheme, size, s), cell.get(("uniform", size, s)))) for s in sizes]
+                pts = [p for p in pts if p[1]]
+            if len(pts) >= 3:
+                out.append(knee_sentence(f"Knee of the curve ({label})", [p[0] for p in pts], [p[1] for p in pts], 0.1) + "\n")
 
     if by["lines"]:
         out.append("## Line width (2^30 reads per launch)\n")
@@ -166,6 +198,10 @@ def report(rows):
         body = [[sch + (", 16x longer launches" if size == "16x" else "")]
                 + [f"{cell[(sch, size, g)]:.0f}" if (sch, size, g) in cell else "" for g in sizes] for sch, size in schemes]
         out.append(table(["scheme"] + [gib(g) for g in sizes], body))
+        for sch, size in schemes:
+            pts = [(g, cell[(sch, size, g)]) for g in sizes if (sch, size, g) in cell]
+            if size == "1x" and len(pts) >= 3:
+                out.append(knee_sentence(f"`{sch}`", [p[0] for p in pts], [p[1] for p in pts], 0.05) + "\n")
         if by["beyond-latency"]:
             out.append("Dependent-load walk pinned to CU 0, footprint = the region (ns per hop): "
                        + ", ".join(f"{r['footprint_mib'] / 1024:g} GiB: {r['ns_per_hop']:.0f}" for r in by["beyond-latency"]) + ".\n")

@@ -399,6 +399,28 @@ def test_report_renders_every_kind_of_row():
     assert "Line width" not in report.report(rows[:1])
 
 
+def test_knee_finder_on_synthetic_curves():
+    """The knee of a throughput-vs-size curve (paper Sec. 2.1, Fig. 1: flat up to the translation reach, then a cliff)."""
+    from paper_2405_11425_amd.report import find_knee, knee_sentence
+    sizes = [1, 2, 4, 8, 16, 32, 64, 128, 192, 256]
+    flat = [6950, 6960, 6940, 6930, 6945, 6935, 6925, 6600, 6610, 6250]            # two steps of 4-5 %: no cliff at 10 %
+    assert find_knee(sizes, flat, 0.10) == (None, 6932.5)
+    assert find_knee(sizes, flat, 0.03)[0] == 128                                   # ... but a knee at 3 %
+    a100 = [1400, 1405, 1398, 1402, 1400, 1399, 1401, 600, 420, 380]               # the paper's picture: collapse above 64
+    assert find_knee(sizes, a100, 0.10) == (128, 1400)
+    assert find_knee(sizes[::-1], a100[::-1], 0.10) == (128, 1400)                  # order of the points does not matter
+    dip = [1400, 1400, 1400, 1100, 1400, 1400, 1400, 1400, 1400, 1400]             # one bad point that recovers: no knee
+    assert find_knee(sizes, dip, 0.10)[0] is None
+    late = [100.0] * 9 + [94.9]
+    assert find_knee(sizes, late, 0.05) == (256, 100.0) and find_knee(sizes, late, 0.06)[0] is None
+    rng = np.random.default_rng(5)
+    for knee_at in range(2, 10):                                                    # noisy plateau (1 %), then a drop of 30 %
+        curve = [1000 * (1 + 0.01 * rng.standard_normal()) * (0.7 if i >= knee_at else 1.0) for i in range(10)]
+        assert find_knee(sizes, curve, 0.10)[0] == sizes[knee_at]
+    assert find_knee([1, 2], [5.0, 1.0], 0.1) == (2, 5.0) and find_knee([1], [5.0], 0.1) == (None, 5.0)
+    assert "no knee up to 256 GiB" in knee_sentence("x", sizes, flat, 0.1) and "knee at 128 GiB" in knee_sentence("x", sizes, a100, 0.1)
+
+
 def test_region_create_validation():
     """Argument checks of the piecewise region come before any HIP call."""
     for args, needle in (((0, 4096), "multiple of piece_bytes"), ((8192, 0), "multiple of piece_bytes"),
