@@ -286,6 +286,14 @@ def main():
                                        "achieved": round(bytes_per_launch / avg_all / 1e6, 1),
                                        "frac": round(bytes_per_launch / avg_all / 1e6 / HBM_PEAK_GBPS, 4)}}
 
+    # the knee of the paper's Fig. 1: the first region from which the curve stays more than 10 % below the median of the
+    # smaller regions (None: flat)
+    from paper_2405_11425_amd.report import find_knee
+    knee_at, plateau = find_knee([c["region_gib"] for c in curve], [c["gbps"] for c in curve], 0.10)
+    knee = {"rule": "first region from which the curve stays more than 10 % below the median of the smaller regions",
+            "region_gib": knee_at, "median_gbps": round(plateau, 1),
+            "lowest_point_pct_below_median": round((1 - min(c["gbps"] for c in curve) / plateau) * 100, 2)}
+
     out = {
         "metric": "random-line read GB/s vs region size (1-256 GiB); % of 8 TB/s HBM peak",
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -311,6 +319,7 @@ def main():
         "curve": curve,
         "environment": env,
         "gbps_at_largest_region": curve[-1]["gbps"],
+        "knee_of_curve": knee,
         "fill_gbps": round(alloc_gib * GiB / fill_s / 1e9, 1),
         "roofline": roofline,
         # context: the same launches as one wavefront per pair of logical waves, every wave slot occupied
