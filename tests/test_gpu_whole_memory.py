@@ -109,6 +109,34 @@ def test_every_scheme_over_the_whole_allocation(whole):
     print(f"\n[{R // GiB} GiB, zones {zm}; one launch each, nothing warmed up] " + ", ".join(f"{k}: {v:.0f} GB/s" for k, v in rates.items()), flush=True)
 
 
+def test_shapes_of_the_papers_figures_beyond_the_reach(whole):
+    """The qualitative shapes of the paper's Fig. 1 and Fig. 5 where this GPU shows them, with wide margins (measured:
+    factors of 1.3-1.55): over more than the second-level translation reach, windows per resource group keep the rate
+    that windows drawn per CU lose (Sec. 2.4 against Sec. 2.1), and so does the library's division of a plain read."""
+    R = whole.numel()
+    if R < 272 * GiB:
+        pytest.skip("the effect is measured on an allocation of 272 GiB or more")
+    import statistics
+    cus = rl.enumerate_cus()
+    n = len(cus)
+    W, I = wl.resident_logical_waves(n), wl.ITERS_PER_WAVE
+
+    def rate(wm=None, **kw):
+        for i in range(3):
+            rl.rand_read(whole, 128, W * I, I, 100 + i, wm, **kw)
+        ms = statistics.median(rl.rand_read(whole, 128, W * I, I, wl.READ_SEED + i, wm, **kw).kernel_ms_event for i in range(5))
+        return W * I * 128 / ms / 1e6
+    rate()                                                       # clocks up
+    xcd = rate(rl.WindowMap(8, *wl.window_map_by_xcd(cus, 8)))
+    per_cu = rate(rl.WindowMap(8, *wl.window_map_random_per_cu(n, 8, seed=8)))
+    divided, undivided = rate(), rate(xcd_split=rl.SPLIT_OFF)
+    print(f"\n[{R // GiB} GiB] one window of 8 per XCD {xcd:.0f}, drawn per CU {per_cu:.0f}; plain read divided {divided:.0f}, "
+          f"undivided {undivided:.0f} GB/s", flush=True)
+    assert xcd > 1.15 * per_cu
+    assert divided > 1.15 * undivided
+    assert abs(xcd - divided) < 0.1 * xcd                        # the division reaches the rate of the windows
+
+
 def test_other_entry_points_over_the_whole_allocation(whole):
     """The entry point that allocates nothing and the batched one take the same path over more than 256 GiB (the region
     divided between the XCD halves) and return the same checksums."""
