@@ -794,6 +794,52 @@ def test_probe_single_cu_and_group(region, cu_table):
     assert res.checksum == want and set(res.placement.tolist()) <= set(xcd0)
 
 
+def test_groups_scale_and_are_independent(region, cu_table):
+    """The shapes of the paper's Sec. 2.3 with this GPU's groups, with wide margins: compute units inside one XCD add up
+    (1, 2, 4 CUs of different shader engines: 54, 108, 215 GB/s measured), and two XCDs reading disjoint halves of a
+    region together reach the sum of what each reaches alone (measured 0.98-1.01).  Checksums against the oracle."""
+    import statistics
+    need(region, 80)
+    n = len(cu_table)
+    xcc = cu_table[:, 0]
+    I = 1024
+
+    def pinned(group_of_cu, window_of_group, n_windows, R, W):
+        wm = rl.WindowMap(n_windows, group_of_cu, window_of_group)
+        want = oracle(R, 128, W, I, n_windows=n_windows, window_of_group=window_of_group)
+        rl.rand_read(region, 128, W * I, I, 99, wm, region_bytes=R)
+        res = [rl.rand_read(region, 128, W * I, I, wl.READ_SEED, wm, region_bytes=R) for _ in range(3)]
+        assert all(r.checksum == want for r in res)
+        return W * I * 128 / statistics.median(r.kernel_ms_device for r in res) / 1e6
+
+    # k CUs of XCD 0, one per shader engine (CUs of one shader engine share a path: four of them reach 215 GB/s, eight 320)
+    ids0 = np.flatnonzero(xcc == xcc[0])
+    by_se = [int(ids0[np.flatnonzero(cu_table[ids0, 1] == se)[0]]) for se in sorted(set(cu_table[ids0, 1].tolist()))]
+    rates = {}
+    for k in (1, 2, 4):
+        if k > len(by_se):
+            continue
+        g = np.full(n, rl.RR_CU_EXCLUDED, np.uint16)
+        g[by_se[:k]] = 0
+        rates[k] = pinned(g, np.zeros(1, np.uint16), 1, 16 * GiB, 2048 * k)
+    for k in rates:
+        assert 0.8 * k * rates[1] < rates[k] < 1.2 * k * rates[1], rates
+    # two XCDs, each on its own 40 GiB half
+    xs = sorted(set(xcc.tolist()))[:2]
+    R, W = 80 * GiB, 16384
+    alone = []
+    for i, x in enumerate(xs):
+        g = np.full(n, rl.RR_CU_EXCLUDED, np.uint16)
+        g[xcc == x] = 0
+        alone.append(pinned(g, np.array([i], np.uint16), 2, R, W))
+    g = np.full(n, rl.RR_CU_EXCLUDED, np.uint16)
+    g[xcc == xs[0]] = 0
+    g[xcc == xs[1]] = 1
+    both = pinned(g, np.array([0, 1], np.uint16), 2, R, 2 * W)
+    print(f"\n[groups] CUs of one XCD {rates}; XCDs alone {alone[0]:.0f}, {alone[1]:.0f}, together {both:.0f} GB/s", flush=True)
+    assert 0.85 * sum(alone) < both < 1.15 * sum(alone)
+
+
 def test_probe_rejects_bad_targets(region, cu_table):
     n = len(cu_table)
     for cus in ([3, 3], [0, n], []):
