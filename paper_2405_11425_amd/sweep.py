@@ -114,16 +114,17 @@ class Runner:
             with open(self.args.out, "a") as f:
                 f.write(line + "\n")
 
-    def timed_read(self, cfg, wm=None, reps=None, alternate=None, **kw):
-        """Median / min / max over reps (seeds 7, 8, ...) after one warm-up launch.  `alternate`: a list of option
-        sets, launch i takes set i mod len (the warm-up the last one)."""
+    def timed_read(self, cfg, wm=None, reps=None, alternate=None, warmups=1, **kw):
+        """Median / min / max over reps (seeds 7, 8, ...) after `warmups` warm-up launches.  `alternate`: a list of
+        option sets, launch i takes set i mod len (the last warm-up the last one)."""
         reps = reps or self.args.reps
         rl = self.rl
         alt = alternate or [{}]
         call = lambda seed, i: rl.rand_read(self.region, cfg.line_bytes, cfg.n_reads, cfg.iters_per_wave, seed, wm,
                                             lanes_per_line=cfg.lanes_per_line, region_bytes=cfg.region_bytes,
                                             **{**self.launch, **kw, **alt[i % len(alt)]})
-        call(1000, -1)
+        for k in range(warmups):
+            call(1000 + k, k - warmups)
         res = [call(cfg.read_seed + i, i) for i in range(reps)]
         ms = [r.kernel_ms_event for r in res]
         med = statistics.median(ms)
@@ -708,7 +709,10 @@ class Runner:
                     wm = rl.WindowMap(*wmap)
                     row.update(n_windows=wmap[0], window_of_group=wmap[2].tolist())
                 reps = 3 if long else self.args.reps + self.args.reps % 2   # even: both directions equally often
-                self.emit(key, {**row, **self.timed_read(c, wm, reps=reps, **kw), "kernel": rl.last_kernel(), **self.meta})
+                # several warm-up launches: after a change of the region's size the first dozen launches run 1-4 %
+                # slower than the later ones (seen at 258 and 260 GiB)
+                self.emit(key, {**row, **self.timed_read(c, wm, reps=reps, warmups=1 if long else 6, **kw),
+                                "kernel": rl.last_kernel(), **self.meta})
             if self.args.beyond_short:
                 continue
             key = f"beyond-latency/{gib}GiB"

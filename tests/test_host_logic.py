@@ -70,12 +70,12 @@ def test_plans_of_reads_beyond_the_translation_reach():
     256 GiB away by both."""
     GiB = 1 << 30
     plan = lambda gib, B=128, **kw: rl.describe_read((1 << 21, gib * GiB), B, 16384 * 4096, 4096, **kw)
-    for gib in (1, 64, 255, 256):
+    for gib in (1, 64, 255, 256, 257, 260, 263):       # by default only from one whole window beyond 256 GiB on
         d = plan(gib)
         assert (d["mode"], d["zone_kernel"], d["xcd_split"]) == (rl.MODE_STREAM, 0, 0), gib
     for gib in list(range(257, 300)) + [320, 384, 448, 511, 512]:
         for B in (128, 512):
-            d = plan(gib, B)
+            d = plan(gib, B, xcd_split=rl.SPLIT_ON if gib < 264 else rl.SPLIT_DEFAULT)
             n, w = d["n_zone_windows"], d["zone_window_bytes"]
             assert (d["mode"], d["zone_kernel"], d["n_zones"], d["xcd_split"]) == (rl.MODE_STREAM, 1, 1, 1), gib
             assert w & (w - 1) == 0 and n <= 64 and (n - 1) * w < gib * GiB <= n * w
@@ -107,8 +107,8 @@ def test_plans_of_reads_beyond_the_translation_reach():
     assert (d["n_zones"], d["xcd_split"], d["n_zone_windows"]) == (3, 0, 35)
     assert d["zone_windows"] == [0xFFF, 0xFFF000, 0x7FF000000]
     assert plan(280, zone_of_window=zm, zone_descending=True)["zone_windows"] == [0x7FF000000, 0xFFF000, 0xFFF]
-    d = plan(280, zone_of_window=zm, xcd_split=rl.SPLIT_ON)
-    assert d["xcd_split"] == 1 and d["split_windows"] == plan(280)["split_windows"]
+    d = plan(280, zone_of_window=zm, xcd_split=rl.SPLIT_ON)      # several zones: one half gives up the upper windows, the other the lower
+    assert d["xcd_split"] == 1 and d["split_windows"] == [(1 << 32) - 1, ((1 << 35) - 1) & ~0b111]
     with pytest.raises(rl.RandlineError) as e:       # the same checks as the call itself
         rl.describe_read((0, GiB), 128, 64, 64)
     assert e.value.code == rl.RR_EINVAL and "NULL" in str(e.value)
