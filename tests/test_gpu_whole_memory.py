@@ -177,3 +177,29 @@ def test_zone_direction_does_not_change_the_checksum(whole, R, B, lanes, W, I, z
         got = rl.rand_read(whole, B, W * I, I, wl.READ_SEED, lanes_per_line=lanes, region_bytes=R,
                            zone_of_window=[2, 0, 1, 0, 2, 2, 1, 0], zone_descending=True)
         assert got.checksum == want
+
+
+def test_zz_updates_over_the_whole_allocation(whole):
+    """Random line writes and atomic adds over all of the allocation (line indices above 2^31): checksum, and the lines a
+    few logical waves drew read back and compared with the oracle's values.  Runs last in this module and restores the
+    fill."""
+    R, B, W, I = whole.numel(), 128, 1024, 4096
+    idx = orc.indices(R, B, W, I, 11)
+    assert int(idx.max()) > 1 << 31
+    lines, hits = np.unique(idx, return_counts=True)
+    count = dict(zip(lines.tolist(), hits.tolist()))
+    top = int(lines[-1])
+    try:
+        for op in (rl.OP_WRITE, rl.OP_ADD):
+            got = rl.rand_update(whole, B, W * I, I, 11, op, 99)
+            assert got.checksum == orc.update_checksum(R, B, W, I, 11, 99)
+            for line in list(idx[0, :6]) + list(idx[W - 1, -6:]) + [top, int(lines[np.argmax(hits)])]:
+                line = int(line)
+                now = whole[line * B:(line + 1) * B].cpu().numpy().view(np.uint32).astype(np.uint64)
+                old = orc.fill_words(wl.FILL_SEED, line * 32, 32).astype(np.uint64)
+                v = np.array([orc.update_value(99, line * 32 + j) for j in range(32)], dtype=np.uint64)
+                want = v if op == rl.OP_WRITE else (old + count[line] * v) % (1 << 32)
+                assert np.array_equal(now, want), (op, line)
+            rl.fill(whole, wl.FILL_SEED)
+    finally:
+        rl.fill(whole, wl.FILL_SEED)
