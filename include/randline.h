@@ -333,7 +333,8 @@ int rr_probe_cus(const void *region, uint64_t region_bytes, const uint32_t *cus,
  * The final content of the region does not depend on the order of execution.
  * out->checksum = wrapping 64-bit sum of v(i) over all words of all lines hit (repeats count);
  * throughput = n_updates * line_bytes / time (an add moves twice that in DRAM).
- * Arguments as for rr_rand_read; region is written.
+ * Arguments as for rr_rand_read; region is written.  A region of 264 GiB or more is divided
+ * between the two halves of the XCDs like a plain read (RR_SPLIT_DEFAULT): same content, same checksum.
  */
 #define RR_OP_WRITE 1
 #define RR_OP_ADD 2

@@ -556,6 +556,23 @@ extern "C" int rr_rand_update(void *region, uint64_t region_bytes, uint32_t line
     p.log2_line = pl.log2_line;
     p.red = make_reducer(pl.n_lines);
     p.scratch = st->scratch;
+    // A region of more than the second-level translation reach plus one window: divided between the halves of the XCDs
+    // like a plain read (RR_SPLIT_*), the region as up to 64 windows of a power-of-two number of lines.
+    {
+        u32 shift = 0;
+        while ((64ull << shift) < pl.n_lines) shift++;
+        const u64 window_bytes = ((u64)1 << shift) * line_bytes;
+        const u32 n_win = (u32)((pl.n_lines + ((u64)1 << shift) - 1) >> shift);
+        const u32 n_xcds = count_xcds(*st), half = n_xcds / 2;
+        u64 incl[2];
+        if (region_bytes >= kSecondLevelReachBytes + window_bytes && n_xcds % 2 == 0 && (half & (half - 1)) == 0 &&
+            grid % n_xcds == 0 && divide_windows(n_win, (u32)std::min<u64>(64, kSecondLevelReachBytes / window_bytes), true, incl)) {
+            p.split_half = half;
+            p.window_shift = shift;
+            p.split_incl[0] = incl[0];
+            p.split_incl[1] = incl[1];
+        }
+    }
     rc = begin_cells(*st, stream);
     if (rc != RR_OK) return rc;
     void *args[] = {(void *)&p};

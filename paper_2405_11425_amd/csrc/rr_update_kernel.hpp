@@ -9,6 +9,9 @@
 //   write : word i <- v(i)            -- the same value whoever writes it, so repeated hits are harmless
 //   add   : word i <- word i + v(i)   -- one device-scope atomic per word, so concurrent hits all count
 // Checksum: wrapping 64-bit sum of v(i) over all words of all lines hit, repeats included.
+// Over more memory than the second-level translation cache of an XCD covers the launch is divided between the two halves
+// of the XCDs like a read (see rand_read_zone_stream_kernel): every wave goes through its own logical waves and keeps the
+// lines its half may touch, then through those of its partner in the other half and keeps what the partner may not.
 #pragma once
 #include "rr_read_kernel.hpp"
 
@@ -26,6 +29,9 @@ struct UpdateParams {
     u32 log2_line;
     Reducer red;         // L = lines of the region
     Scratch *scratch;
+    u32 split_half;      // 0, or half the number of XCDs: the region is divided between the halves of the XCDs as in the
+    u32 window_shift;    // zone stream read kernel (windows of 2^window_shift lines; half (b / split_half) & 1 of workgroup
+    u64 split_incl[2];   // b may touch the windows in split_incl[half]; the rest of its work workgroup b ^ split_half does)
 };
 
 template <int LANES, int WDW, int OP>
@@ -37,43 +43,57 @@ __global__ void __launch_bounds__(256) rand_update_kernel(const UpdateParams p) 
     const u32 sub = lane & (LANES - 1);
     const u32 itl = lane & (ITB - 1);
     const u32 launch_index = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
-    const u64 j0 = (u64)launch_index * LPW;
-    if (j0 >= p.n_waves) return;
-    const u64 j = j0 + half;
-    const bool valid = j < p.n_waves;  // odd number of logical waves: the upper half stays idle
-    const u64 wave_seed = mix64(p.draw_seed + ((valid ? j : j0) + 1) * kGamma);
     const u32 words_per_line_log2 = p.log2_line - 2;
     const u64 t0 = clock_ticks();
     u64 acc = 0;
-    for (u32 it0 = 0; it0 < p.iters; it0 += ITB) {
-        const u32 mine = reduce_to_line(mix64(wave_seed + ((u64)it0 + itl + 1) * kGamma), p.red);
-        static_for<0, ITB>([&](auto kc) {
-            constexpr int K = decltype(kc)::value;
-            const u32 line = __builtin_amdgcn_update_dpp(0u, mine, 0x150 + K, 0xF, 0xF, true);  // row_newbcast:K
-            if (it0 + K < p.iters && valid) {
-                const u64 first_word = ((u64)line << words_per_line_log2) + sub * WDW;
-                u32 *dst = (u32 *)p.region + first_word;
-                u32 v[WDW];
+    bool worked = false;
+    // the logical waves of hardware wave `li` of the launch, as far as their lines lie in the windows of `keep`
+    auto pass = [&](u32 li, u64 keep) {
+        const u64 j0 = (u64)li * LPW;
+        if (j0 >= p.n_waves) return;
+        worked = true;
+        const u64 j = j0 + half;
+        const bool valid = j < p.n_waves;  // odd number of logical waves: the upper half stays idle
+        const u64 wave_seed = mix64(p.draw_seed + ((valid ? j : j0) + 1) * kGamma);
+        const bool all = keep == ~0ull;
+        for (u32 it0 = 0; it0 < p.iters; it0 += ITB) {
+            const u32 mine = reduce_to_line(mix64(wave_seed + ((u64)it0 + itl + 1) * kGamma), p.red);
+            static_for<0, ITB>([&](auto kc) {
+                constexpr int K = decltype(kc)::value;
+                const u32 line = __builtin_amdgcn_update_dpp(0u, mine, 0x150 + K, 0xF, 0xF, true);  // row_newbcast:K
+                if (it0 + K < p.iters && valid && (all || ((keep >> (line >> p.window_shift)) & 1ull))) {
+                    const u64 first_word = ((u64)line << words_per_line_log2) + sub * WDW;
+                    u32 *dst = (u32 *)p.region + first_word;
+                    u32 v[WDW];
 #pragma unroll
-                for (int q = 0; q < WDW; ++q) {
-                    v[q] = (u32)(p.value_seed + (first_word + q) * kValueMul);
-                    acc += v[q];
-                }
-                if constexpr (OP == OP_WRITE) {
-                    if constexpr (WDW == 1) {
-                        __builtin_nontemporal_store(v[0], dst);
-                    } else if constexpr (WDW == 2) {
-                        __builtin_nontemporal_store(u32x2{v[0], v[1]}, (u32x2 *)dst);
-                    } else {
-                        __builtin_nontemporal_store(u32x4{v[0], v[1], v[2], v[3]}, (u32x4 *)dst);
+                    for (int q = 0; q < WDW; ++q) {
+                        v[q] = (u32)(p.value_seed + (first_word + q) * kValueMul);
+                        acc += v[q];
                     }
-                } else {
+                    if constexpr (OP == OP_WRITE) {
+                        if constexpr (WDW == 1) {
+                            __builtin_nontemporal_store(v[0], dst);
+                        } else if constexpr (WDW == 2) {
+                            __builtin_nontemporal_store(u32x2{v[0], v[1]}, (u32x2 *)dst);
+                        } else {
+                            __builtin_nontemporal_store(u32x4{v[0], v[1], v[2], v[3]}, (u32x4 *)dst);
+                        }
+                    } else {
 #pragma unroll
-                    for (int q = 0; q < WDW; ++q) atomicAdd(dst + q, v[q]);
+                        for (int q = 0; q < WDW; ++q) atomicAdd(dst + q, v[q]);
+                    }
                 }
-            }
-        });
+            });
+        }
+    };
+    if (!p.split_half) {
+        pass(launch_index, ~0ull);
+    } else {  // own logical waves where this half of the XCDs may write, the partner's where the partner's half may not
+        const u32 h = (blockIdx.x / p.split_half) & 1u;
+        pass(launch_index, p.split_incl[h]);
+        pass((blockIdx.x ^ p.split_half) * (blockDim.x >> 6) + (threadIdx.x >> 6), ~p.split_incl[h ^ 1u]);
     }
+    if (!worked) return;
     const u64 total = wave_sum(acc);  // idle lanes hold 0
     const u64 t1 = clock_ticks();
     if (lane == 0) {

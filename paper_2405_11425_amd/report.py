@@ -108,8 +108,9 @@ def report(rows):
 
     if by["updates"]:
         out.append("## Random 128-byte line writes and atomic adds (2^26 lines per launch)\n")
-        body = [[r["op"], gib(r["region_gib"]), f"{r['gbps_lines']:.0f} ({pct(r['gbps_lines'])})"] for r in by["updates"]]
-        out.append(table(["operation", "region", "GB/s of lines"], body))
+        body = [[r["op"], gib(r["region_gib"]), gib(r["allocation_gib"]) if "allocation_gib" in r else "",
+                 f"{r['gbps_lines']:.0f} ({pct(r['gbps_lines'])})"] for r in by["updates"]]
+        out.append(table(["operation", "region", "of an allocation of", "GB/s of lines"], body))
 
     if by["zones"]:
         out.append("## Memory zones (two 8 GiB windows read at a time, all pairs)\n")

@@ -409,21 +409,22 @@ class Runner:
                             "gbps_alone": alone, "gbps_pairs": pairs, "pair_over_sum_of_singles": ratios,
                             "ratio_min": min(ratios.values()), "ratio_max": max(ratios.values()), **self.meta})
 
-    def updates(self):
+    def updates(self, sizes=(1, 16, 64, 128, 192, 256), prefix="updates", warmups=1):
         """Random 128-byte line writes and atomic adds vs region size (the fill is restored afterwards)."""
         rl, wl = self.rl, self.wl
         n = len(self.cus)
         touched = False
-        for gib in sorted({min(g, self.max_gib) for g in (1, 16, 64, 128, 192, 256)}):
+        for gib in sorted({min(g, self.max_gib) for g in sizes}):
             cfg = wl.ReadConfig(f"update-{gib}GiB", gib * wl.GiB, 128, 32, wl.resident_logical_waves(n), wl.ITERS_PER_WAVE)
             for op, name in ((rl.OP_WRITE, "write"), (rl.OP_ADD, "add")):
-                key = f"updates/{name}/{cfg.name}"
+                key = f"{prefix}/{name}/{cfg.name}"
                 if key in self.seen:
                     continue
                 touched = True
                 call = lambda seed: rl.rand_update(self.region, 128, cfg.n_reads, cfg.iters_per_wave, seed, op, 99,
                                                    region_bytes=cfg.region_bytes)
-                call(1000)
+                for k in range(warmups):
+                    call(1000 + k)
                 res = [call(cfg.read_seed + i) for i in range(self.args.reps)]
                 med = statistics.median(r.kernel_ms_event for r in res)
                 self.emit(key, {"experiment": "updates", "op": name, "region_gib": gib, "n_updates": cfg.n_reads,
@@ -748,6 +749,8 @@ class Runner:
                                 "ns_per_hop": round(statistics.median(r.ns_per_hop for r in walks), 1),
                                 "final_line": walks[0].final_line, "word_sum": walks[0].word_sum, **self.meta})
 
+        # writes and atomic adds out here (the same draws; the fill is restored afterwards)
+        self.updates(sizes=(256, 264, 272, self.max_gib), prefix="beyond-updates", warmups=6)
         # What a change of zone costs: launches over [0, 96), [96, 192), [192, top) GiB in a cycle against the same
         # launches with each region repeated, by top and by launch length; and with a small launch over the next
         # region in front of each (does touching its translations ahead help?)

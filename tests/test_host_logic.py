@@ -392,7 +392,7 @@ def test_report_renders_every_kind_of_row():
                    "one line per 128 MiB: 2239 [2239]: 304", "| 280 GiB | 1024 | 317.9 | 381.4 | +63.5 | 379.0 |"):
         assert needle in text, needle
     for needle in ("Throughput vs region size", "| 256 GiB |  | 6700 (83.8 %) |  | 6400 (80.0 %) |", "64 x 4 B = 256 B", "xcd | 8",
-                   "sequential read", "write | 16 GiB", "2 zones", "32 groups of [8] CUs", "1190-1200 GB/s", "| 1 MiB | 155.0 |",
+                   "sequential read", "write | 16 GiB |", "2 zones", "32 groups of [8] CUs", "1190-1200 GB/s", "| 1 MiB | 155.0 |",
                    "| 33 | 200.0 |", "| 512 MiB | 4096 | 280 |", "96: 10", "6: 11.0", "the groups are the XCDs: True",
                    "401, 405 ns per hop", "64: 733", "reach 24 pieces", "| 2 | 6 MiB | 6100 | 900 |"):
         assert needle in text, needle
