@@ -47,7 +47,31 @@ __global__ void __launch_bounds__(256) rand_update_kernel(const UpdateParams p) 
     const u64 t0 = clock_ticks();
     u64 acc = 0;
     bool worked = false;
-    // the logical waves of hardware wave `li` of the launch, as far as their lines lie in the windows of `keep`
+    // this lane's words of `line`: stored, or added to
+    auto touch = [&](u32 line) {
+        const u64 first_word = ((u64)line << words_per_line_log2) + sub * WDW;
+        u32 *dst = (u32 *)p.region + first_word;
+        u32 v[WDW];
+#pragma unroll
+        for (int q = 0; q < WDW; ++q) {
+            v[q] = (u32)(p.value_seed + (first_word + q) * kValueMul);
+            acc += v[q];
+        }
+        if constexpr (OP == OP_WRITE) {
+            if constexpr (WDW == 1) {
+                __builtin_nontemporal_store(v[0], dst);
+            } else if constexpr (WDW == 2) {
+                __builtin_nontemporal_store(u32x2{v[0], v[1]}, (u32x2 *)dst);
+            } else {
+                __builtin_nontemporal_store(u32x4{v[0], v[1], v[2], v[3]}, (u32x4 *)dst);
+            }
+        } else {
+#pragma unroll
+            for (int q = 0; q < WDW; ++q) atomicAdd(dst + q, v[q]);
+        }
+    };
+    // The logical waves of hardware wave `li` of the launch, as far as their lines lie in the windows of `keep` (most
+    // of them): every 16-lane row evaluates a batch of 16 iterations and broadcasts them one by one.
     auto pass = [&](u32 li, u64 keep) {
         const u64 j0 = (u64)li * LPW;
         if (j0 >= p.n_waves) return;
@@ -61,29 +85,37 @@ __global__ void __launch_bounds__(256) rand_update_kernel(const UpdateParams p) 
             static_for<0, ITB>([&](auto kc) {
                 constexpr int K = decltype(kc)::value;
                 const u32 line = __builtin_amdgcn_update_dpp(0u, mine, 0x150 + K, 0xF, 0xF, true);  // row_newbcast:K
-                if (it0 + K < p.iters && valid && (all || ((keep >> (line >> p.window_shift)) & 1ull))) {
-                    const u64 first_word = ((u64)line << words_per_line_log2) + sub * WDW;
-                    u32 *dst = (u32 *)p.region + first_word;
-                    u32 v[WDW];
-#pragma unroll
-                    for (int q = 0; q < WDW; ++q) {
-                        v[q] = (u32)(p.value_seed + (first_word + q) * kValueMul);
-                        acc += v[q];
-                    }
-                    if constexpr (OP == OP_WRITE) {
-                        if constexpr (WDW == 1) {
-                            __builtin_nontemporal_store(v[0], dst);
-                        } else if constexpr (WDW == 2) {
-                            __builtin_nontemporal_store(u32x2{v[0], v[1]}, (u32x2 *)dst);
-                        } else {
-                            __builtin_nontemporal_store(u32x4{v[0], v[1], v[2], v[3]}, (u32x4 *)dst);
-                        }
-                    } else {
-#pragma unroll
-                        for (int q = 0; q < WDW; ++q) atomicAdd(dst + q, v[q]);
-                    }
-                }
+                if (it0 + K < p.iters && valid && (all || ((keep >> (line >> p.window_shift)) & 1ull))) touch(line);
             });
+        }
+    };
+    // The same for windows that hold few of the lines (what a partner leaves over): the 64 lanes evaluate 64 different
+    // iterations of one logical wave at a time, and the few lines that are kept are handed to the lanes one by one
+    // (two at a time where a line takes 32 lanes) -- a fifth of the instructions of the pass above per draw.
+    auto sparse_pass = [&](u32 li, u64 keep) {
+        for (u32 w = 0; w < LPW; ++w) {
+            const u64 j = (u64)li * LPW + w;
+            if (j >= p.n_waves) break;
+            worked = true;
+            const u64 wave_seed = mix64(p.draw_seed + (j + 1) * kGamma);
+            for (u32 it0 = 0; it0 < p.iters; it0 += 64) {
+                const u32 it = it0 + lane;
+                const u32 line = reduce_to_line(mix64(wave_seed + ((u64)it + 1) * kGamma), p.red);
+                unsigned long long m = __ballot(it < p.iters && ((keep >> (line >> p.window_shift)) & 1ull));
+                while (m) {
+                    const u32 b0 = (u32)__builtin_ctzll(m);
+                    m &= m - 1;
+                    u32 b1 = b0;
+                    bool two = false;
+                    if (LANES == 32 && m) {
+                        b1 = (u32)__builtin_ctzll(m);
+                        m &= m - 1;
+                        two = true;
+                    }
+                    const u32 l0 = __builtin_amdgcn_readlane(line, b0), l1 = __builtin_amdgcn_readlane(line, b1);
+                    if (half == 0 || two) touch(half ? l1 : l0);
+                }
+            }
         }
     };
     if (!p.split_half) {
@@ -91,7 +123,7 @@ __global__ void __launch_bounds__(256) rand_update_kernel(const UpdateParams p) 
     } else {  // own logical waves where this half of the XCDs may write, the partner's where the partner's half may not
         const u32 h = (blockIdx.x / p.split_half) & 1u;
         pass(launch_index, p.split_incl[h]);
-        pass((blockIdx.x ^ p.split_half) * (blockDim.x >> 6) + (threadIdx.x >> 6), ~p.split_incl[h ^ 1u]);
+        sparse_pass((blockIdx.x ^ p.split_half) * (blockDim.x >> 6) + (threadIdx.x >> 6), ~p.split_incl[h ^ 1u]);
     }
     if (!worked) return;
     const u64 total = wave_sum(acc);  // idle lanes hold 0

@@ -179,27 +179,34 @@ def test_zone_direction_does_not_change_the_checksum(whole, R, B, lanes, W, I, z
         assert got.checksum == want
 
 
-def test_zz_updates_over_the_whole_allocation(whole):
-    """Random line writes and atomic adds over all of the allocation (line indices above 2^31): checksum, and the lines a
-    few logical waves drew read back and compared with the oracle's values.  Runs last in this module and restores the
-    fill."""
-    R, B, W, I = whole.numel(), 128, 1024, 4096
+@pytest.mark.parametrize("B,lanes", [(128, 32), (256, 64), (512, 32)])
+def test_zz_updates_over_the_whole_allocation(whole, B, lanes):
+    """Random line writes and atomic adds over all of the allocation (line indices above 2^31 for 128-byte lines; the launch
+    divided between the XCD halves): checksum, and the lines a few logical waves drew read back and compared with the
+    oracle's values.  Runs last in this module and restores the fill."""
+    R, W, I = whole.numel(), 1024, 4096
     idx = orc.indices(R, B, W, I, 11)
-    assert int(idx.max()) > 1 << 31
+    assert B != 128 or int(idx.max()) > 1 << 31
     lines, hits = np.unique(idx, return_counts=True)
     count = dict(zip(lines.tolist(), hits.tolist()))
-    top = int(lines[-1])
+    words = B // 4
+    # lines in the first and the last window of 8 GiB (what changes hands between the halves), and the busiest line
+    first = [int(x) for x in lines[lines < (8 * GiB) // B][:4]]
+    last = [int(x) for x in lines[lines >= (R - 8 * GiB) // B][-4:]]
     try:
         for op in (rl.OP_WRITE, rl.OP_ADD):
-            got = rl.rand_update(whole, B, W * I, I, 11, op, 99)
+            got = rl.rand_update(whole, B, W * I, I, 11, op, 99, lanes_per_line=lanes)
             assert got.checksum == orc.update_checksum(R, B, W, I, 11, 99)
-            for line in list(idx[0, :6]) + list(idx[W - 1, -6:]) + [top, int(lines[np.argmax(hits)])]:
+            for line in list(idx[0, :4]) + list(idx[W - 1, -4:]) + first + last + [int(lines[np.argmax(hits)])]:
                 line = int(line)
                 now = whole[line * B:(line + 1) * B].cpu().numpy().view(np.uint32).astype(np.uint64)
-                old = orc.fill_words(wl.FILL_SEED, line * 32, 32).astype(np.uint64)
-                v = np.array([orc.update_value(99, line * 32 + j) for j in range(32)], dtype=np.uint64)
+                old = orc.fill_words(wl.FILL_SEED, line * words, words).astype(np.uint64)
+                v = np.array([orc.update_value(99, line * words + j) for j in range(words)], dtype=np.uint64)
                 want = v if op == rl.OP_WRITE else (old + count[line] * v) % (1 << 32)
                 assert np.array_equal(now, want), (op, line)
+            untouched = int(np.setdiff1d(np.arange(lines[-1] - 1000, lines[-1]), lines)[0])   # nobody drew it: still the fill
+            now = whole[untouched * B:(untouched + 1) * B].cpu().numpy().view(np.uint32)
+            assert np.array_equal(now, orc.fill_words(wl.FILL_SEED, untouched * words, words))
             rl.fill(whole, wl.FILL_SEED)
     finally:
         rl.fill(whole, wl.FILL_SEED)
